@@ -1,0 +1,289 @@
+"""CPU checker for the target-model verify step of speculative decoding.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+GPU library is compared against.  It is imported by the tests, by the smoke
+check and by the benchmark's CPU-baseline leg; the product never calls it, and
+it shares no code with the GPU kernels.
+
+Everything is evaluated in float64 with NumPy.  Inputs are float arrays (their
+values may lie on the bfloat16 grid); where the step *stores* a tensor in
+bfloat16 (rows appended to the KV cache, the layer's output) the value is
+rounded to that grid, nothing else is rounded.
+
+What the paper fixes (Section 2.1, "Speculative Decoding"):
+  * the target scores the gamma drafted tokens plus one more position in a
+    single parallel forward, position i conditioning on everything before it;
+  * drafted token x_i is accepted with probability min(1, p_i(x_i)/q_i(x_i)),
+    tokens are examined in order and the first rejection ends the iteration;
+  * on rejection a replacement is drawn from norm(max(p_i - q_i, 0));
+  * at temperature 0 a token is accepted iff it equals argmax p_i and a
+    rejected token is replaced by argmax p_i.
+  * Eq. (TVD): TVD(P,Q) = 1/2 sum_x |P(x) - Q(x)|  (Section 6, "Distribution
+    Analysis").
+What it leaves open, and the reading taken here:
+  R1  The verify forward receives the last emitted token followed by the gamma
+      drafts (gamma+1 query positions); the cache holds everything earlier.
+      Query i attends to cache rows [0, kv_len + i] inclusive.
+  R2  When all gamma drafts are accepted one further token is emitted from
+      p_{gamma+1} (arg-max at temperature 0), as in the algorithm of Leviathan
+      et al. that Section 2.1 cites; each step emits n+1 in [1, gamma+1] tokens.
+  R3  One temperature T divides target and draft logits; T = 0 is the greedy
+      branch.  No top-p / top-k truncation in verification.
+  R4  uniforms[b, i] (i < gamma) decides draft i whether or not it is reached;
+      uniforms[b, gamma] drives the one inverse-CDF draw.
+  R5  Accept iff p >= q or u*q < p (no division; u in [0,1)).
+  R6  arg-max ties: lowest index.
+  R7  Inverse CDF: ascending token id, smallest k with cumsum_k > u * total.
+      total == 0 (p == q everywhere): draw from p_i instead.  If rounding lets no
+      k cross, the largest index with positive mass.
+  R8  Layer internals (the paper only says "one forward call"): pre-norm decoder
+      layer, RMSNorm y = x*g/sqrt(mean(x^2)+eps), grouped-query attention with
+      head h reading KV head h // (n_q/n_kv), rotary embedding in the
+      half-split pairing (j, j + d/2) with angle pos * theta^(-2j/d), gated MLP
+      down(act(gate(x)) * up(x)) with act = SiLU or tanh-GELU.
+
+Pins (tests/test_oracle_*.py): brute-force attention loops, closed forms for
+constant keys / values, causality and grouped-head invariants, equivalence of
+the parallel pass with one-query-at-a-time decoding, library special cases for
+norm / activations / matmul, rotary invariants, the temperature-0
+longest-prefix invariant, E[accept] = 1 - TVD, chi-square of emitted tokens
+against the target distribution, inverse-CDF exact histograms.
+The whole layer and lm_head at 7B shapes have no external pin beyond the
+composition of these pinned parts.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+ACT_SILU = 0
+ACT_GELU_TANH = 1
+
+
+# ----------------------------------------------------------------------------
+# storage rounding
+# ----------------------------------------------------------------------------
+def round_bf16(a):
+    """Nearest bfloat16 (ties to even) of each value, returned as float64."""
+    f = np.asarray(a, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(a))
+
+
+def _store(a, dtype):
+    if dtype == "bf16":
+        return round_bf16(a)
+    if dtype == "f32":
+        return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------
+# layer pieces (reading R8)
+# ----------------------------------------------------------------------------
+def rmsnorm(x, g, eps):
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(g, dtype=np.float64)
+
+
+def linear(x, w, b=None):
+    """y = x W^T (+ b);  w is [out, in]."""
+    y = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+    if b is not None:
+        y = y + np.asarray(b, dtype=np.float64)
+    return y
+
+
+def rope(x, pos, theta):
+    """Rotate x[..., d] by angle pos * theta^(-2j/d) in the pairs (j, j+d/2).
+
+    x: [B, Q, heads, d]; pos: [B, Q] integer position ids."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    half = d // 2
+    j = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * j / d)
+    ang = np.asarray(pos, dtype=np.float64)[..., None, None] * inv_freq   # [B,Q,1,half]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def silu(x):
+    x = np.asarray(x, dtype=np.float64)
+    return x / (1.0 + np.exp(-x))
+
+
+def gelu_tanh(x):
+    x = np.asarray(x, dtype=np.float64)
+    return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
+
+
+def gated_mlp(x, wg, wu, wd, act):
+    a = silu if act == ACT_SILU else gelu_tanh
+    return linear(a(linear(x, wg)) * linear(x, wu), wd)
+
+
+def softmax(z, axis=-1):
+    z = np.asarray(z, dtype=np.float64)
+    z = z - np.max(z, axis=axis, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def attention(q, k_cache, v_cache, kv_len, scale=None):
+    """Grouped-query causal attention of the Q new positions (reading R1).
+
+    q: [B, Q, n_q, d]; k_cache, v_cache: [B, n_kv, L_max, d] whose rows
+    [0, kv_len[b] + Q) are valid (the new positions are already appended);
+    kv_len: [B] lengths before the step.  Returns [B, Q, n_q, d] float64.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k_cache = np.asarray(k_cache, dtype=np.float64)
+    v_cache = np.asarray(v_cache, dtype=np.float64)
+    B, Q, n_q, d = q.shape
+    n_kv = k_cache.shape[1]
+    G = n_q // n_kv
+    if scale is None or scale == 0:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros_like(q)
+    for b in range(B):
+        L = int(kv_len[b])
+        for h in range(n_q):
+            g = h // G
+            for i in range(Q):
+                n_vis = L + i + 1
+                s = scale * (k_cache[b, g, :n_vis] @ q[b, i, h])
+                out[b, i, h] = softmax(s) @ v_cache[b, g, :n_vis]
+    return out
+
+
+def verify_layer(shape, w, x, pos, k_cache, v_cache, kv_len):
+    """One decoder layer over the Q new positions of every sequence.
+
+    shape: object with hidden, n_q_heads, n_kv_heads, head_dim, mlp, act,
+    norm_eps, rope_theta, dtype.  w: dict of ln1, wq, wk, wv, bq, bk, bv, wo,
+    ln2, wg, wu, wd.  x: [B, Q, H].  Returns (x_out, k_cache, v_cache) with the
+    new rows written at [kv_len[b], kv_len[b] + Q) on the storage grid."""
+    x = np.asarray(x, dtype=np.float64)
+    B, Q, H = x.shape
+    nq, nkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    k_cache = np.array(k_cache, dtype=np.float64)
+    v_cache = np.array(v_cache, dtype=np.float64)
+
+    xn = rmsnorm(x, w["ln1"], shape.norm_eps)
+    q = linear(xn, w["wq"], w.get("bq")).reshape(B, Q, nq, d)
+    k = linear(xn, w["wk"], w.get("bk")).reshape(B, Q, nkv, d)
+    v = linear(xn, w["wv"], w.get("bv")).reshape(B, Q, nkv, d)
+    q = rope(q, pos, shape.rope_theta)
+    k = rope(k, pos, shape.rope_theta)
+    for b in range(B):
+        L = int(kv_len[b])
+        k_cache[b, :, L:L + Q] = _store(k[b].transpose(1, 0, 2), shape.dtype)
+        v_cache[b, :, L:L + Q] = _store(v[b].transpose(1, 0, 2), shape.dtype)
+    o = attention(q, k_cache, v_cache, kv_len)
+    h = x + linear(o.reshape(B, Q, nq * d), w["wo"])
+    hn = rmsnorm(h, w["ln2"], shape.norm_eps)
+    y = h + gated_mlp(hn, w["wg"], w["wu"], w["wd"], shape.act)
+    return _store(y, shape.dtype), k_cache, v_cache
+
+
+def lm_head_logits(x, final_norm, w_lm, eps):
+    """logits = RMSNorm(x) W_lm^T (no norm when final_norm is None); x: [M, H]."""
+    xn = np.asarray(x, dtype=np.float64) if final_norm is None else rmsnorm(x, final_norm, eps)
+    return linear(xn, w_lm)
+
+
+# ----------------------------------------------------------------------------
+# acceptance (Section 2.1)
+# ----------------------------------------------------------------------------
+def first_argmax(row):
+    return int(np.argmax(np.asarray(row)))       # np.argmax returns the first maximum (R6)
+
+
+def inverse_cdf(r, u):
+    """Smallest k with sum_{x<=k} r_x > u * sum_x r_x (R7); also the relative
+    distance of u*total from the two cumulative values that bracket it."""
+    r = np.asarray(r, dtype=np.float64)
+    c = np.cumsum(r)
+    total = c[-1]
+    thr = float(u) * total
+    hit = np.nonzero(c > thr)[0]
+    if hit.size:
+        k = int(hit[0])
+    else:
+        k = int(np.nonzero(r > 0)[0][-1])
+    below = c[k - 1] if k > 0 else 0.0
+    margin = min(abs(c[k] - thr), abs(thr - below) if k > 0 else np.inf) / total
+    return k, float(margin)
+
+
+def tvd(p, q):
+    """Eq. (TVD): half the L1 distance between two distributions."""
+    return 0.5 * float(np.sum(np.abs(np.asarray(p, dtype=np.float64) - np.asarray(q, dtype=np.float64))))
+
+
+def residual(p, q):
+    """max(p - q, 0) without normalisation; p itself when that is identically 0 (R7)."""
+    r = np.maximum(np.asarray(p, dtype=np.float64) - np.asarray(q, dtype=np.float64), 0.0)
+    return r if r.sum() > 0.0 else np.asarray(p, dtype=np.float64)
+
+
+def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature,
+                return_final_mass=False):
+    """Sequential accept / reject / resample for every sequence of the batch.
+
+    target_logits [B, gamma+1, V], draft_logits [B, gamma, V] (ignored at T=0),
+    draft_tokens [B, gamma], uniforms [B, gamma+1] (ignored at T=0).
+    Returns n_accepted [B] int32, out_tokens [B, gamma+1] int32 (accepted
+    drafts, the final token, then -1), and margin [B, 2]: the smallest relative
+    distance from flipping of (0) any evaluated accept comparison with p < q,
+    |u - p/q| / max(u, p/q), and (1) the inverse-CDF draw, as a fraction of the
+    total mass (both inf at T=0).  With return_final_mass the unnormalised mass
+    vector the final token was drawn from is returned per sequence as well.
+    """
+    t = np.asarray(target_logits, dtype=np.float64)
+    B, Q, V = t.shape
+    gamma = Q - 1
+    x = np.asarray(draft_tokens).reshape(B, gamma)
+    n_acc = np.zeros(B, dtype=np.int32)
+    out = np.full((B, Q), -1, dtype=np.int32)
+    margin = np.full((B, 2), np.inf)
+    masses = []
+    greedy = (temperature == 0)
+    if not greedy:
+        dl = np.asarray(draft_logits, dtype=np.float64)
+        u = np.asarray(uniforms, dtype=np.float64).reshape(B, Q)
+    for b in range(B):
+        n = 0
+        for i in range(gamma):
+            tok = int(x[b, i])
+            if greedy:
+                ok = (tok == first_argmax(t[b, i]))
+            else:
+                p = softmax(t[b, i] / temperature)[tok]
+                q = softmax(dl[b, i] / temperature)[tok]
+                ok = (p >= q) or (u[b, i] * q < p)
+                if p < q:
+                    ratio = p / q
+                    margin[b, 0] = min(margin[b, 0], abs(u[b, i] - ratio) / max(u[b, i], ratio))
+            if not ok:
+                break
+            out[b, n] = tok
+            n += 1
+        if greedy:
+            final = first_argmax(t[b, n])
+        else:
+            p = softmax(t[b, n] / temperature)
+            r = residual(p, softmax(dl[b, n] / temperature)) if n < gamma else p
+            final, margin[b, 1] = inverse_cdf(r, u[b, gamma])
+            if return_final_mass:
+                masses.append(r)
+        out[b, n] = final
+        n_acc[b] = n
+    if return_final_mass:
+        return n_acc, out, margin, masses
+    return n_acc, out, margin
