@@ -1,0 +1,215 @@
+/*
+ * massv_verify.h -- C ABI of the target-model verify step of speculative decoding
+ * for AMD MI355X (gfx950).
+ *
+ * One iteration of speculative decoding (MASSV paper, Section 2.1): a drafter
+ * proposes gamma tokens; the target model scores those gamma tokens plus one
+ * further position in ONE parallel forward pass; the drafts are then examined
+ * in order, each accepted with probability min(1, p/q), the first rejection is
+ * replaced by a draw from norm(max(p - q, 0)) and ends the iteration; at
+ * temperature 0 a draft is accepted iff it equals argmax p and a rejected one
+ * is replaced by argmax p.  This library is the target's half of that
+ * iteration: the parallel forward (decoder layers, vocabulary projection) and
+ * the accept / resample rule.
+ *
+ * Conventions common to every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or synchronises; a call only enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream).  Scratch space is the caller's `workspace`, whose minimum size
+ *     the matching *_workspace() function returns; it need not be zeroed and
+ *     holds nothing between calls.  Descriptor structs are HOST pointers and
+ *     are read before the call returns.
+ *   - Return value: MASSV_OK or a negative massv_status.  Arguments are
+ *     validated on the host before anything is enqueued; on MASSV_EINVAL,
+ *     MASSV_EUNSUPPORTED and MASSV_EWORKSPACE nothing has been launched.
+ *     Values held in device memory (kv_len, tokens) cannot be checked without
+ *     a synchronisation; kernels clamp them so that no access leaves the
+ *     buffers described by the descriptor, but results are then unspecified.
+ *   - Calls are stateless; the same inputs give bit-identical outputs (no
+ *     floating-point atomics, reductions in a fixed order).
+ *   - Notation: B batch, gamma speculation length, Q = gamma+1 query positions,
+ *     M = B*Q rows, H hidden, n_q / n_kv query / KV heads, G = n_q/n_kv,
+ *     d head_dim, F MLP width, V vocabulary, L_b = kv_len[b] = cached length of
+ *     sequence b BEFORE the step, L_max = rows allocated per sequence.
+ *
+ * KV cache layout (dtype = f32 or bf16 elements)
+ *   k_cache [B][n_kv][L_max][d]            row j of (b, g) at ((b*n_kv+g)*L_max + j)*d
+ *   v_cache [B][n_kv][L_max/32][d][32]     element (j, c) of (b, g) at
+ *                                          (((b*n_kv+g)*(L_max/32) + j/32)*d + c)*32 + j%32
+ *   L_max must be a multiple of 32.  Values are stored key-minor in blocks of
+ *   32 keys so that the probability-times-value product reads them in matrix
+ *   operand order with 16-byte loads.  massv_v_cache_pack() converts a
+ *   row-major [B][n_kv][L_max][d] tensor into this layout.
+ *   The leading rows of a sequence's cache are its image-token positions
+ *   followed by text positions (Section 2.2); the kernels treat both alike.
+ */
+#ifndef MASSV_VERIFY_H
+#define MASSV_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MASSV_OK = 0,
+    MASSV_EINVAL = -1,        /* NULL pointer, non-positive size, n_q % n_kv != 0, T < 0 or NaN ... */
+    MASSV_EUNSUPPORTED = -2,  /* valid but outside what the kernels are built for */
+    MASSV_EWORKSPACE = -3,    /* workspace NULL or smaller than *_workspace() says */
+    MASSV_ELAUNCH = -4        /* the HIP runtime refused a launch */
+} massv_status;
+
+typedef enum { MASSV_F32 = 0, MASSV_BF16 = 1 } massv_dtype;
+typedef enum { MASSV_ACT_SILU = 0, MASSV_ACT_GELU_TANH = 1 } massv_act;
+
+#define MASSV_V_BLOCK 32          /* keys per block of the value cache */
+#define MASSV_MAX_ROWS 64         /* largest M = B*Q (and G*Q) the bf16 kernels take */
+
+/* Text for a status code; never NULL.  Host pointer to static storage. */
+const char* massv_status_string(int status);
+/* ABI version, bumped when a signature or layout changes. */
+int massv_abi_version(void);
+
+/* ------------------------------------------------------------------------- */
+/* verify_attention: grouped-query causal attention of the Q new positions.   */
+/* Section 2.1: position i of the parallel forward conditions on all earlier  */
+/* positions, so query i (0-based) attends to cache rows [0, L_b + i], the    */
+/* new positions' own keys included (they must already be in the cache at     */
+/* rows L_b .. L_b+Q-1).  Query head h reads KV head h / G.                   */
+/*   out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:].k[b,h/G,j,:]) v[b,h/G,j,:] */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t batch;            /* B >= 1 */
+    int32_t n_query;          /* Q = gamma+1 >= 1 */
+    int32_t n_q_heads;
+    int32_t n_kv_heads;       /* divides n_q_heads */
+    int32_t head_dim;         /* f32: multiple of 2, <= 256; bf16: 64, 128 or 256 */
+    int32_t l_max;            /* rows allocated per (b, kv head); multiple of 32 */
+    float   scale;            /* 0 => 1/sqrt(head_dim) */
+    int32_t dtype;            /* massv_dtype of q, caches and out */
+} massv_attn_desc;
+
+/* Bytes of workspace massv_verify_attention needs for this descriptor (0 if the
+ * descriptor is invalid). */
+size_t massv_verify_attention_workspace(const massv_attn_desc* desc);
+
+/* q   [B][Q][n_q][d]  (dtype)   in
+ * k_cache, v_cache    (dtype)   in, layouts above; rows [0, kv_len[b]+Q) valid
+ * kv_len [B] int32              in, 0 <= kv_len[b], kv_len[b]+Q <= l_max (caller's duty)
+ * out [B][Q][n_q][d]  (dtype)   out
+ * bf16 path requires G*Q <= MASSV_MAX_ROWS, else MASSV_EUNSUPPORTED. */
+int massv_verify_attention(const massv_attn_desc* desc, const void* q,
+                           const void* k_cache, const void* v_cache,
+                           const int32_t* kv_len, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Row-major [B][n_kv][L_max][d] values -> blocked value-cache layout. src and
+ * dst must not overlap. */
+int massv_v_cache_pack(const void* src_row_major, void* dst_blocked,
+                       int32_t batch, int32_t n_kv_heads, int32_t l_max, int32_t head_dim,
+                       int32_t dtype, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* verify_layer: one pre-norm decoder layer of the parallel forward over the  */
+/* M = B*Q new positions ("one forward call" of Section 2.1; the paper does    */
+/* not spell the layer out -- this is the usual gated-MLP transformer block):  */
+/*   xn = rmsnorm(x, ln1);  q,k,v = xn Wq^T+bq, xn Wk^T+bk, xn Wv^T+bv         */
+/*   q,k = rope(q,k; pos);  cache rows L_b+i <- k,v;  a = attention(q, cache)  */
+/*   h = x + a Wo^T;  hn = rmsnorm(h, ln2)                                     */
+/*   x <- h + (act(hn Wg^T) * (hn Wu^T)) Wd^T                                  */
+/* rmsnorm(x,g) = x * g / sqrt(mean(x^2) + eps).  rope rotates the pairs       */
+/* (j, j + d/2) of every head by angle pos * theta^(-2j/d).                    */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    massv_attn_desc attn;     /* batch, n_query, heads, head_dim, l_max, scale, dtype */
+    int32_t hidden;           /* H */
+    int32_t mlp;              /* F */
+    int32_t act;              /* massv_act */
+    int32_t qkv_bias;         /* 0: bq,bk,bv ignored (may be NULL) */
+    float   norm_eps;
+    float   rope_theta;
+} massv_layer_desc;
+
+/* All weights are DEVICE pointers of the layer's dtype, row-major [out][in]. */
+typedef struct {
+    const void* ln1;          /* [H] */
+    const void* wq;           /* [n_q*d][H] */
+    const void* wk;           /* [n_kv*d][H] */
+    const void* wv;           /* [n_kv*d][H] */
+    const void* bq;           /* [n_q*d] or NULL */
+    const void* bk;           /* [n_kv*d] or NULL */
+    const void* bv;           /* [n_kv*d] or NULL */
+    const void* wo;           /* [H][n_q*d] */
+    const void* ln2;          /* [H] */
+    const void* wg;           /* [F][H] */
+    const void* wu;           /* [F][H] */
+    const void* wd;           /* [H][F] */
+} massv_layer_weights;
+
+size_t massv_verify_layer_workspace(const massv_layer_desc* desc);
+
+/* x   [B][Q][H] (dtype)  in/out: the residual stream, updated in place
+ * pos [B][Q] int32       in: rotary position id of each new token (need not
+ *                        equal its cache row: image prefixes may be numbered
+ *                        differently from the rows they occupy)
+ * k_cache, v_cache       in/out: rows kv_len[b]+i (i < Q) are written, then
+ *                        rows [0, kv_len[b]+Q) are read
+ * kv_len [B] int32       in
+ * bf16 path requires M <= MASSV_MAX_ROWS, H, F, n_q*d multiples of 32 and
+ * every projection's output size a multiple of 16. */
+int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* weights,
+                       void* x, const int32_t* pos, void* k_cache, void* v_cache,
+                       const int32_t* kv_len,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* lm_head_logits: logits[m, v] = sum_k rmsnorm(x, final_norm)[m, k] * w_lm[v, k] */
+/* (no norm when final_norm == NULL).  Row i of sequence b gives the scores   */
+/* from which p_{i+1}( . | ...) of Section 2.1 is formed.                      */
+/* ------------------------------------------------------------------------- */
+size_t massv_lm_head_logits_workspace(int32_t M, int32_t H, int32_t V, int32_t dtype);
+
+/* x [M][H] (dtype) in; final_norm [H] (dtype) or NULL; w_lm [V][H] (dtype) in;
+ * logits [M][V] float32 out.  bf16 path: M <= MASSV_MAX_ROWS, H % 32 == 0, V % 16 == 0. */
+int massv_lm_head_logits(const void* x, const void* final_norm, const void* w_lm,
+                         float* logits, int32_t M, int32_t H, int32_t V,
+                         float norm_eps, int32_t dtype,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* spec_accept: the sequential accept / reject / resample rule of Section 2.1  */
+/* for every sequence of the batch.                                           */
+/*   T > 0: p_i = softmax(target_logits[b,i]/T), q_i = softmax(draft_logits[b,i]/T); */
+/*          draft x_i (i = 0..gamma-1, examined in order) is accepted iff      */
+/*          p_i(x_i) >= q_i(x_i) or uniforms[b,i] * q_i(x_i) < p_i(x_i);        */
+/*          at the first rejection (index n) the final token is the smallest k */
+/*          with sum_{x<=k} r_x > uniforms[b,gamma] * sum_x r_x,                */
+/*          r = max(p_n - q_n, 0) (r = p_n if that is identically zero);        */
+/*          if all gamma are accepted (n = gamma) the same draw with r = p_gamma. */
+/*   T = 0: x_i accepted iff x_i == argmax target_logits[b,i] (lowest index on */
+/*          ties); final token = argmax target_logits[b,n].                    */
+/* After the call the caller keeps kv_len[b] + n_accepted[b] + 1 cache rows.   */
+/* ------------------------------------------------------------------------- */
+size_t massv_spec_accept_workspace(int32_t B, int32_t gamma, int32_t V);
+
+/* target_logits [B][gamma+1][V] float32 in
+ * draft_logits  [B][gamma][V]   float32 in; may be NULL iff temperature == 0
+ * draft_tokens  [B][gamma]      int32   in; values outside [0,V) are rejected
+ * uniforms      [B][gamma+1]    float32 in, in [0,1); may be NULL iff temperature == 0
+ * n_accepted    [B]             int32   out, 0..gamma
+ * out_tokens    [B][gamma+1]    int32   out: the accepted drafts, the final
+ *                                       token, then -1 padding
+ * Logits must not contain NaN or +inf (-inf is a zero-probability token). */
+int massv_spec_accept(const float* target_logits, const float* draft_logits,
+                      const int32_t* draft_tokens, const float* uniforms,
+                      float temperature, int32_t B, int32_t gamma, int32_t V,
+                      int32_t* n_accepted, int32_t* out_tokens,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MASSV_VERIFY_H */

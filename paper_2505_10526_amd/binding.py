@@ -1,0 +1,287 @@
+"""ctypes binding of libmassv_verify.so (see include/massv_verify.h).
+
+Argument marshalling only: tensors are torch CUDA tensors whose device
+pointers are handed to the C ABI; every step of the verify path runs in the
+library's HIP kernels.  There is no CPU or PyTorch fallback: if the shared
+library is missing, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmassv_verify.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
+F32, BF16 = 0, 1
+ACT_SILU, ACT_GELU_TANH = 0, 1
+V_BLOCK = 32
+MAX_ROWS = 64
+
+EXPORTS = [
+    "massv_status_string", "massv_abi_version",
+    "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack",
+    "massv_verify_layer_workspace", "massv_verify_layer",
+    "massv_lm_head_logits_workspace", "massv_lm_head_logits",
+    "massv_spec_accept_workspace", "massv_spec_accept",
+]
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_query", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("l_max", C.c_int32),
+                ("scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("attn", AttnDesc), ("hidden", C.c_int32), ("mlp", C.c_int32), ("act", C.c_int32),
+                ("qkv_bias", C.c_int32), ("norm_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+WEIGHT_FIELDS = ["ln1", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ln2", "wg", "wu", "wd"]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class MassvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load():
+    """Load the shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_10526_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+    lib.massv_status_string.restype = C.c_char_p
+    lib.massv_status_string.argtypes = [C.c_int]
+    lib.massv_abi_version.restype = C.c_int
+    lib.massv_abi_version.argtypes = []
+    lib.massv_verify_attention_workspace.restype = sz
+    lib.massv_verify_attention_workspace.argtypes = [C.POINTER(AttnDesc)]
+    lib.massv_verify_attention.restype = C.c_int
+    lib.massv_verify_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.massv_v_cache_pack.restype = C.c_int
+    lib.massv_v_cache_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.massv_verify_layer_workspace.restype = sz
+    lib.massv_verify_layer_workspace.argtypes = [C.POINTER(LayerDesc)]
+    lib.massv_verify_layer.restype = C.c_int
+    lib.massv_verify_layer.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), vp, vp, vp, vp, vp,
+                                       vp, sz, vp]
+    lib.massv_lm_head_logits_workspace.restype = sz
+    lib.massv_lm_head_logits_workspace.argtypes = [i32, i32, i32, i32]
+    lib.massv_lm_head_logits.restype = C.c_int
+    lib.massv_lm_head_logits.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, sz, vp]
+    lib.massv_spec_accept_workspace.restype = sz
+    lib.massv_spec_accept_workspace.argtypes = [i32, i32, i32]
+    lib.massv_spec_accept.restype = C.c_int
+    lib.massv_spec_accept.argtypes = [vp, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().massv_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise MassvError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+_workspaces: dict = {}
+
+
+def workspace(nbytes: int, device) -> torch.Tensor:
+    """A reusable scratch buffer of at least nbytes on `device`."""
+    key = (torch.device(device).index or 0)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(int(nbytes), 1 << 20), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def _need(t, name, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+
+
+# ---------------------------------------------------------------------------
+# verify_attention
+# ---------------------------------------------------------------------------
+def attn_desc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, dtype, scale=0.0) -> AttnDesc:
+    return AttnDesc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, scale, dtype)
+
+
+def v_cache_pack(v_row_major: torch.Tensor) -> torch.Tensor:
+    """[B, n_kv, L_max, d] row-major values -> the library's blocked value-cache
+    layout [B, n_kv, L_max/32, d, 32] (done by the library's own kernel)."""
+    _need(v_row_major, "v")
+    B, n_kv, L, d = v_row_major.shape
+    out = torch.empty((B, n_kv, L // V_BLOCK, d, V_BLOCK), dtype=v_row_major.dtype, device=v_row_major.device)
+    _check(load().massv_v_cache_pack(_ptr(v_row_major), _ptr(out), B, n_kv, L, d,
+                                     dtype_code(v_row_major), _stream()), "massv_v_cache_pack")
+    return out
+
+
+def verify_attention(q, k_cache, v_cache, kv_len, scale=0.0, out=None, ws=None):
+    """q [B,Q,n_q,d]; k_cache [B,n_kv,L_max,d]; v_cache blocked [B,n_kv,L_max/32,d,32];
+    kv_len int32 [B].  Returns out [B,Q,n_q,d]."""
+    lib = load()
+    for t, n in ((q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _need(t, n, q.dtype)
+    _need(kv_len, "kv_len", torch.int32)
+    B, Q, n_q, d = q.shape
+    n_kv, l_max = k_cache.shape[1], k_cache.shape[2]
+    desc = attn_desc(B, Q, n_q, n_kv, d, l_max, dtype_code(q), scale)
+    if out is None:
+        out = torch.empty_like(q)
+    need = lib.massv_verify_attention_workspace(C.byref(desc))
+    if ws is None:
+        ws = workspace(need, q.device)
+    _check(lib.massv_verify_attention(C.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
+                                      _ptr(out), _ptr(ws), ws.numel(), _stream()), "massv_verify_attention")
+    return out
+
+
+# ---------------------------------------------------------------------------
+# verify_layer / lm_head_logits
+# ---------------------------------------------------------------------------
+@dataclass
+class LayerConfig:
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    mlp: int
+    act: int = ACT_SILU
+    qkv_bias: bool = True
+    norm_eps: float = 1e-6
+    rope_theta: float = 1e6
+    scale: float = 0.0
+
+
+def layer_desc(cfg: LayerConfig, batch, n_query, l_max, dtype) -> LayerDesc:
+    a = attn_desc(batch, n_query, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, l_max, dtype, cfg.scale)
+    return LayerDesc(a, cfg.hidden, cfg.mlp, cfg.act, int(bool(cfg.qkv_bias)), cfg.norm_eps, cfg.rope_theta)
+
+
+def layer_weights(w: dict) -> LayerWeights:
+    """dict of CUDA tensors (keys ln1, wq, ... wd; biases may be None) -> struct of device pointers.
+    The caller keeps the tensors alive."""
+    lw = LayerWeights()
+    for name in WEIGHT_FIELDS:
+        t = w.get(name)
+        if t is not None:
+            _need(t, name)
+        setattr(lw, name, None if t is None else t.data_ptr())
+    return lw
+
+
+def verify_layer_workspace(desc: LayerDesc) -> int:
+    return load().massv_verify_layer_workspace(C.byref(desc))
+
+
+def verify_layer(cfg: LayerConfig, w, x, pos, k_cache, v_cache, kv_len, ws=None, desc=None, lw=None):
+    """One decoder layer over the new positions; x [B,Q,H] is updated in place
+    and the caches receive the new rows.  `w` is a dict of tensors or a prebuilt
+    LayerWeights."""
+    lib = load()
+    _need(x, "x")
+    _need(pos, "pos", torch.int32)
+    _need(kv_len, "kv_len", torch.int32)
+    _need(k_cache, "k_cache", x.dtype)
+    _need(v_cache, "v_cache", x.dtype)
+    B, Q, _ = x.shape
+    if desc is None:
+        desc = layer_desc(cfg, B, Q, k_cache.shape[2], dtype_code(x))
+    if lw is None:
+        lw = w if isinstance(w, LayerWeights) else layer_weights(w)
+    if ws is None:
+        ws = workspace(lib.massv_verify_layer_workspace(C.byref(desc)), x.device)
+    _check(lib.massv_verify_layer(C.byref(desc), C.byref(lw), _ptr(x), _ptr(pos), _ptr(k_cache), _ptr(v_cache),
+                                  _ptr(kv_len), _ptr(ws), ws.numel(), _stream()), "massv_verify_layer")
+    return x
+
+
+def lm_head_logits(x, final_norm, w_lm, norm_eps=1e-6, out=None, ws=None):
+    """x [M,H] (or [B,Q,H]); w_lm [V,H]; returns float32 logits [M,V]."""
+    lib = load()
+    _need(x, "x")
+    _need(w_lm, "w_lm", x.dtype)
+    H = x.shape[-1]
+    M = x.numel() // H
+    V = w_lm.shape[0]
+    if out is None:
+        out = torch.empty((M, V), dtype=torch.float32, device=x.device)
+    need = lib.massv_lm_head_logits_workspace(M, H, V, dtype_code(x))
+    if ws is None:
+        ws = workspace(need, x.device)
+    _check(lib.massv_lm_head_logits(_ptr(x), _ptr(final_norm), _ptr(w_lm), _ptr(out), M, H, V,
+                                    float(norm_eps), dtype_code(x), _ptr(ws), ws.numel(), _stream()),
+           "massv_lm_head_logits")
+    return out
+
+
+# ---------------------------------------------------------------------------
+# spec_accept
+# ---------------------------------------------------------------------------
+def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature,
+                n_accepted=None, out_tokens=None, ws=None):
+    """target_logits [B,gamma+1,V] f32, draft_logits [B,gamma,V] f32 (None at T=0),
+    draft_tokens [B,gamma] i32, uniforms [B,gamma+1] f32 (None at T=0).
+    Returns (n_accepted [B] i32, out_tokens [B,gamma+1] i32)."""
+    lib = load()
+    _need(target_logits, "target_logits", torch.float32)
+    _need(draft_tokens, "draft_tokens", torch.int32)
+    if draft_logits is not None:
+        _need(draft_logits, "draft_logits", torch.float32)
+    if uniforms is not None:
+        _need(uniforms, "uniforms", torch.float32)
+    B, Q, V = target_logits.shape
+    gamma = Q - 1
+    dev = target_logits.device
+    if n_accepted is None:
+        n_accepted = torch.empty((B,), dtype=torch.int32, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, Q), dtype=torch.int32, device=dev)
+    need = lib.massv_spec_accept_workspace(B, gamma, V)
+    if ws is None:
+        ws = workspace(need, dev)
+    _check(lib.massv_spec_accept(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(uniforms),
+                                 float(temperature), B, gamma, V, _ptr(n_accepted), _ptr(out_tokens),
+                                 _ptr(ws), ws.numel(), _stream()), "massv_spec_accept")
+    return n_accepted, out_tokens

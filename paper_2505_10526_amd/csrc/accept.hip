@@ -1,0 +1,349 @@
+// spec_accept: vocabulary-wide softmax statistics and the sequential
+// accept / reject / resample rule of speculative decoding (paper Section 2.1).
+//
+// The work is a stream over the logits, bound by HBM bandwidth:
+//   pass 1  accept_stats   every target row (and, at T > 0, every draft row) is
+//                          cut into chunks of 4096 logits; one workgroup per
+//                          (row, chunk) produces {max, first arg-max, sum exp}.
+//           accept_decide  one wave per sequence merges the chunk partials in
+//                          chunk order, gathers the logits of the drafted
+//                          tokens and walks the accept chain.
+//   pass 2  residual_mass  (T > 0) re-reads the ONE target/draft row pair per
+//                          sequence the final token is drawn from and sums
+//                          max(p - q, 0) and p per chunk,
+//           residual_pick  finds the chunk, then the token, where the running
+//                          sum first exceeds uniform * total.
+// Sums that decide a token are carried in double so that the result does not
+// depend on how the vocabulary was cut into chunks.
+#include "common.h"
+
+#include <limits.h>
+
+namespace massv {
+
+constexpr int kAccThreads = 256;
+constexpr int kAccPerThread = 16;
+constexpr int kAccChunk = kAccThreads * kAccPerThread;   // 4096 logits
+constexpr int kMaxGamma = 15;
+
+struct RowPartial { float m; int arg; double s; };
+struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d; };
+struct ChunkMass { double r, p; };
+
+struct TempScale { float hi, lo; double inv; };   // 1/T split so that d*hi + d*lo is d/T to ~1 ulp
+
+// d is a logit minus the row maximum (<= 0, possibly -inf for padding or a
+// zero-probability token); clamping to the largest finite value keeps
+// (-inf) * lo from producing NaN, the result still underflows exp to 0.
+__device__ inline float scaled(float d, TempScale ts) {
+    d = fmaxf(d, -3.0e38f);
+    return fmaf(d, ts.lo, d * ts.hi);
+}
+
+// Interleaved, coalesced read of one chunk: x[j*4+e] is element
+// base + (j*256 + tid)*4 + e; out-of-range elements read as -inf.
+__device__ inline void load_chunk_interleaved(const float* __restrict__ row, int V, int base,
+                                              int tid, int vec, float (&x)[kAccPerThread]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int idx = base + (j * kAccThreads + tid) * 4;
+        if (vec && idx + 3 < V) {
+            float4 v = *reinterpret_cast<const float4*>(row + idx);
+            x[j * 4 + 0] = v.x; x[j * 4 + 1] = v.y; x[j * 4 + 2] = v.z; x[j * 4 + 3] = v.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[j * 4 + e] = (idx + e < V) ? row[idx + e] : -INFINITY;
+        }
+    }
+}
+
+__device__ inline int interleaved_index(int base, int tid, int k) {
+    return base + ((k >> 2) * kAccThreads + tid) * 4 + (k & 3);
+}
+
+// (value, index) ordering: larger value first, then smaller index.
+__device__ inline void argmax_merge(float& v, int& i, float ov, int oi) {
+    if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+}
+
+__global__ __launch_bounds__(kAccThreads)
+void accept_stats_kernel(const float* __restrict__ target, const float* __restrict__ draft,
+                         int n_target_rows, int V, int C, TempScale ts, int greedy, int vec,
+                         RowPartial* __restrict__ part) {
+    const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+    const float* row = (r < n_target_rows) ? target + (size_t)r * V
+                                           : draft + (size_t)(r - n_target_rows) * V;
+    const int base = c * kAccChunk;
+    float x[kAccPerThread];
+    load_chunk_interleaved(row, V, base, tid, vec, x);
+
+    float m = x[0];
+    int am = interleaved_index(base, tid, 0);
+#pragma unroll
+    for (int k = 1; k < kAccPerThread; ++k)
+        if (x[k] > m) { m = x[k]; am = interleaved_index(base, tid, k); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(m, o, kWave);
+        int oi = __shfl_xor(am, o, kWave);
+        argmax_merge(m, am, ov, oi);
+    }
+    __shared__ float sm[kAccThreads / kWave];
+    __shared__ int sa[kAccThreads / kWave];
+    __shared__ double ss[kAccThreads / kWave];
+    const int w = tid / kWave;
+    if ((tid & (kWave - 1)) == 0) { sm[w] = m; sa[w] = am; }
+    __syncthreads();
+    m = sm[0]; am = sa[0];
+#pragma unroll
+    for (int i = 1; i < kAccThreads / kWave; ++i) argmax_merge(m, am, sm[i], sa[i]);
+
+    double s = 0.0;
+    if (!greedy) {
+        float acc = 0.f;
+        if (m > -INFINITY) {
+#pragma unroll
+            for (int k = 0; k < kAccPerThread; ++k) acc += expf(scaled(x[k] - m, ts));
+        }
+        s = wave_sum((double)acc);
+        if ((tid & (kWave - 1)) == 0) ss[w] = s;
+        __syncthreads();
+        s = ss[0];
+#pragma unroll
+        for (int i = 1; i < kAccThreads / kWave; ++i) s += ss[i];
+    }
+    if (tid == 0) {
+        RowPartial p; p.m = m; p.arg = am; p.s = s;
+        part[(size_t)r * C + c] = p;
+    }
+}
+
+__global__ __launch_bounds__(kWave)
+void accept_decide_kernel(const float* __restrict__ target, const float* __restrict__ draft,
+                          const int* __restrict__ tokens, const float* __restrict__ uniforms,
+                          int B, int gamma, int V, int C, double inv_t, int greedy,
+                          const RowPartial* __restrict__ part, SeqSel* __restrict__ sel,
+                          int* __restrict__ n_accepted, int* __restrict__ out_tokens) {
+    const int b = blockIdx.x, t = threadIdx.x, Q = gamma + 1;
+    __shared__ double row_m[2 * kMaxGamma + 1], row_s[2 * kMaxGamma + 1];
+    __shared__ int row_arg[2 * kMaxGamma + 1];
+    const int nrows = greedy ? Q : Q + gamma;
+    if (t < nrows) {
+        const int r = (t < Q) ? b * Q + t : B * Q + b * gamma + (t - Q);
+        const RowPartial* p = part + (size_t)r * C;
+        float m = p[0].m; int am = p[0].arg;
+        for (int c = 1; c < C; ++c) if (p[c].m > m) { m = p[c].m; am = p[c].arg; }   // ascending chunks: first index wins
+        double s = 0.0;
+        if (!greedy)
+            for (int c = 0; c < C; ++c)
+                if (p[c].m > -INFINITY) s += p[c].s * exp(((double)p[c].m - (double)m) * inv_t);
+        row_m[t] = (double)m; row_s[t] = s; row_arg[t] = am;
+    }
+    __syncthreads();
+    if (t != 0) return;
+
+    int n = 0;
+    for (; n < gamma; ++n) {
+        const int tok = tokens[b * gamma + n];
+        if (tok < 0 || tok >= V) break;
+        bool ok;
+        if (greedy) {
+            ok = (tok == row_arg[n]);
+        } else {
+            const double lt = (double)target[((size_t)b * Q + n) * V + tok];
+            const double ld = (double)draft[((size_t)b * gamma + n) * V + tok];
+            const double p = exp((lt - row_m[n]) * inv_t) / row_s[n];
+            const double q = exp((ld - row_m[Q + n]) * inv_t) / row_s[Q + n];
+            const double u = (double)uniforms[b * Q + n];
+            ok = (p >= q) || (u * q < p);
+        }
+        if (!ok) break;
+        out_tokens[b * Q + n] = tok;
+    }
+    n_accepted[b] = n;
+    for (int i = n + 1; i < Q; ++i) out_tokens[b * Q + i] = -1;
+    if (greedy) {
+        out_tokens[b * Q + n] = row_arg[n];
+    } else {
+        SeqSel s;
+        s.n = n; s.bonus = (n == gamma); s.pad0 = s.pad1 = 0;
+        s.m_t = row_m[n]; s.s_t = row_s[n];
+        s.m_d = s.bonus ? 0.0 : row_m[Q + n];
+        s.s_d = s.bonus ? 1.0 : row_s[Q + n];
+        sel[b] = s;
+    }
+}
+
+// Unnormalised-to-normalised probability of one logit in double.
+__device__ inline double prob_of(float logit, double m, double inv_s, TempScale ts) {
+    return (double)expf(scaled(logit - (float)m, ts)) * inv_s;
+}
+
+__global__ __launch_bounds__(kAccThreads)
+void residual_mass_kernel(const float* __restrict__ target, const float* __restrict__ draft,
+                          int gamma, int V, int C, TempScale ts, int vec,
+                          const SeqSel* __restrict__ sel, ChunkMass* __restrict__ mass) {
+    const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, Q = gamma + 1;
+    const SeqSel s = sel[b];
+    const int base = c * kAccChunk;
+    float xt[kAccPerThread], xd[kAccPerThread];
+    load_chunk_interleaved(target + ((size_t)b * Q + s.n) * V, V, base, tid, vec, xt);
+    if (!s.bonus) load_chunk_interleaved(draft + ((size_t)b * gamma + s.n) * V, V, base, tid, vec, xd);
+    const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
+    double sr = 0.0, sp = 0.0;
+#pragma unroll
+    for (int k = 0; k < kAccPerThread; ++k) {
+        const double p = prob_of(xt[k], s.m_t, inv_st, ts);
+        sp += p;
+        if (!s.bonus) {
+            const double q = prob_of(xd[k], s.m_d, inv_sd, ts);
+            sr += fmax(p - q, 0.0);
+        }
+    }
+    sr = wave_sum(sr); sp = wave_sum(sp);
+    __shared__ double s_r[kAccThreads / kWave], s_p[kAccThreads / kWave];
+    const int w = tid / kWave;
+    if ((tid & (kWave - 1)) == 0) { s_r[w] = sr; s_p[w] = sp; }
+    __syncthreads();
+    if (tid == 0) {
+        ChunkMass m; m.r = 0.0; m.p = 0.0;
+        for (int i = 0; i < kAccThreads / kWave; ++i) { m.r += s_r[i]; m.p += s_p[i]; }
+        mass[(size_t)b * C + c] = m;
+    }
+}
+
+__global__ __launch_bounds__(kAccThreads)
+void residual_pick_kernel(const float* __restrict__ target, const float* __restrict__ draft,
+                          const float* __restrict__ uniforms, int gamma, int V, int C, TempScale ts,
+                          const SeqSel* __restrict__ sel, const ChunkMass* __restrict__ mass,
+                          int* __restrict__ out_tokens) {
+    const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
+    const SeqSel s = sel[b];
+    __shared__ int sh_chunk, sh_use_p, sh_first, sh_last;
+    __shared__ double sh_prefix, sh_thr;
+    __shared__ double sh_tot[kAccThreads];
+    if (tid == 0) {
+        const ChunkMass* m = mass + (size_t)b * C;
+        double tr = 0.0, tp = 0.0;
+        for (int c = 0; c < C; ++c) { tr += m[c].r; tp += m[c].p; }
+        const int use_p = s.bonus || !(tr > 0.0);
+        const double total = use_p ? tp : tr;
+        const double thr = (double)uniforms[b * Q + gamma] * total;
+        double run = 0.0; int chunk = -1, last_pos = 0;
+        for (int c = 0; c < C; ++c) {
+            const double v = use_p ? m[c].p : m[c].r;
+            if (v > 0.0) last_pos = c;
+            if (run + v > thr) { chunk = c; break; }
+            run += v;
+        }
+        if (chunk < 0) {                      // rounding kept the sum from crossing: last chunk with mass
+            chunk = last_pos;
+            run = 0.0;
+            for (int c = 0; c < chunk; ++c) run += use_p ? m[c].p : m[c].r;
+        }
+        sh_chunk = chunk; sh_use_p = use_p; sh_prefix = run; sh_thr = thr;
+        sh_first = INT_MAX; sh_last = -1;
+    }
+    __syncthreads();
+    const int base = sh_chunk * kAccChunk + tid * kAccPerThread;
+    const int use_p = sh_use_p;
+    const float* trow = target + ((size_t)b * Q + s.n) * V;
+    const float* drow = draft + ((size_t)b * gamma + (s.bonus ? 0 : s.n)) * V;
+    const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
+    double r[kAccPerThread];
+    double tot = 0.0;
+#pragma unroll
+    for (int k = 0; k < kAccPerThread; ++k) {
+        const int idx = base + k;
+        double v = 0.0;
+        if (idx < V) {
+            const double p = prob_of(trow[idx], s.m_t, inv_st, ts);
+            v = use_p ? p : fmax(p - prob_of(drow[idx], s.m_d, inv_sd, ts), 0.0);
+        }
+        r[k] = v; tot += v;
+    }
+    sh_tot[tid] = tot;
+    __syncthreads();
+    double before = sh_prefix;                // mass of everything ahead of this thread's 16 tokens
+    for (int i = 0; i < tid; ++i) before += sh_tot[i];
+    int first = INT_MAX, last = -1;
+    double run = before;
+#pragma unroll
+    for (int k = 0; k < kAccPerThread; ++k) {
+        run += r[k];
+        if (r[k] > 0.0) last = base + k;
+        if (first == INT_MAX && run > sh_thr && base + k < V) first = base + k;
+    }
+    if (first != INT_MAX) atomicMin(&sh_first, first);
+    if (last >= 0) atomicMax(&sh_last, last);
+    __syncthreads();
+    if (tid == 0) out_tokens[b * Q + s.n] = (sh_first != INT_MAX) ? sh_first : (sh_last >= 0 ? sh_last : 0);
+}
+
+static inline int n_chunks(int V) { return (V + kAccChunk - 1) / kAccChunk; }
+
+struct AcceptLayout { size_t part, sel, mass, total; };
+static AcceptLayout accept_layout(int B, int gamma, int V) {
+    AcceptLayout l;
+    const size_t C = n_chunks(V), rows = (size_t)B * (2 * gamma + 1);
+    l.part = 0;
+    l.sel = align_up(l.part + rows * C * sizeof(RowPartial), 256);
+    l.mass = align_up(l.sel + (size_t)B * sizeof(SeqSel), 256);
+    l.total = align_up(l.mass + (size_t)B * C * sizeof(ChunkMass), 256);
+    return l;
+}
+
+}  // namespace massv
+
+using namespace massv;
+
+extern "C" size_t massv_spec_accept_workspace(int32_t B, int32_t gamma, int32_t V) {
+    if (B < 1 || gamma < 1 || gamma > kMaxGamma || V < 1) return 0;
+    return accept_layout(B, gamma, V).total;
+}
+
+extern "C" int massv_spec_accept(const float* target_logits, const float* draft_logits,
+                                 const int32_t* draft_tokens, const float* uniforms,
+                                 float temperature, int32_t B, int32_t gamma, int32_t V,
+                                 int32_t* n_accepted, int32_t* out_tokens,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 1 || gamma < 1 || V < 1) return MASSV_EINVAL;
+    if (!(temperature >= 0.f) || isinf(temperature)) return MASSV_EINVAL;     // also catches NaN
+    if (!target_logits || !draft_tokens || !n_accepted || !out_tokens) return MASSV_EINVAL;
+    const int greedy = (temperature == 0.f);
+    if (!greedy && (!draft_logits || !uniforms)) return MASSV_EINVAL;
+    if (gamma > kMaxGamma) return MASSV_EUNSUPPORTED;
+    if ((size_t)B * (gamma + 1) > 65535 || (size_t)B > 65535) return MASSV_EUNSUPPORTED;   // grid.y limit
+    const AcceptLayout lay = accept_layout(B, gamma, V);
+    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+    if ((size_t)B * (2 * gamma + 1) > 65535) return MASSV_EUNSUPPORTED;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    RowPartial* part = (RowPartial*)(ws + lay.part);
+    SeqSel* sel = (SeqSel*)(ws + lay.sel);
+    ChunkMass* mass = (ChunkMass*)(ws + lay.mass);
+    const int C = n_chunks(V), Q = gamma + 1;
+    TempScale ts; ts.hi = 1.f; ts.lo = 0.f; ts.inv = 1.0;
+    if (!greedy) {
+        ts.inv = 1.0 / (double)temperature;
+        ts.hi = (float)ts.inv;
+        ts.lo = (float)(ts.inv - (double)ts.hi);
+    }
+    const int vec = (V % 4 == 0) && ((uintptr_t)target_logits % 16 == 0) &&
+                    (greedy || (uintptr_t)draft_logits % 16 == 0);
+    const int rows = greedy ? B * Q : B * (Q + gamma);
+
+    hipLaunchKernelGGL(accept_stats_kernel, dim3(C, rows), dim3(kAccThreads), 0, st,
+                       target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kWave), 0, st,
+                       target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
+                       greedy, part, sel, n_accepted, out_tokens);
+    if (!greedy) {
+        hipLaunchKernelGGL(residual_mass_kernel, dim3(C, B), dim3(kAccThreads), 0, st,
+                           target_logits, draft_logits, gamma, V, C, ts, vec, sel, mass);
+        hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,
+                           target_logits, draft_logits, uniforms, gamma, V, C, ts, sel, mass, out_tokens);
+    }
+    return launch_status();
+}

@@ -1,0 +1,453 @@
+// verify_attention: grouped-query causal attention of the Q = gamma+1 new
+// positions over the KV cache (paper Section 2.1: one parallel forward scores
+// every drafted position; query i sees cache rows [0, kv_len + i]).
+//
+// bf16 path (the one that matters): the cost is one pass over the cached K and
+// V of every (sequence, KV head), so the kernel is built as an HBM stream.
+//   * The G*Q query rows that share a KV head are stacked as the 16-row tiles
+//     of the matrix instruction, so each K / V element is fetched once for all
+//     of them (G*Q = 42 for 28/4 heads and gamma = 5).
+//   * Scores are formed transposed, S^T = K Q^T with v_mfma_f32_16x16x32_bf16:
+//     the A operand is a 16-key x 32-dim tile of K that every lane loads
+//     straight from HBM with one 16-byte load, the B operand is Q held in
+//     registers for the whole kernel.  The result leaves each lane holding, for
+//     one query row, 4 consecutive keys of the 32-key block per instruction.
+//     Choosing the 16 keys of a tile as {8c + 4t + i} makes the two tiles of a
+//     block hand lane group c exactly keys 8c..8c+7 -- the operand order the
+//     second product needs -- so probabilities never move between lanes.
+//   * O^T += V^T P^T takes V^T tiles (16 dims x 32 keys) as the A operand.  The
+//     value cache stores each block of 32 keys dim-major, so that tile is again
+//     one 16-byte load per lane, contiguous over the wave.  No LDS staging and
+//     no transposes are needed; LDS is used only to merge the waves of a
+//     workgroup at the end.
+//   * A workgroup (4 waves) owns one (sequence, KV head, split of the key
+//     range); its waves take 32-key blocks round-robin, keep a running
+//     (max, sum, O) in registers with the usual streaming softmax, and are
+//     merged through LDS.  Splits are merged by a second small kernel in fixed
+//     order.  Only the blocks holding the new positions pay for the causal
+//     mask.
+// f32 path: a plain one-workgroup-per-(b, head, query) kernel for the small
+// fp32 configuration.
+#include "kernels.h"
+
+namespace massv {
+
+constexpr int kAttnWaves = 4;
+constexpr int kAttnThreads = kAttnWaves * kWave;
+constexpr int kBlk = MASSV_V_BLOCK;            // keys per block
+
+__device__ inline size_t v_index(size_t bg, int l_max, int d, int j, int c) {
+    return ((bg * (size_t)(l_max / kBlk) + (size_t)(j / kBlk)) * d + c) * kBlk + (j % kBlk);
+}
+
+__device__ inline int clamp_total(int kv_len, int Q, int l_max) {
+    int n = (kv_len < 0 ? 0 : kv_len) + Q;
+    return n > l_max ? l_max : n;
+}
+
+// ---------------------------------------------------------------------------
+// generic kernel (any dtype, any d <= 256): grid (Q, n_q, B), 256 threads.
+// Keys are taken 256 at a time: thread t scores key t, the tile's weights go
+// through LDS, thread c accumulates output column c.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256)
+void attention_generic_kernel(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
+                              const int32_t* __restrict__ kv_len, T* __restrict__ out,
+                              int Q, int n_q, int n_kv, int d, int l_max, float scale) {
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int G = n_q / n_kv, g = h / G;
+    const size_t bg = (size_t)b * n_kv + g;
+    int L = kv_len[b]; L = L < 0 ? 0 : L;
+    int n_vis = L + i + 1;
+    if (n_vis > l_max) n_vis = l_max;
+    __shared__ float qs[256];
+    __shared__ float w[256];
+    __shared__ float red[4];
+    const T* qr = q + (((size_t)b * Q + i) * n_q + h) * d;
+    if (tid < d) qs[tid] = ldf(qr + tid);
+    __syncthreads();
+    float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+    for (int j0 = 0; j0 < n_vis; j0 += 256) {
+        const int j = j0 + tid;
+        float s = -INFINITY;
+        if (j < n_vis) {
+            const T* kr = kc + (bg * l_max + j) * d;
+            float dot = 0.f;
+            for (int c = 0; c < d; ++c) dot += qs[c] * ldf(kr + c);
+            s = dot * scale;
+        }
+        float mx = wave_max(s);
+        if ((tid & 63) == 0) red[tid >> 6] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        const float m_new = fmaxf(m_run, mx);                 // finite: key j0 is visible
+        const float p = (j < n_vis) ? expf(s - m_new) : 0.f;
+        w[tid] = p;
+        float ps = wave_sum(p);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = ps;
+        __syncthreads();
+        ps = red[0] + red[1] + red[2] + red[3];
+        const float alpha = expf(m_run - m_new);
+        l_run = l_run * alpha + ps;
+        acc *= alpha;
+        if (tid < d) {
+            const int cnt = (n_vis - j0) < 256 ? (n_vis - j0) : 256;
+            for (int t = 0; t < cnt; ++t) acc += w[t] * ldf(vc + v_index(bg, l_max, d, j0 + t, tid));
+        }
+        m_run = m_new;
+        __syncthreads();
+    }
+    if (tid < d) stf(out + (((size_t)b * Q + i) * n_q + h) * d + tid, acc / l_run);
+}
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernel.
+// ---------------------------------------------------------------------------
+__device__ inline float xor16_max(float v) {        // over the 4 lane groups that share a query row
+    v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    return fmaxf(v, __shfl_xor(v, 32, kWave));
+}
+__device__ inline float xor16_sum(float v) {
+    v += __shfl_xor(v, 16, kWave);
+    return v + __shfl_xor(v, 32, kWave);
+}
+
+struct AttnParams {
+    const bf16_t* q; const bf16_t* kc; const bf16_t* vc; const int32_t* kv_len;
+    bf16_t* out;                 // used when n_split == 1
+    float* part_o; float* part_ml;   // [B][n_kv][S][rows_pad][D], [B][n_kv][S][rows_pad][2]
+    int Q, n_q, n_kv, l_max, n_split;
+    float scale_log2;            // scale * log2(e)
+};
+
+template <int D, int MT>
+__global__ __launch_bounds__(kAttnThreads)
+void attention_mfma_kernel(AttnParams p) {
+    constexpr int KS = D / 32;          // k-steps of the score product
+    constexpr int NT = D / 16;          // 16-dim tiles of the output
+    constexpr int ROWS = MT * 16;
+    constexpr int LDS_STRIDE = D + 4;   // floats per row in the merge buffer (keeps float4 stores conflict-light)
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int lr = lane % 16, lc = lane / 16;
+    const int G = p.n_q / p.n_kv, rows = G * p.Q;
+    const size_t bg = (size_t)b * p.n_kv + g;
+    int L = p.kv_len[b]; L = L < 0 ? 0 : L;
+    const int n_total = clamp_total(L, p.Q, p.l_max);
+    const int n_blocks = (n_total + kBlk - 1) / kBlk;
+    const int per = (n_blocks + p.n_split - 1) / p.n_split;
+    const int blk_begin = split * per;
+    const int blk_end = (blk_begin + per < n_blocks) ? blk_begin + per : n_blocks;
+    const int first_masked_blk = L / kBlk;      // blocks before it hold cached positions only
+
+    // ---- Q operand: lane (lr, lc) holds Q[row = 16 mt + lr][32 ks + 8 lc .. +8] ----
+    bf16x8 qreg[MT][KS];
+    int qi[MT];                                 // query position of this lane's row in tile mt (clamped)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r = mt * 16 + lr;
+        const int i = r / G, hh = r % G;
+        qi[mt] = i < p.Q ? i : p.Q - 1;
+        const bf16_t* qr = p.q + (((size_t)b * p.Q + (i < p.Q ? i : 0)) * p.n_q + g * G + hh) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (r < rows) v = *reinterpret_cast<const bf16x8*>(qr + ks * 32 + lc * 8);
+            qreg[mt][ks] = v;
+        }
+    }
+
+    floatx4 acc[MT][NT];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY; l_run[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const bf16_t* kbase = p.kc + bg * (size_t)p.l_max * D;
+    const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D;
+
+    for (int blk = blk_begin + wave; blk < blk_end; blk += kAttnWaves) {
+        // ---- loads: K tile t holds keys {8c + 4t + i}; lane lr = 4c + i ----
+        bf16x8 kreg[2][KS], vreg[NT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = blk * kBlk + (lr / 4) * 8 + t * 4 + (lr % 4);
+            const bf16_t* kr = kbase + (size_t)key * D + lc * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kreg[t][ks] = *reinterpret_cast<const bf16x8*>(kr + ks * 32);
+        }
+        const bf16_t* vb = vbase + (size_t)blk * D * kBlk + lc * 8;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            vreg[nt] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kBlk);
+
+        const bool tail = (blk + 1) * kBlk > n_total;         // block reaches past the valid rows
+        if (tail) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (blk * kBlk + lc * 8 + e >= n_total) vreg[nt][e] = (bf16_t)0.f;
+        }
+        const bool masked = blk >= first_masked_blk;
+
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            // ---- S^T tile pair: lane holds keys 8 lc + (0..7) of query row 16 mt + lr ----
+            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qreg[mt][ks], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qreg[mt][ks], s1, 0, 0, 0);
+            }
+            float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sv[e] *= p.scale_log2;
+            if (masked) {
+                const int last_visible = L + qi[mt];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (blk * kBlk + lc * 8 + e > last_visible) sv[e] = -INFINITY;
+            }
+            float mx = sv[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+            mx = xor16_max(mx);
+            const float m_new = fmaxf(m_run[mt], mx);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m_run[mt] - m_safe);
+            float ps = 0.f;
+            bf16x8 pv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pe = exp2f(sv[e] - m_safe);
+                ps += pe;
+                pv[e] = (bf16_t)pe;
+            }
+            l_run[mt] = l_run[mt] * alpha + ps;
+            m_run[mt] = m_new;
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= alpha;
+            }
+            // ---- O^T += V^T P^T ----
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[nt], pv, acc[mt][nt], 0, 0, 0);
+        }
+    }
+
+    // ---- merge the waves of the workgroup ----
+    __shared__ float s_m[kAttnWaves][ROWS];
+    __shared__ float s_l[kAttnWaves][ROWS];
+    __shared__ float s_lt[ROWS];
+    extern __shared__ float s_o[];               // [ROWS][LDS_STRIDE]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const float l = xor16_sum(l_run[mt]);
+        if (lc == 0) { s_m[wave][mt * 16 + lr] = m_run[mt]; s_l[wave][mt * 16 + lr] = l; }
+    }
+    __syncthreads();
+    float m_tot[MT], l_tot[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r = mt * 16 + lr;
+        float m = s_m[0][r];
+#pragma unroll
+        for (int w = 1; w < kAttnWaves; ++w) m = fmaxf(m, s_m[w][r]);
+        const float m_safe = (m == -INFINITY) ? 0.f : m;
+        float l = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) l += s_l[w][r] * exp2f(s_m[w][r] - m_safe);
+        const float f = exp2f(m_run[mt] - m_safe);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= f;
+        m_tot[mt] = m; l_tot[mt] = l;
+        if (wave == 0 && lc == 0) s_lt[r] = l;
+    }
+    for (int w = 0; w < kAttnWaves; ++w) {          // waves add into the buffer one after another
+        if (wave == w) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    float* dst = s_o + (mt * 16 + lr) * LDS_STRIDE + nt * 16 + lc * 4;
+                    floatx4 v = acc[mt][nt];
+                    if (w > 0) v += *reinterpret_cast<floatx4*>(dst);
+                    *reinterpret_cast<floatx4*>(dst) = v;
+                }
+        }
+        __syncthreads();
+    }
+
+    // ---- write: final output if there is one split, else the partial ----
+    if (p.n_split == 1) {
+        for (int idx = tid; idx < rows * (D / 4); idx += kAttnThreads) {
+            const int r = idx / (D / 4), c4 = idx % (D / 4);
+            const int i = r / G, hh = r % G;
+            const floatx4 v = *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
+            const float inv = 1.0f / s_lt[r];
+            bf16x4 o = {(bf16_t)(v[0] * inv), (bf16_t)(v[1] * inv), (bf16_t)(v[2] * inv), (bf16_t)(v[3] * inv)};
+            *reinterpret_cast<bf16x4*>(p.out + (((size_t)b * p.Q + i) * p.n_q + g * G + hh) * D + c4 * 4) = o;
+        }
+    } else {
+        const size_t slot = (bg * p.n_split + split) * ROWS;
+        for (int idx = tid; idx < rows * (D / 4); idx += kAttnThreads) {
+            const int r = idx / (D / 4), c4 = idx % (D / 4);
+            *reinterpret_cast<floatx4*>(p.part_o + (slot + r) * D + c4 * 4) =
+                *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
+        }
+        if (wave == 0 && lc == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float* ml = p.part_ml + (slot + mt * 16 + lr) * 2;
+                ml[0] = m_tot[mt]; ml[1] = l_tot[mt];
+            }
+        }
+    }
+}
+
+// Merge of the key-range splits: one workgroup of D/4 threads per output row.
+template <int D>
+__global__ void attention_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                         bf16_t* __restrict__ out, int Q, int n_q, int n_kv, int n_split, int rows_pad) {
+    const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, t = threadIdx.x;
+    const int G = n_q / n_kv, g = h / G, r = i * G + (h % G);
+    const size_t slot0 = ((size_t)b * n_kv + g) * n_split * rows_pad;
+    float m = -INFINITY;
+    for (int s = 0; s < n_split; ++s) m = fmaxf(m, part_ml[(slot0 + (size_t)s * rows_pad + r) * 2]);
+    floatx4 o = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+        const size_t row = slot0 + (size_t)s * rows_pad + r;
+        const float ms = part_ml[row * 2];
+        if (ms == -INFINITY) continue;                      // split saw no visible key for this row
+        const float w = exp2f(ms - m);
+        l += part_ml[row * 2 + 1] * w;
+        o += *reinterpret_cast<const floatx4*>(part_o + row * D + t * 4) * w;
+    }
+    const float inv = 1.0f / l;
+    bf16x4 ob = {(bf16_t)(o[0] * inv), (bf16_t)(o[1] * inv), (bf16_t)(o[2] * inv), (bf16_t)(o[3] * inv)};
+    *reinterpret_cast<bf16x4*>(out + (((size_t)b * Q + i) * n_q + h) * D + t * 4) = ob;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static int rows_pad_of(const massv_attn_desc& a) {
+    const int rows = (a.n_q_heads / a.n_kv_heads) * a.n_query;
+    return (rows + 15) / 16 * 16;
+}
+
+// Number of key-range splits: enough workgroups to give every CU one, but no
+// split shorter than one block per wave.
+static int n_split_of(const massv_attn_desc& a) {
+    const int pairs = a.batch * a.n_kv_heads;
+    const int max_blocks = a.l_max / kBlk;
+    int s = (256 + pairs - 1) / pairs;
+    const int cap = (max_blocks + kAttnWaves - 1) / kAttnWaves;
+    if (s > cap) s = cap;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return s;
+}
+
+int check_attn_desc(const massv_attn_desc* a) {
+    if (!a) return MASSV_EINVAL;
+    if (a->batch < 1 || a->n_query < 1 || a->n_q_heads < 1 || a->n_kv_heads < 1 || a->head_dim < 2) return MASSV_EINVAL;
+    if (a->n_q_heads % a->n_kv_heads) return MASSV_EINVAL;
+    if (a->l_max < kBlk || a->l_max % kBlk) return MASSV_EINVAL;
+    if (a->n_query > a->l_max) return MASSV_EINVAL;
+    if (!(a->scale >= 0.f) || isinf(a->scale)) return MASSV_EINVAL;
+    if (a->dtype != MASSV_F32 && a->dtype != MASSV_BF16) return MASSV_EINVAL;
+    if (a->head_dim % 2) return MASSV_EINVAL;
+    if (a->batch > 65535 || a->n_q_heads > 65535) return MASSV_EUNSUPPORTED;
+    if (a->dtype == MASSV_F32) {
+        if (a->head_dim > 256) return MASSV_EUNSUPPORTED;
+    } else {
+        if (a->head_dim != 64 && a->head_dim != 128 && a->head_dim != 256) return MASSV_EUNSUPPORTED;
+        if (rows_pad_of(*a) > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
+        if (a->head_dim == 256 && rows_pad_of(*a) > 32) return MASSV_EUNSUPPORTED;
+    }
+    return MASSV_OK;
+}
+
+size_t attention_workspace(const massv_attn_desc& a) {
+    if (a.dtype == MASSV_F32) return 256;
+    const size_t slots = (size_t)a.batch * a.n_kv_heads * n_split_of(a) * rows_pad_of(a);
+    return align_up(slots * a.head_dim * sizeof(float), 256) + align_up(slots * 2 * sizeof(float), 256);
+}
+
+template <int D, int MT>
+static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
+    const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float);
+    hipLaunchKernelGGL((attention_mfma_kernel<D, MT>), dim3(p.n_split, a.n_kv_heads, a.batch), dim3(kAttnThreads),
+                       lds, st, p);
+    if (p.n_split > 1)
+        hipLaunchKernelGGL((attention_combine_kernel<D>), dim3(a.n_q_heads, a.n_query, a.batch), dim3(D / 4), 0, st,
+                           p.part_o, p.part_ml, p.out, a.n_query, a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16);
+    return launch_status();
+}
+
+template <int D>
+static int launch_mfma_d(const massv_attn_desc& a, AttnParams p, int mt, hipStream_t st) {
+    switch (mt) {
+        case 1: return launch_mfma<D, 1>(a, p, st);
+        case 2: return launch_mfma<D, 2>(a, p, st);
+        case 3: if constexpr (D <= 128) return launch_mfma<D, 3>(a, p, st); else return MASSV_EUNSUPPORTED;
+        case 4: if constexpr (D <= 128) return launch_mfma<D, 4>(a, p, st); else return MASSV_EUNSUPPORTED;
+    }
+    return MASSV_EUNSUPPORTED;
+}
+
+int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* kv_len, void* out, void* ws, hipStream_t st) {
+    const float scale = a.scale > 0.f ? a.scale : 1.0f / sqrtf((float)a.head_dim);
+    if (a.dtype == MASSV_F32) {
+        hipLaunchKernelGGL(attention_generic_kernel<float>, dim3(a.n_query, a.n_q_heads, a.batch), dim3(256), 0, st,
+                           (const float*)q, (const float*)k_cache, (const float*)v_cache, kv_len, (float*)out,
+                           a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, scale);
+        return launch_status();
+    }
+    AttnParams p;
+    p.q = (const bf16_t*)q; p.kc = (const bf16_t*)k_cache; p.vc = (const bf16_t*)v_cache; p.kv_len = kv_len;
+    p.out = (bf16_t*)out;
+    p.Q = a.n_query; p.n_q = a.n_q_heads; p.n_kv = a.n_kv_heads; p.l_max = a.l_max;
+    p.n_split = n_split_of(a);
+    p.scale_log2 = scale * 1.4426950408889634f;
+    const int rp = rows_pad_of(a);
+    const size_t slots = (size_t)a.batch * a.n_kv_heads * p.n_split * rp;
+    p.part_o = (float*)ws;
+    p.part_ml = (float*)((char*)ws + align_up(slots * a.head_dim * sizeof(float), 256));
+    const int mt = rp / 16;
+    switch (a.head_dim) {
+        case 64: return launch_mfma_d<64>(a, p, mt, st);
+        case 128: return launch_mfma_d<128>(a, p, mt, st);
+        case 256: return launch_mfma_d<256>(a, p, mt, st);
+    }
+    return MASSV_EUNSUPPORTED;
+}
+
+}  // namespace massv
+
+using namespace massv;
+
+extern "C" size_t massv_verify_attention_workspace(const massv_attn_desc* desc) {
+    if (check_attn_desc(desc) != MASSV_OK) return 0;
+    return attention_workspace(*desc);
+}
+
+extern "C" int massv_verify_attention(const massv_attn_desc* desc, const void* q, const void* k_cache,
+                                      const void* v_cache, const int32_t* kv_len, void* out,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_attn_desc(desc);
+    if (rc != MASSV_OK) return rc;
+    if (!q || !k_cache || !v_cache || !kv_len || !out) return MASSV_EINVAL;
+    if (!workspace || workspace_bytes < attention_workspace(*desc)) return MASSV_EWORKSPACE;
+    return launch_attention(*desc, q, k_cache, v_cache, kv_len, out, workspace, (hipStream_t)stream);
+}

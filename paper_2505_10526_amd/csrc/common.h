@@ -1,0 +1,57 @@
+// Internal helpers shared by the gfx950 kernels of libmassv_verify.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+
+#include "massv_verify.h"
+
+namespace massv {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Status of the launch that was just enqueued.
+static inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? MASSV_OK : MASSV_ELAUNCH;
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+template <typename T> struct ElemOf;
+template <> struct ElemOf<float> {
+    __device__ static inline float load(const float* p) { return *p; }
+    __device__ static inline void store(float* p, float v) { *p = v; }
+};
+template <> struct ElemOf<bf16_t> {
+    __device__ static inline float load(const bf16_t* p) { return (float)*p; }
+    __device__ static inline void store(bf16_t* p, float v) { *p = (bf16_t)v; }
+};
+
+template <typename T> __device__ inline float ldf(const T* p) { return ElemOf<T>::load(p); }
+template <typename T> __device__ inline void stf(T* p, float v) { ElemOf<T>::store(p, v); }
+
+// ---- wavefront reductions (all 64 lanes take part, all receive the result) ----
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+}  // namespace massv

@@ -1,0 +1,155 @@
+// Row-wise kernels of the decoder layer: RMSNorm, rotary embedding with KV
+// append, gated activation, value-cache packing.  All traffic here is a few
+// hundred KB per call; the kernels are written for clarity and coalescing,
+// the math is fp32 (angles in double).
+#include "kernels.h"
+
+namespace massv {
+
+// ---------------------------------------------------------------------------
+// RMSNorm: one workgroup per row.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256)
+void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restrict__ y, int H, float eps) {
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const T* xr = x + (size_t)m * H;
+    float ss = 0.f;
+    for (int k = tid; k < H; k += 256) { float v = ldf(xr + k); ss += v * v; }
+    ss = wave_sum(ss);
+    __shared__ float part[4];
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = part[0] + part[1] + part[2] + part[3];
+    const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+    T* yr = y + (size_t)m * H;
+    for (int k = tid; k < H; k += 256) stf(yr + k, ldf(xr + k) * rstd * ldf(g + k));
+}
+
+int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st) {
+    if (dtype == MASSV_F32)
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, H, eps);
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------
+// Rotary embedding + KV append.  grid = (M, n_q + 2 n_kv); thread j < d/2 owns
+// the pair (j, j + d/2) of one head of one token.
+// ---------------------------------------------------------------------------
+__device__ inline size_t v_cache_index(size_t bg, int l_max, int d, int j, int c) {
+    return ((bg * (size_t)(l_max / MASSV_V_BLOCK) + (size_t)(j / MASSV_V_BLOCK)) * d + c) * MASSV_V_BLOCK + (j % MASSV_V_BLOCK);
+}
+
+template <typename T>
+__global__ void rope_append_kernel(const T* __restrict__ qkv, const int32_t* __restrict__ pos,
+                                   const int32_t* __restrict__ kv_len, T* __restrict__ q_out,
+                                   T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                   int Q, int n_q, int n_kv, int d, int l_max, double log2_theta) {
+    const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
+    const int half = d / 2;
+    if (j >= half) return;
+    const int b = m / Q, i = m % Q;
+    const int width = (n_q + 2 * n_kv) * d;
+    const T* src = qkv + (size_t)m * width + (size_t)head * d;
+    const float x1 = ldf(src + j), x2 = ldf(src + j + half);
+    int row = kv_len[b];
+    row = (row < 0 ? 0 : row) + i;
+    if (head < n_q + n_kv) {
+        const double ang = (double)pos[m] * exp2(-2.0 * (double)j / (double)d * log2_theta);
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        const float y1 = (float)((double)x1 * cs - (double)x2 * sn);
+        const float y2 = (float)((double)x2 * cs + (double)x1 * sn);
+        if (head < n_q) {
+            T* dst = q_out + ((size_t)m * n_q + head) * d;
+            stf(dst + j, y1); stf(dst + j + half, y2);
+        } else if (row < l_max) {
+            const int g = head - n_q;
+            T* dst = k_cache + (((size_t)b * n_kv + g) * l_max + row) * d;
+            stf(dst + j, y1); stf(dst + j + half, y2);
+        }
+    } else if (row < l_max) {
+        const int g = head - n_q - n_kv;
+        const size_t bg = (size_t)b * n_kv + g;
+        stf(v_cache + v_cache_index(bg, l_max, d, row, j), x1);
+        stf(v_cache + v_cache_index(bg, l_max, d, row, j + half), x2);
+    }
+}
+
+int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
+                       void* k_cache, void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st) {
+    const int M = a.batch * a.n_query;
+    dim3 grid(M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
+    const double l2t = log2((double)theta);
+    if (a.dtype == MASSV_F32)
+        hipLaunchKernelGGL(rope_append_kernel<float>, grid, block, 0, st, (const float*)qkv, pos, kv_len, (float*)q_out,
+                           (float*)k_cache, (float*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+    else
+        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)qkv, pos, kv_len, (bf16_t*)q_out,
+                           (bf16_t*)k_cache, (bf16_t*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------
+// h = act(g) * u
+// ---------------------------------------------------------------------------
+__device__ inline float act_fn(float x, int act) {
+    if (act == MASSV_ACT_SILU) return x / (1.0f + expf(-x));
+    const float c = 0.7978845608028654f;      // sqrt(2/pi)
+    return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
+}
+
+template <typename T>
+__global__ void act_mul_kernel(const T* __restrict__ g, const T* __restrict__ u, T* __restrict__ h, size_t n, int act) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) stf(h + i, act_fn(ldf(g + i), act) * ldf(u + i));
+}
+
+int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int dtype, hipStream_t st) {
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (dtype == MASSV_F32)
+        hipLaunchKernelGGL(act_mul_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)g, (const float*)u, (float*)h, n, act);
+    else
+        hipLaunchKernelGGL(act_mul_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)g, (const bf16_t*)u, (bf16_t*)h, n, act);
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------
+// Row-major values -> blocked value cache.  One thread per destination element
+// (writes coalesced).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void v_pack_kernel(const T* __restrict__ src, T* __restrict__ dst, size_t total, int l_max, int d) {
+    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total) return;
+    const int jj = (int)(o % MASSV_V_BLOCK);
+    const size_t t1 = o / MASSV_V_BLOCK;
+    const int c = (int)(t1 % d);
+    const size_t t2 = t1 / d;
+    const int blk = (int)(t2 % (l_max / MASSV_V_BLOCK));
+    const size_t bg = t2 / (l_max / MASSV_V_BLOCK);
+    const int j = blk * MASSV_V_BLOCK + jj;
+    dst[o] = src[(bg * l_max + j) * d + c];
+}
+
+}  // namespace massv
+
+using namespace massv;
+
+extern "C" int massv_v_cache_pack(const void* src, void* dst, int32_t batch, int32_t n_kv_heads,
+                                  int32_t l_max, int32_t head_dim, int32_t dtype, void* stream) {
+    if (!src || !dst || batch < 1 || n_kv_heads < 1 || l_max < 1 || head_dim < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    if (l_max % MASSV_V_BLOCK) return MASSV_EINVAL;
+    const size_t total = (size_t)batch * n_kv_heads * l_max * head_dim;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffu) return MASSV_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == MASSV_F32)
+        hipLaunchKernelGGL(v_pack_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)src, (float*)dst, total, l_max, head_dim);
+    else
+        hipLaunchKernelGGL(v_pack_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, total, l_max, head_dim);
+    return launch_status();
+}

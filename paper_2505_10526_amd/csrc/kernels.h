@@ -1,0 +1,49 @@
+// Internal launch interface between the translation units of libmassv_verify.
+// Every function only enqueues on `st` and returns a massv_status.
+#pragma once
+
+#include "common.h"
+
+namespace massv {
+
+// ---- small row-wise kernels (elementwise.hip) ----
+// y[m,:] = x[m,:] * g / sqrt(mean(x[m,:]^2) + eps)
+int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st);
+// Rotates the q and k heads of qkv[M][(n_q+2n_kv)*d] by pos[m], writes q to
+// q_out[M][n_q][d] and the k / v rows of token (b,i) to cache row kv_len[b]+i.
+int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
+                       void* k_cache, void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st);
+int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int dtype, hipStream_t st);
+
+// ---- projections (gemm.hip) ----
+// One linear map Y = X W^T over M rows.  Up to three weight matrices that share
+// X are applied in one launch; their outputs are laid side by side in Y
+// ([M][n0+n1+n2]).
+enum Epilogue {
+    EPI_STORE = 0,      // y = acc (+ bias), stored in the activation dtype
+    EPI_RESIDUAL = 1,   // y = acc + residual (residual may alias y), activation dtype
+    EPI_GATED = 2,      // two matrices (gate, up) of equal size: y = act(gate) * up
+    EPI_LOGITS = 3      // y = acc stored as float32
+};
+struct GemmArgs {
+    const void* x;            // [M][K]
+    const void* w[3];         // [n_i][K]
+    const void* bias[3];      // [n_i] or nullptr
+    int n[3];                 // rows of each matrix (0 = unused)
+    const void* residual;     // EPI_RESIDUAL: [M][n0]
+    void* y;
+    void* scratch;            // f32 + EPI_GATED only: [M][2*n0] floats
+    int M, K;
+    int epilogue, act, dtype;
+};
+int launch_gemm(const GemmArgs& g, hipStream_t st);
+// Whether launch_gemm can run this problem (host-side shape check only).
+int gemm_supported(const GemmArgs& g);
+
+// ---- attention (attention.hip) ----
+size_t attention_workspace(const massv_attn_desc& a);
+int check_attn_desc(const massv_attn_desc* a);
+int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* kv_len, void* out, void* ws, hipStream_t st);
+
+}  // namespace massv

@@ -1,0 +1,136 @@
+// verify_layer and lm_head_logits: the parallel forward of the verify step
+// (paper Section 2.1, "one forward call") as a fixed sequence of kernel
+// launches on the caller's stream.
+#include "kernels.h"
+
+namespace massv {
+
+struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, attn_ws, total; };
+
+static LayerLayout layer_layout(const massv_layer_desc& d) {
+    const massv_attn_desc& a = d.attn;
+    const size_t es = a.dtype == MASSV_F32 ? 4 : 2;
+    const size_t M = (size_t)a.batch * a.n_query;
+    const size_t nq = (size_t)a.n_q_heads * a.head_dim, nkv = (size_t)a.n_kv_heads * a.head_dim;
+    LayerLayout l;
+    size_t o = 0;
+    l.xn = o;   o = align_up(o + M * d.hidden * es, 256);
+    l.qkv = o;  o = align_up(o + M * (nq + 2 * nkv) * es, 256);
+    l.qrot = o; o = align_up(o + M * nq * es, 256);
+    l.attn = o; o = align_up(o + M * nq * es, 256);
+    l.h = o;    o = align_up(o + M * d.mlp * es, 256);
+    l.gu = o;   o = align_up(o + (a.dtype == MASSV_F32 ? M * 2 * d.mlp * 4 : 0), 256);
+    l.attn_ws = o; o = align_up(o + attention_workspace(a), 256);
+    l.total = o;
+    return l;
+}
+
+static int check_layer_desc(const massv_layer_desc* d) {
+    if (!d) return MASSV_EINVAL;
+    const int rc = check_attn_desc(&d->attn);
+    if (rc != MASSV_OK) return rc;
+    if (d->hidden < 1 || d->mlp < 1) return MASSV_EINVAL;
+    if (d->act != MASSV_ACT_SILU && d->act != MASSV_ACT_GELU_TANH) return MASSV_EINVAL;
+    if (!(d->norm_eps >= 0.f) || !(d->rope_theta > 0.f)) return MASSV_EINVAL;
+    if (d->attn.dtype == MASSV_BF16) {
+        const int M = d->attn.batch * d->attn.n_query;
+        if (M > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
+        if (d->hidden % 32 || d->mlp % 32 || (d->attn.n_q_heads * d->attn.head_dim) % 32) return MASSV_EUNSUPPORTED;
+    }
+    return MASSV_OK;
+}
+
+}  // namespace massv
+
+using namespace massv;
+
+extern "C" size_t massv_verify_layer_workspace(const massv_layer_desc* desc) {
+    if (check_layer_desc(desc) != MASSV_OK) return 0;
+    return layer_layout(*desc).total;
+}
+
+extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
+                                  void* x, const int32_t* pos, void* k_cache, void* v_cache,
+                                  const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer_desc(desc);
+    if (rc != MASSV_OK) return rc;
+    if (!w || !x || !pos || !k_cache || !v_cache || !kv_len) return MASSV_EINVAL;
+    if (!w->ln1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2 || !w->wg || !w->wu || !w->wd) return MASSV_EINVAL;
+    if (desc->qkv_bias && (!w->bq || !w->bk || !w->bv)) return MASSV_EINVAL;
+    const LayerLayout lay = layer_layout(*desc);
+    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+
+    const massv_attn_desc& a = desc->attn;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    const int M = a.batch * a.n_query, H = desc->hidden, F = desc->mlp;
+    const int nq = a.n_q_heads * a.head_dim, nkv = a.n_kv_heads * a.head_dim;
+    const bool bias = desc->qkv_bias != 0;
+
+    GemmArgs qkv = {};
+    qkv.x = ws + lay.xn;
+    qkv.w[0] = w->wq; qkv.w[1] = w->wk; qkv.w[2] = w->wv;
+    qkv.bias[0] = bias ? w->bq : nullptr; qkv.bias[1] = bias ? w->bk : nullptr; qkv.bias[2] = bias ? w->bv : nullptr;
+    qkv.n[0] = nq; qkv.n[1] = nkv; qkv.n[2] = nkv;
+    qkv.y = ws + lay.qkv; qkv.M = M; qkv.K = H; qkv.epilogue = EPI_STORE; qkv.act = desc->act; qkv.dtype = a.dtype;
+
+    GemmArgs op = {};
+    op.x = ws + lay.attn; op.w[0] = w->wo; op.n[0] = H; op.residual = x; op.y = x;
+    op.M = M; op.K = nq; op.epilogue = EPI_RESIDUAL; op.act = desc->act; op.dtype = a.dtype;
+
+    GemmArgs gu = {};
+    gu.x = ws + lay.xn; gu.w[0] = w->wg; gu.w[1] = w->wu; gu.n[0] = F; gu.n[1] = F;
+    gu.y = ws + lay.h; gu.scratch = ws + lay.gu;
+    gu.M = M; gu.K = H; gu.epilogue = EPI_GATED; gu.act = desc->act; gu.dtype = a.dtype;
+
+    GemmArgs dn = {};
+    dn.x = ws + lay.h; dn.w[0] = w->wd; dn.n[0] = H; dn.residual = x; dn.y = x;
+    dn.M = M; dn.K = F; dn.epilogue = EPI_RESIDUAL; dn.act = desc->act; dn.dtype = a.dtype;
+
+    // shape checks for every projection before the first launch
+    if ((rc = gemm_supported(qkv)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(op)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(gu)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(dn)) != MASSV_OK) return rc;
+
+    if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(qkv, st)) != MASSV_OK) return rc;
+    if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a, desc->rope_theta, st)) != MASSV_OK) return rc;
+    if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(op, st)) != MASSV_OK) return rc;
+    if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(gu, st)) != MASSV_OK) return rc;
+    return launch_gemm(dn, st);
+}
+
+static int check_lm_head(int32_t M, int32_t H, int32_t V, int32_t dtype) {
+    if (M < 1 || H < 1 || V < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    if (dtype == MASSV_BF16 && (M > MASSV_MAX_ROWS || H % 32 || V % 16)) return MASSV_EUNSUPPORTED;
+    return MASSV_OK;
+}
+
+extern "C" size_t massv_lm_head_logits_workspace(int32_t M, int32_t H, int32_t V, int32_t dtype) {
+    if (check_lm_head(M, H, V, dtype) != MASSV_OK) return 0;
+    return align_up((size_t)M * H * (dtype == MASSV_F32 ? 4 : 2), 256);
+}
+
+extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const void* w_lm, float* logits,
+                                    int32_t M, int32_t H, int32_t V, float norm_eps, int32_t dtype,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_lm_head(M, H, V, dtype);
+    if (rc != MASSV_OK) return rc;
+    if (!x || !w_lm || !logits) return MASSV_EINVAL;
+    if (!(norm_eps >= 0.f)) return MASSV_EINVAL;
+    if (!workspace || workspace_bytes < massv_lm_head_logits_workspace(M, H, V, dtype)) return MASSV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    GemmArgs g = {};
+    g.x = x;
+    if (final_norm) {
+        if ((rc = launch_rmsnorm(x, final_norm, workspace, M, H, norm_eps, dtype, st)) != MASSV_OK) return rc;
+        g.x = workspace;
+    }
+    g.w[0] = w_lm; g.n[0] = V; g.y = logits; g.M = M; g.K = H;
+    g.epilogue = EPI_LOGITS; g.dtype = dtype;
+    return launch_gemm(g, st);
+}

@@ -1,0 +1,118 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_10526_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "massv_verify.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(massv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    assert binding.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert binding.status_string(code)
+    assert lib.massv_abi_version() >= 1
+
+
+def test_struct_sizes_match_header():
+    assert C.sizeof(binding.AttnDesc) == 32
+    assert C.sizeof(binding.LayerDesc) == 32 + 24
+    assert C.sizeof(binding.LayerWeights) == 12 * C.sizeof(C.c_void_p)
+
+
+FAKE = C.c_void_p(0x1000)      # never dereferenced: every call below must fail validation first
+
+
+def test_spec_accept_argument_checks(lib):
+    f = lib.massv_spec_accept
+    ws = lib.massv_spec_accept_workspace(2, 5, 1000)
+    assert ws > 0
+    assert lib.massv_spec_accept_workspace(0, 5, 1000) == 0
+    ok_args = lambda **kw: [kw.get("t", FAKE), kw.get("d", FAKE), kw.get("x", FAKE), kw.get("u", FAKE),
+                            kw.get("T", 1.0), kw.get("B", 2), kw.get("g", 5), kw.get("V", 1000),
+                            kw.get("n", FAKE), kw.get("o", FAKE), kw.get("ws", FAKE), kw.get("wsb", ws), None]
+    assert f(*ok_args(t=None)) == binding.EINVAL
+    assert f(*ok_args(d=None)) == binding.EINVAL            # T > 0 needs draft logits
+    assert f(*ok_args(u=None)) == binding.EINVAL
+    assert f(*ok_args(T=-0.5)) == binding.EINVAL
+    assert f(*ok_args(T=float("nan"))) == binding.EINVAL
+    assert f(*ok_args(B=0)) == binding.EINVAL
+    assert f(*ok_args(g=0)) == binding.EINVAL
+    assert f(*ok_args(g=99)) == binding.EUNSUPPORTED
+    assert f(*ok_args(wsb=ws - 1)) == binding.EWORKSPACE
+    assert f(*ok_args(ws=None)) == binding.EWORKSPACE
+
+
+def test_attention_argument_checks(lib):
+    f = lib.massv_verify_attention
+    good = binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16)
+    need = lib.massv_verify_attention_workspace(C.byref(good))
+    assert need > 0
+    call = lambda d, q=FAKE, wsb=need: f(C.byref(d), q, FAKE, FAKE, FAKE, FAKE, FAKE, wsb, None)
+    assert call(good, q=None) == binding.EINVAL
+    assert call(good, wsb=need - 1) == binding.EWORKSPACE
+    bad = binding.attn_desc(2, 6, 28, 5, 128, 2080, binding.BF16)        # 28 % 5 != 0
+    assert call(bad) == binding.EINVAL and lib.massv_verify_attention_workspace(C.byref(bad)) == 0
+    assert call(binding.attn_desc(2, 6, 28, 4, 128, 2070, binding.BF16)) == binding.EINVAL     # l_max % 32
+    assert call(binding.attn_desc(2, 6, 28, 4, 96, 2080, binding.BF16)) == binding.EUNSUPPORTED
+    assert call(binding.attn_desc(2, 12, 28, 4, 128, 2080, binding.BF16)) == binding.EUNSUPPORTED  # 84 stacked rows
+    assert call(binding.attn_desc(2, 6, 28, 4, 128, 2080, 7)) == binding.EINVAL
+    assert call(binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16, scale=-1.0)) == binding.EINVAL
+
+
+def test_layer_and_lm_head_argument_checks(lib):
+    cfg = binding.LayerConfig(3584, 28, 4, 128, 18944)
+    d = binding.layer_desc(cfg, 8, 6, 2080, binding.BF16)
+    need = lib.massv_verify_layer_workspace(C.byref(d))
+    assert need > 0
+    w = binding.LayerWeights(*([0x1000] * 12))
+    f = lib.massv_verify_layer
+    assert f(C.byref(d), C.byref(w), None, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == binding.EINVAL
+    assert f(C.byref(d), C.byref(w), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, need - 1, None) == binding.EWORKSPACE
+    w2 = binding.LayerWeights(*([0x1000] * 12)); w2.bq = None
+    assert f(C.byref(d), C.byref(w2), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, need, None) == binding.EINVAL
+    big = binding.layer_desc(cfg, 16, 6, 2080, binding.BF16)             # M = 96 rows
+    assert f(C.byref(big), C.byref(w), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == binding.EUNSUPPORTED
+    odd = binding.layer_desc(binding.LayerConfig(3584, 28, 4, 128, 18950), 1, 6, 2080, binding.BF16)
+    assert f(C.byref(odd), C.byref(w), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == binding.EUNSUPPORTED
+
+    g = lib.massv_lm_head_logits
+    need = lib.massv_lm_head_logits_workspace(48, 3584, 152064, binding.BF16)
+    assert need >= 48 * 3584 * 2
+    assert g(None, FAKE, FAKE, FAKE, 48, 3584, 152064, 1e-6, binding.BF16, FAKE, need, None) == binding.EINVAL
+    assert g(FAKE, FAKE, FAKE, FAKE, 48, 3584, 152064, 1e-6, binding.BF16, FAKE, need - 1, None) == binding.EWORKSPACE
+    assert g(FAKE, FAKE, FAKE, FAKE, 65, 3584, 152064, 1e-6, binding.BF16, FAKE, 1 << 30, None) == binding.EUNSUPPORTED
+    assert g(FAKE, FAKE, FAKE, FAKE, 48, 3584, 152065, 1e-6, binding.BF16, FAKE, 1 << 30, None) == binding.EUNSUPPORTED
+    assert g(FAKE, FAKE, FAKE, FAKE, 0, 3584, 152064, 1e-6, binding.BF16, FAKE, need, None) == binding.EINVAL
+
+
+def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.load()

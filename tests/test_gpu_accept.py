@@ -1,0 +1,134 @@
+"""GPU parity of spec_accept against the CPU checker on shared logits, tokens
+and uniforms (paper Section 2.1).  Integer outputs are compared bit-exactly.
+
+Where a floating-point comparison decides a token (the accept test u < p/q and
+the inverse-CDF draw) the checker reports how far that comparison was from
+flipping.  Sequences whose margin exceeds TOL must match exactly; for the few
+below it the GPU's choice must still be a valid answer once the threshold is
+moved by TOL (the neighbouring token of the cumulative distribution)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import verify_oracle as O
+from paper_2505_10526_amd import synth, binding
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4          # relative decision margin above which results must be identical
+
+
+def run_gpu(a, temperature):
+    dev = "cuda:0"
+    t = torch.from_numpy(a.target_logits).to(dev)
+    d = torch.from_numpy(a.draft_logits).to(dev) if temperature > 0 else None
+    x = torch.from_numpy(a.draft_tokens).to(dev)
+    u = torch.from_numpy(a.uniforms).to(dev) if temperature > 0 else None
+    n, out = binding.spec_accept(t, d, x, u, temperature)
+    torch.cuda.synchronize()
+    return n.cpu().numpy(), out.cpu().numpy()
+
+
+def check(a, temperature, min_exact=0.8):
+    temperature = float(np.float32(temperature))
+    n_g, out_g = run_gpu(a, temperature)
+    n_o, out_o, margin, masses = O.spec_accept(a.target_logits, a.draft_logits, a.draft_tokens, a.uniforms,
+                                               temperature, return_final_mass=True)
+    B, Q = out_o.shape
+    if temperature == 0:
+        assert np.array_equal(n_g, n_o)
+        assert np.array_equal(out_g, out_o)
+        return n_o
+    assert np.all(margin[:, 0] > TOL), "pick another seed: an accept comparison is too close to call"
+    assert np.array_equal(n_g, n_o)
+    exact = 0
+    for b in range(B):
+        n = int(n_o[b])
+        assert np.array_equal(out_g[b, :n], out_o[b, :n])
+        assert np.all(out_g[b, n + 1:] == -1)
+        k = int(out_g[b, n])
+        if margin[b, 1] > TOL:
+            assert k == out_o[b, n], (b, k, out_o[b, n], margin[b])
+            exact += 1
+        else:
+            r = masses[b]
+            c = np.cumsum(r)
+            thr = float(a.uniforms[b, Q - 1]) * c[-1]
+            lo = c[k - 1] if k > 0 else 0.0
+            assert 0 <= k < len(r) and r[k] > 0
+            assert lo - TOL * c[-1] <= thr <= c[k] + TOL * c[-1], (b, k, out_o[b, n])
+    assert exact >= min_exact * B
+    return n_o
+
+
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_tiny_config(temperature):
+    """B=1, gamma=5, V=4096, draft = target + N(0,1)."""
+    for seed in range(4):
+        a = synth.accept_inputs(1, 5, 4096, temperature, seed=seed, noise_std=1.0)
+        check(a, temperature, min_exact=0.0)
+
+
+@pytest.mark.parametrize("temperature", [0.0, 1.0, 0.7])
+@pytest.mark.parametrize("V", [152064, 4096 + 5, 1000, 262144])
+def test_vocab_sizes_and_ragged_tail(V, temperature):
+    a = synth.accept_inputs(3, 5, V, temperature, seed=11, target_std=2.0, noise_std=1.5)
+    check(a, temperature, min_exact=0.0)
+
+
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_peaked_logits_cover_every_accept_length(temperature):
+    a = synth.accept_inputs(48, 5, 8192, temperature, seed=5, noise_std=1.0, peak=6.0)
+    n = check(a, temperature)
+    assert set(np.unique(n)) == set(range(6))
+
+
+def test_long_context_stress_shape():
+    """B=32, gamma=7, V=152064, correlated logits, T=0.7."""
+    a = synth.accept_inputs(32, 7, 152064, 0.7, seed=0, target_std=3.0, corr=0.8)
+    check(a, 0.7)
+
+
+def test_ties_resolve_to_lowest_index():
+    a = synth.accept_inputs(4, 3, 20000, 0.0, seed=2)
+    t = synth.bf16_representable(a.target_logits)         # bf16-valued logits tie often
+    t[:, :, 17] = t.max() + 1
+    t[:, :, 9000] = t[:, :, 17]
+    t[:, :, 19999] = t[:, :, 17]
+    a.target_logits = t
+    a.draft_tokens[:, 0] = 17
+    a.draft_tokens[:, 1] = 9000
+    n, out = run_gpu(a, 0.0)
+    assert np.all(n == 1) and np.all(out[:, 0] == 17) and np.all(out[:, 1] == 17)
+    check(a, 0.0)
+
+
+def test_identical_and_disjoint_distributions():
+    V, gamma, B = 5000, 4, 6
+    a = synth.accept_inputs(B, gamma, V, 1.0, seed=3)
+    a.draft_logits = a.target_logits[:, :gamma].copy()            # p == q: everything accepted
+    n, out = run_gpu(a, 1.0)
+    assert np.all(n == gamma)
+    check(a, 1.0, min_exact=0.0)
+    t = np.full((B, gamma + 1, V), -np.inf, dtype=np.float32)      # disjoint supports: reject at once
+    d = np.full((B, gamma, V), -np.inf, dtype=np.float32)
+    t[:, :, : V // 2] = a.target_logits[:, :, : V // 2]
+    d[:, :, V // 2:] = a.target_logits[:, :gamma, V // 2:]
+    a.target_logits, a.draft_logits = t, d
+    a.draft_tokens = synth.draft_tokens_from(d, 1.0, 9)
+    n, out = run_gpu(a, 1.0)
+    assert np.all(n == 0) and np.all(out[:, 0] < V // 2)
+    check(a, 1.0, min_exact=0.0)
+
+
+def test_out_of_range_draft_token_is_rejected():
+    a = synth.accept_inputs(2, 3, 3000, 0.0, seed=4)
+    a.draft_tokens[:] = np.array([[-1, 0, 0], [3000, 0, 0]], dtype=np.int32)
+    n, out = run_gpu(a, 0.0)
+    assert np.all(n == 0)
+
+
+def test_repeatable_bits():
+    a = synth.accept_inputs(8, 5, 152064, 1.0, seed=6, noise_std=1.5)
+    r1 = run_gpu(a, 1.0)
+    r2 = run_gpu(a, 1.0)
+    assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1])

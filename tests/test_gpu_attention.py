@@ -1,0 +1,117 @@
+"""GPU parity of verify_attention against the CPU checker (paper Section 2.1:
+gamma+1 positions scored in one parallel pass over the KV cache whose prefix
+holds image-token then text positions)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import verify_oracle as O
+from paper_2505_10526_amd import synth, binding
+from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2      # max |err| / max |ref|, the bound set for bf16 activations
+TOL_F32 = 2e-5       # fp32 path: fp32 accumulation over <= 300 keys of O(1) values
+
+
+def run_case(shape, B, Q, kv_len, n_img, seed, std=1.0, hot_keys=0, l_max=None, q_std=1.0, nan_tail=False):
+    kv = synth.kv_cache(shape, B, Q, kv_len, n_img, seed, std=std, hot_keys=hot_keys)
+    # the step's own rows: new keys / values at [kv_len, kv_len+Q)
+    newk = synth.normal((B, shape.n_kv_heads, Q, shape.head_dim), std, seed, 77, dtype=shape.dtype)
+    newv = synth.normal((B, shape.n_kv_heads, Q, shape.head_dim), std, seed, 78, dtype=shape.dtype)
+    for b in range(B):
+        L = int(kv.kv_len[b])
+        kv.k[b, :, L:L + Q] = newk[b]
+        kv.v[b, :, L:L + Q] = newv[b]
+        if nan_tail:
+            kv.k[b, :, L + Q:] = np.nan
+            kv.v[b, :, L + Q:] = np.nan
+    q = synth.queries(shape, B, Q, seed, std=q_std)
+    ref = O.attention(q, kv.k, kv.v, kv.kv_len)
+    lm = round_up(l_max or kv.l_max, 32)
+    kd = to_dev(pad_rows(kv.k, lm), shape.dtype)
+    vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), shape.dtype))
+    out = binding.verify_attention(to_dev(q, shape.dtype), kd, vd, i32(kv.kv_len))
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), ref
+
+
+def test_tiny_fp32_config():
+    """B=1, gamma=5, KV prefix 256 (64 image rows), 4 q / 2 kv heads, d=64, K,V ~ N(0, 0.02)."""
+    got, ref = run_case(synth.TINY, 1, 6, [256], [64], seed=0, std=0.02)
+    assert_close(got, ref, TOL_F32, "tiny fp32")
+
+
+def test_tiny_fp32_rescale_variant():
+    """Same shape with K,V ~ N(0,1) and a few keys scaled by 8: the running maximum moves late."""
+    got, ref = run_case(synth.TINY, 2, 6, [256, 300], [64, 10], seed=1, std=1.0, hot_keys=3)
+    assert_close(got, ref, TOL_F32, "tiny fp32 hot keys")
+
+
+@pytest.mark.parametrize("kv_len", [[0], [1], [26], [27], [31], [32], [250], [256], [1000]])
+def test_bf16_ragged_lengths_d64(kv_len):
+    """Block boundaries of 32 keys, an empty cache, lengths that end inside / at a block."""
+    s = synth.LayerShape(256, 4, 2, 64, 704, 4096, dtype="bf16")
+    got, ref = run_case(s, 1, 6, kv_len, [min(kv_len[0], 64)], seed=2, hot_keys=2 if kv_len[0] > 4 else 0, nan_tail=True)
+    assert_close(got, ref, TOL_BF16, f"bf16 d64 kv_len={kv_len}")
+
+
+def test_qwen7b_shape_single_sequence():
+    """28 q / 4 kv heads, d=128, gamma=5, KV 1024 (700 image rows)."""
+    got, ref = run_case(synth.QWEN7B, 1, 6, [1024], [700], seed=3, hot_keys=2)
+    assert_close(got, ref, TOL_BF16, "qwen7b B=1")
+
+
+def test_qwen7b_shape_ragged_batch():
+    """B=8, per-sequence lengths in [1024, 2048] with 256-1024 leading image rows; one
+    allocation size for all, rows past each sequence's end hold NaN."""
+    rng = np.random.default_rng(4)
+    kv_len = rng.integers(1024, 2049, 8)
+    n_img = rng.integers(256, 1025, 8)
+    got, ref = run_case(synth.QWEN7B, 8, 6, kv_len, n_img, seed=4, hot_keys=2, nan_tail=True)
+    assert_close(got, ref, TOL_BF16, "qwen7b B=8 ragged")
+
+
+def test_gemma12b_shape():
+    """16 q / 8 kv heads, d=256, B=4 (two sequences checked against the checker at full length 4096)."""
+    got, ref = run_case(synth.GEMMA12B, 2, 6, [4096, 4000], [256, 256], seed=5, hot_keys=2, nan_tail=True)
+    assert_close(got, ref, TOL_BF16, "gemma12b")
+
+
+def test_long_context_gamma7():
+    """gamma=7 (56 stacked query rows), KV 8192 with 1280 image rows."""
+    got, ref = run_case(synth.QWEN7B, 2, 8, [8192, 5000], [1280, 1280], seed=6, hot_keys=3, nan_tail=True)
+    assert_close(got, ref, TOL_BF16, "long context")
+
+
+def test_parallel_pass_equals_sequential_decode_on_gpu():
+    """The Q-query pass equals Q single-query calls with a growing cache (Section 2.1)."""
+    s = synth.QWEN7B
+    B, Q = 2, 6
+    kv = synth.kv_cache(s, B, Q, [300, 77], [100, 10], 7, junk_tail=False)
+    q = synth.queries(s, B, Q, 7)
+    lm = round_up(kv.l_max, 32)
+    kd = to_dev(pad_rows(kv.k, lm), "bf16")
+    vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), "bf16"))
+    qd = to_dev(q, "bf16")
+    par = binding.verify_attention(qd, kd, vd, i32(kv.kv_len)).float().cpu().numpy()
+    for i in range(Q):
+        one = binding.verify_attention(qd[:, i:i + 1].contiguous(), kd, vd, i32(kv.kv_len + i)).float().cpu().numpy()
+        # same keys, same per-row arithmetic up to how the key range is cut into splits
+        np.testing.assert_allclose(one[:, 0], par[:, i], rtol=2e-2, atol=2e-3)
+
+
+def test_repeatable_bits_and_pack_roundtrip():
+    s = synth.QWEN7B
+    kv = synth.kv_cache(s, 2, 6, [500, 333], [100, 100], 8, junk_tail=False)
+    q = to_dev(synth.queries(s, 2, 6, 8), "bf16")
+    lm = round_up(kv.l_max, 32)
+    kd = to_dev(pad_rows(kv.k, lm), "bf16")
+    vrow = to_dev(np.nan_to_num(pad_rows(kv.v, lm)), "bf16")
+    vd = binding.v_cache_pack(vrow)
+    from helpers import v_blocked_to_rows
+    assert torch.equal(v_blocked_to_rows(vd), vrow)
+    a = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
+    b = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
+    assert torch.equal(a, b)

@@ -1,0 +1,114 @@
+"""GPU parity of verify_layer and lm_head_logits against the CPU checker."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import verify_oracle as O
+from paper_2505_10526_amd import synth, binding
+from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close, v_blocked_to_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+TOL_F32 = 5e-5      # fp32 path; sums of up to 688 products, fp32 accumulation in a different order
+
+
+def cfg_of(s):
+    return binding.LayerConfig(s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.mlp, s.act, s.qkv_bias,
+                               s.norm_eps, s.rope_theta)
+
+
+def run_layer(s, B, Q, kv_len, n_img, seed, kv_std=1.0, compress=True, w_std=0.02):
+    w = synth.layer_weights(s, seed, std=w_std)
+    kv = synth.kv_cache(s, B, Q, kv_len, n_img, seed, std=kv_std, hot_keys=1)
+    x = synth.hidden_states(s, B, Q, seed)
+    pos = synth.positions(kv.kv_len, kv.n_img, Q, compress_image=compress)
+    y_ref, k_ref, v_ref = O.verify_layer(s, w, x, pos, kv.k, kv.v, kv.kv_len)
+    lm = round_up(kv.l_max, 32)
+    kd = to_dev(pad_rows(kv.k, lm), s.dtype)
+    vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype))
+    wd = {k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()}
+    xd = to_dev(x, s.dtype)
+    binding.verify_layer(cfg_of(s), wd, xd, i32(pos), kd, vd, i32(kv.kv_len))
+    torch.cuda.synchronize()
+    tol = TOL_BF16 if s.dtype == "bf16" else TOL_F32
+    assert_close(xd.float().cpu().numpy(), y_ref, tol, "layer output")
+    kg = kd.float().cpu().numpy()
+    vg = v_blocked_to_rows(vd).float().cpu().numpy()
+    for b in range(B):
+        L = int(kv.kv_len[b])
+        assert_close(kg[b, :, L:L + Q], k_ref[b, :, L:L + Q], tol, "appended keys")
+        assert_close(vg[b, :, L:L + Q], v_ref[b, :, L:L + Q], tol, "appended values")
+        # the cached prefix is untouched
+        assert np.array_equal(kg[b, :, :L], kv.k[b, :, :L])
+        assert np.array_equal(vg[b, :, :L], kv.v[b, :, :L])
+    return xd
+
+
+def test_tiny_fp32_layer():
+    """Config 1: hidden 256, 4/2 heads, d=64, SwiGLU 688, fp32, KV prefix 256 (64 image rows)."""
+    run_layer(synth.TINY, 1, 6, [256], [64], seed=0, kv_std=0.02)
+    run_layer(synth.TINY, 2, 6, [256, 100], [64, 30], seed=1, kv_std=1.0, w_std=0.05)
+
+
+def test_tiny_bf16_layer():
+    run_layer(synth.TINY_BF16, 1, 6, [256], [64], seed=2, w_std=0.05)
+    run_layer(synth.TINY_BF16, 3, 4, [40, 0, 95], [8, 0, 64], seed=3, w_std=0.05)
+
+
+def test_qwen7b_layer_b1():
+    """Config 2: one Qwen2.5-VL-7B-shaped layer, B=1, gamma=5, KV 1024 (700 image rows)."""
+    run_layer(synth.QWEN7B, 1, 6, [1024], [700], seed=4)
+
+
+def test_qwen7b_layer_b8_ragged():
+    """Config 3's layer shape: B=8 (M=48), ragged lengths.  Shorter caches than 1024-2048 keep the
+    checker's run time in seconds; the full lengths are covered by the attention tests."""
+    rng = np.random.default_rng(5)
+    run_layer(synth.QWEN7B, 8, 6, rng.integers(100, 400, 8), rng.integers(20, 100, 8), seed=5)
+
+
+def test_gemma12b_layer_b4():
+    """Config 4's layer: hidden 3840, 16/8 heads, d=256, GeGLU 15360, no bias, B=4 (M=24)."""
+    run_layer(synth.GEMMA12B, 4, 6, [300, 256, 50, 411], [256, 200, 10, 256], seed=6)
+
+
+@pytest.mark.parametrize("shape,M", [(synth.TINY, 6), (synth.TINY_BF16, 6), (synth.TINY_BF16, 48)])
+def test_lm_head_small(shape, M):
+    lw = synth.lm_head_weights(shape, 7, std=0.05)
+    x = synth.normal((M, shape.hidden), 1.0, 7, 60, dtype=shape.dtype)
+    ref = O.lm_head_logits(x, lw["final_norm"], lw["w_lm"], shape.norm_eps)
+    got = binding.lm_head_logits(to_dev(x, shape.dtype), to_dev(lw["final_norm"], shape.dtype),
+                                 to_dev(lw["w_lm"], shape.dtype), shape.norm_eps)
+    assert_close(got.cpu().numpy(), ref, TOL_BF16 if shape.dtype == "bf16" else TOL_F32, "logits")
+    ref2 = O.lm_head_logits(x, None, lw["w_lm"], shape.norm_eps)
+    got2 = binding.lm_head_logits(to_dev(x, shape.dtype), None, to_dev(lw["w_lm"], shape.dtype))
+    assert_close(got2.cpu().numpy(), ref2, TOL_BF16 if shape.dtype == "bf16" else TOL_F32, "logits no norm")
+
+
+@pytest.mark.parametrize("shape,M", [(synth.QWEN7B, 6), (synth.QWEN7B, 48), (synth.GEMMA12B, 24)])
+def test_lm_head_full_vocab(shape, M):
+    """lm_head at the real vocabulary (152064 / 262144 rows)."""
+    lw = synth.lm_head_weights(shape, 8)
+    x = synth.normal((M, shape.hidden), 1.0, 8, 60, dtype=shape.dtype)
+    ref = O.lm_head_logits(x, lw["final_norm"], lw["w_lm"], shape.norm_eps)
+    got = binding.lm_head_logits(to_dev(x, shape.dtype), to_dev(lw["final_norm"], shape.dtype),
+                                 to_dev(lw["w_lm"], shape.dtype), shape.norm_eps)
+    assert_close(got.cpu().numpy(), ref, TOL_BF16, "logits")
+
+
+def test_layer_repeatable_bits():
+    s = synth.QWEN7B
+    w = {k: (None if v is None else to_dev(v, s.dtype)) for k, v in synth.layer_weights(s, 9).items()}
+    kv = synth.kv_cache(s, 2, 6, [64, 200], [10, 50], 9, junk_tail=False)
+    pos = i32(synth.positions(kv.kv_len, kv.n_img, 6))
+    outs = []
+    for _ in range(2):
+        lm = round_up(kv.l_max, 32)
+        kd = to_dev(pad_rows(kv.k, lm), s.dtype)
+        vd = binding.v_cache_pack(to_dev(np.nan_to_num(pad_rows(kv.v, lm)), s.dtype))
+        x = to_dev(synth.hidden_states(s, 2, 6, 9), s.dtype)
+        binding.verify_layer(cfg_of(s), w, x, pos, kd, vd, i32(kv.kv_len))
+        outs.append((x.clone(), kd.clone(), vd.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(torch.nan_to_num(a.float()), torch.nan_to_num(b.float()))
