@@ -1,0 +1,326 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding verify step on one MI355X.
+
+One "step" is one whole verify step: 28 decoder layers over the B*(gamma+1)
+new positions, the vocabulary projection, and accept / resample -- every call
+goes through the C ABI of libmassv_verify.so.  Inputs are synthetic and
+resident in HBM before the timed region.
+
+    python bench.py [--steps K] [--warmup W] [--workload NAME] [--no-extra] [--no-cpu]
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen7b_full",
+                    choices=["qwen7b_full", "qwen7b_layer", "gemma12b_layer"])
+    ap.add_argument("--layers", type=int, default=None, help="override the layer count (debugging)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the attention/accept bandwidth section")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU checker timing")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+WORKLOADS = {
+    # BASELINE config 3: full 28-layer Qwen2.5-VL-7B-shaped verify step
+    "qwen7b_full": dict(shape="QWEN7B", layers=28, batch=8, gamma=5, kv_lo=1024, kv_hi=2048,
+                        img_lo=256, img_hi=1024, noise=1.5, temperature=0.0,
+                        label="Qwen2.5-VL-7B-shaped full verify step: 28 layers + lm_head + accept, "
+                              "B=8, gamma=5, kv_len U[1024,2048], 256-1024 image rows, T=0"),
+    # BASELINE config 2: one layer + lm_head + accept, B=1
+    "qwen7b_layer": dict(shape="QWEN7B", layers=1, batch=1, gamma=5, kv_lo=1024, kv_hi=1024,
+                         img_lo=700, img_hi=700, noise=1.5, temperature=0.0,
+                         label="one Qwen2.5-VL-7B-shaped layer + lm_head + accept, B=1, gamma=5, KV 1024, T=0"),
+    # BASELINE config 4
+    "gemma12b_layer": dict(shape="GEMMA12B", layers=1, batch=4, gamma=5, kv_lo=4096, kv_hi=4096,
+                           img_lo=256, img_hi=256, noise=2.0, temperature=0.0,
+                           label="one Gemma3-12B-shaped layer + lm_head + accept, B=4, gamma=5, KV 4096, T=0"),
+}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_10526_amd import binding, synth
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_10526_amd import build
+        build.build(verbose=False)
+    binding.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = dict(WORKLOADS[args.workload])
+    if args.layers:
+        wl["layers"] = args.layers
+    shape = getattr(synth, wl["shape"])
+    B, gamma, N = wl["batch"], wl["gamma"], wl["layers"]
+    Q, M = gamma + 1, wl["batch"] * (gamma + 1)
+    H, F, V, d = shape.hidden, shape.mlp, shape.vocab, shape.head_dim
+    nq, nkv = shape.n_q_heads * d, shape.n_kv_heads * d
+
+    # ---------------- synthetic inputs, generated on the device ----------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    bf = torch.bfloat16
+
+    def randn(*s, std=1.0, mean=0.0):
+        return (torch.randn(*s, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(bf)
+
+    rng = np.random.default_rng(args.seed)
+    kv_len_h = rng.integers(wl["kv_lo"], wl["kv_hi"] + 1, B).astype(np.int32)
+    n_img_h = rng.integers(wl["img_lo"], wl["img_hi"] + 1, B).astype(np.int32)
+    l_max = (int(wl["kv_hi"]) + Q + 31) // 32 * 32
+    kv_len = torch.from_numpy(kv_len_h).to(dev)
+    pos = torch.from_numpy(synth.positions(kv_len_h, n_img_h, Q)).to(dev)
+
+    layers = []
+    for _ in range(N):
+        w = {"ln1": randn(H, std=0.1, mean=1.0), "wq": randn(nq, H, std=0.02), "wk": randn(nkv, H, std=0.02),
+             "wv": randn(nkv, H, std=0.02), "wo": randn(H, nq, std=0.02), "ln2": randn(H, std=0.1, mean=1.0),
+             "wg": randn(F, H, std=0.02), "wu": randn(F, H, std=0.02), "wd": randn(H, F, std=0.02),
+             "bq": None, "bk": None, "bv": None}
+        if shape.qkv_bias:
+            w.update(bq=randn(nq, std=0.02), bk=randn(nkv, std=0.02), bv=randn(nkv, std=0.02))
+        kc = randn(B, shape.n_kv_heads, l_max, d)
+        vc = binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d))
+        for b in range(B):                       # image rows carry a wider spread (input recipe)
+            kc[b, :, : int(n_img_h[b])] *= 1.5
+        layers.append((w, binding.layer_weights(w), kc, vc))
+    final_norm = randn(H, std=0.1, mean=1.0)
+    w_lm = randn(V, H, std=0.02)
+    x0 = randn(B, Q, H)
+    x = torch.empty_like(x0)
+    logits = torch.empty((M, V), dtype=torch.float32, device=dev)
+    n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    out_tok = torch.empty((B, Q), dtype=torch.int32, device=dev)
+
+    cfg = binding.LayerConfig(H, shape.n_q_heads, shape.n_kv_heads, d, F, shape.act, shape.qkv_bias,
+                              shape.norm_eps, shape.rope_theta)
+    desc = binding.layer_desc(cfg, B, Q, l_max, binding.BF16)
+    ws_bytes = max(binding.verify_layer_workspace(desc),
+                   binding.load().massv_lm_head_logits_workspace(M, H, V, binding.BF16),
+                   binding.load().massv_spec_accept_workspace(B, gamma, V))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    T = wl["temperature"]
+
+    def forward():
+        x.copy_(x0)
+        for (w, lw, kc, vc) in layers:
+            binding.verify_layer(cfg, w, x, pos, kc, vc, kv_len, ws=ws, desc=desc, lw=lw)
+        binding.lm_head_logits(x.view(M, H), final_norm, w_lm, shape.norm_eps, out=logits, ws=ws)
+
+    # draft logits / tokens: the drafter's output is an INPUT of the verify step.  It is derived once from the
+    # target logits (target + N(0, noise)), outside the timed region.
+    forward()
+    torch.cuda.synchronize()
+    tl = logits.view(B, Q, V)
+    draft_logits = (tl[:, :gamma] + torch.randn(B, gamma, V, generator=gen, device=dev) * wl["noise"]).contiguous()
+    draft_tokens = draft_logits.argmax(-1).to(torch.int32).contiguous()
+    uniforms = torch.rand(B, Q, generator=gen, device=dev).clamp_(max=1 - 2 ** -24)
+
+    def step():
+        forward()
+        binding.spec_accept(tl, draft_logits if T > 0 else None, draft_tokens, uniforms if T > 0 else None, T,
+                            n_accepted=n_acc, out_tokens=out_tok, ws=ws)
+
+    # ---------------- timed region ----------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # one gate/up launch per step is bracketed by events (rotating over layers) -> live kernel duration
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in ev:
+        a.record(); b.record()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        x.copy_(x0)
+        for li, (w, lw, kc, vc) in enumerate(layers):
+            if li == s % N:
+                binding.trace_kernel(binding.K_GATEUP, ev[s][0], ev[s][1])
+            binding.verify_layer(cfg, w, x, pos, kc, vc, kv_len, ws=ws, desc=desc, lw=lw)
+        binding.lm_head_logits(x.view(M, H), final_norm, w_lm, shape.norm_eps, out=logits, ws=ws)
+        binding.spec_accept(tl, draft_logits if T > 0 else None, draft_tokens, uniforms if T > 0 else None, T,
+                            n_accepted=n_acc, out_tokens=out_tok, ws=ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    emitted = int((n_acc + 1).sum().item())
+    tokens_per_s = emitted / (ms_per_step * 1e-3)
+    k_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    # ---------------- roofline of the dominant kernel: gate/up projection ----------------
+    gateup_bytes = 2 * F * H * 2 + M * H * 2 + M * F * 2          # Wg, Wu (bf16) + X read + H written
+    weight_bytes_step = N * (nq * H + 2 * nkv * H + H * nq + 3 * F * H) * 2 + V * H * 2
+    achieved = gateup_bytes / (k_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<MT,NT,WK,EPI_GATED> (gate/up projection + activation)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": gateup_bytes, "avg_launch_us": round(k_ms * 1e3, 2),
+                "launches_timed": len(ev),
+                "step_weight_stream_GBps": round(weight_bytes_step / (ms_per_step * 1e-3) / 1e9, 1)}
+
+    result = {
+        "metric": "verified tokens/sec per verify step (7B-shape, gamma=5); attention+accept HBM GB/s",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl["label"], "layers": N, "batch": B, "gamma": gamma, "rows": M,
+                   "kv_len": [int(v) for v in kv_len_h], "l_max": l_max, "temperature": T,
+                   "draft_noise_std": wl["noise"], "launch": "eager, one stream"},
+        "positions_per_s": round(M / (ms_per_step * 1e-3), 1),
+        "mean_emitted_per_sequence": round(emitted / B, 3),
+        "roofline": roofline,
+    }
+
+    if not args.no_extra:
+        result["extra"] = extra_bandwidth(torch, binding, synth, dev, gen)
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, args.seed)
+    print(json.dumps(result))
+
+
+def time_calls(torch, fn, iters, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def extra_bandwidth(torch, binding, synth, dev, gen):
+    """Second half of the metric: HBM GB/s of verify_attention and spec_accept at the long-context
+    batched shape (B=32, gamma=7, KV 8192 bf16, 28/4 heads, d=128, V=152064, T=0.7).  Several
+    buffer sets are rotated so that the 256 MB last-level cache cannot serve the stream."""
+    s = synth.QWEN7B
+    B, gamma, L, V = 32, 7, 8192, s.vocab
+    Q = gamma + 1
+    l_max = (L + Q + 31) // 32 * 32
+    bf = torch.bfloat16
+    sets = 3
+    qs = [torch.randn(B, Q, s.n_q_heads, s.head_dim, generator=gen, device=dev).to(bf) for _ in range(sets)]
+    ks = [torch.randn(B, s.n_kv_heads, l_max, s.head_dim, generator=gen, device=dev).to(bf) for _ in range(sets)]
+    vs = [binding.v_cache_pack(torch.randn(B, s.n_kv_heads, l_max, s.head_dim, generator=gen, device=dev).to(bf))
+          for _ in range(sets)]
+    kv_len = torch.full((B,), L, dtype=torch.int32, device=dev)
+    out = torch.empty_like(qs[0])
+    it = [0]
+
+    def attn():
+        i = it[0] % sets
+        it[0] += 1
+        binding.verify_attention(qs[i], ks[i], vs[i], kv_len, out=out)
+
+    attn_ms = time_calls(torch, attn, 30)
+    attn_bytes = B * 2 * (L + Q) * s.n_kv_heads * s.head_dim * 2
+    del qs, ks, vs
+
+    T = float(np.float32(0.7))
+    tls, dls = [], []
+    for _ in range(2):
+        t = torch.randn(B, Q, V, generator=gen, device=dev) * 3.0
+        dl = 0.8 * t[:, :gamma] + 0.6 * 3.0 * torch.randn(B, gamma, V, generator=gen, device=dev)
+        tls.append(t.contiguous()); dls.append(dl.contiguous())
+    toks = dls[0].argmax(-1).to(torch.int32)
+    u = torch.rand(B, Q, generator=gen, device=dev).clamp_(max=1 - 2 ** -24)
+    n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    out_tok = torch.empty((B, Q), dtype=torch.int32, device=dev)
+
+    def acc_t():
+        i = it[0] % 2
+        it[0] += 1
+        binding.spec_accept(tls[i], dls[i], toks, u, T, n_accepted=n_acc, out_tokens=out_tok)
+
+    def acc_0():
+        i = it[0] % 2
+        it[0] += 1
+        binding.spec_accept(tls[i], None, toks, None, 0.0, n_accepted=n_acc, out_tokens=out_tok)
+
+    acc_ms = time_calls(torch, acc_t, 30)
+    acc0_ms = time_calls(torch, acc_0, 30)
+    acc_bytes = B * Q * V * 4 + B * gamma * V * 4 + B * 2 * V * 4
+    acc0_bytes = B * Q * V * 4
+    gb = lambda nbytes, ms: round(nbytes / (ms * 1e-3) / 1e9, 1)
+    return {
+        "workload": "long-context batched: B=32, gamma=7, KV 8192 bf16, 28/4 heads, d=128, V=152064",
+        "verify_attention": {"us": round(attn_ms * 1e3, 1), "GBps": gb(attn_bytes, attn_ms),
+                             "frac_of_8TBps": round(gb(attn_bytes, attn_ms) / HBM_PEAK_GBS, 4), "bytes": attn_bytes},
+        "spec_accept_T0.7": {"us": round(acc_ms * 1e3, 1), "GBps": gb(acc_bytes, acc_ms),
+                             "frac_of_8TBps": round(gb(acc_bytes, acc_ms) / HBM_PEAK_GBS, 4), "bytes": acc_bytes},
+        "spec_accept_T0": {"us": round(acc0_ms * 1e3, 1), "GBps": gb(acc0_bytes, acc0_ms),
+                           "frac_of_8TBps": round(gb(acc0_bytes, acc0_ms) / HBM_PEAK_GBS, 4), "bytes": acc0_bytes},
+    }
+
+
+def cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, seed):
+    """The CPU checker, as it stands, on a bounded sample of the same workload: ONE decoder layer
+    over all sequences, the vocabulary projection and the accept step; the layer's time is scaled
+    by the layer count."""
+    from oracle import verify_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    B, gamma, N = wl["batch"], wl["gamma"], wl["layers"]
+    Q = gamma + 1
+    w = synth.layer_weights(shape, seed)
+    kv = synth.kv_cache(shape, B, Q, kv_len_h, n_img_h, seed, junk_tail=False)
+    x = synth.hidden_states(shape, B, Q, seed)
+    pos = synth.positions(kv_len_h, n_img_h, Q)
+    t0 = time.perf_counter()
+    y, _, _ = O.verify_layer(shape, w, x, pos, kv.k, kv.v, kv.kv_len)
+    t_layer = time.perf_counter() - t0
+    del w, kv
+    lw = synth.lm_head_weights(shape, seed)
+    t0 = time.perf_counter()
+    logits = O.lm_head_logits(y.reshape(B * Q, -1), lw["final_norm"], lw["w_lm"], shape.norm_eps)
+    t_lm = time.perf_counter() - t0
+    del lw
+    a = synth.accept_inputs(B, gamma, shape.vocab, wl["temperature"], seed, noise_std=wl["noise"],
+                            target_logits=logits.astype(np.float32))
+    t0 = time.perf_counter()
+    n, _, _ = O.spec_accept(a.target_logits, a.draft_logits, a.draft_tokens, a.uniforms, wl["temperature"])
+    t_acc = time.perf_counter() - t0
+    t_step = N * t_layer + t_lm + t_acc
+    return {"value": round(float((n + 1).sum()) / t_step, 3), "unit": "tokens/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"1 of {N} layers (all {B} sequences) timed {t_layer:.2f}s and scaled x{N}, "
+                      f"+ lm_head {t_lm:.2f}s + accept {t_acc:.2f}s; float64 NumPy",
+            "est_ms_per_step": round(t_step * 1e3, 1)}
+
+
+if __name__ == "__main__":
+    main()

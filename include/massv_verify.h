@@ -209,6 +209,30 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
                       int32_t* n_accepted, int32_t* out_tokens,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------- */
+/* Timing hook (diagnostic; for callers that want one kernel's duration        */
+/* without a profiler).  Arms a one-shot request on the CALLING THREAD: the    */
+/* next launch of kernel `kernel_id` made by a library call from this thread   */
+/* is bracketed by hipEventRecord(start_event) / hipEventRecord(stop_event) on */
+/* that call's stream, after which the request is gone.  Events are            */
+/* hipEvent_t created by the caller with timing enabled; the caller            */
+/* synchronises and reads hipEventElapsedTime.  kernel_id < 0 disarms.         */
+/* Do not arm while the stream is being captured into a graph.                 */
+/* ------------------------------------------------------------------------- */
+typedef enum {
+    MASSV_K_QKV = 0,          /* fused q/k/v projection of verify_layer */
+    MASSV_K_ATTENTION = 1,    /* the split-KV attention kernel */
+    MASSV_K_ATTN_COMBINE = 2, /* merge of the KV splits */
+    MASSV_K_OPROJ = 3,        /* output projection + residual */
+    MASSV_K_GATEUP = 4,       /* gate/up projection + activation */
+    MASSV_K_DOWN = 5,         /* down projection + residual */
+    MASSV_K_LMHEAD = 6,       /* vocabulary projection of lm_head_logits */
+    MASSV_K_ACCEPT_STATS = 7, /* pass 1 of spec_accept over all logit rows */
+    MASSV_K_RESIDUAL_MASS = 8 /* pass 2 of spec_accept over the resampled rows */
+} massv_kernel_id;
+
+int massv_trace_kernel(int kernel_id, void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

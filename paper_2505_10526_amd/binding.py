@@ -27,8 +27,9 @@ EXPORTS = [
     "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack",
     "massv_verify_layer_workspace", "massv_verify_layer",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
-    "massv_spec_accept_workspace", "massv_spec_accept",
+    "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel",
 ]
+K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS = range(9)
 
 
 class AttnDesc(C.Structure):
@@ -90,6 +91,8 @@ def load():
     lib.massv_spec_accept_workspace.argtypes = [i32, i32, i32]
     lib.massv_spec_accept.restype = C.c_int
     lib.massv_spec_accept.argtypes = [vp, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.massv_trace_kernel.restype = C.c_int
+    lib.massv_trace_kernel.argtypes = [C.c_int, vp, vp]
     _lib = lib
     return lib
 
@@ -285,3 +288,15 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
                                  float(temperature), B, gamma, V, _ptr(n_accepted), _ptr(out_tokens),
                                  _ptr(ws), ws.numel(), _stream()), "massv_spec_accept")
     return n_accepted, out_tokens
+
+
+# ---------------------------------------------------------------------------
+# one-shot kernel timing
+# ---------------------------------------------------------------------------
+def trace_kernel(kernel_id: int, start: "torch.cuda.Event", stop: "torch.cuda.Event"):
+    """Ask the library to record `start` / `stop` around the next launch of one
+    kernel (K_* ids) made from this thread.  Both events must have been created
+    with enable_timing=True and recorded once (torch creates the HIP event on
+    first use)."""
+    _check(load().massv_trace_kernel(int(kernel_id), C.c_void_p(start.cuda_event), C.c_void_p(stop.cuda_event)),
+           "massv_trace_kernel")

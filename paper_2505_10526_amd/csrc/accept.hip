@@ -15,7 +15,7 @@
 //                          sum first exceeds uniform * total.
 // Sums that decide a token are carried in double so that the result does not
 // depend on how the vocabulary was cut into chunks.
-#include "common.h"
+#include "kernels.h"
 
 #include <limits.h>
 
@@ -334,14 +334,18 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
                     (greedy || (uintptr_t)draft_logits % 16 == 0);
     const int rows = greedy ? B * Q : B * (Q + gamma);
 
+    trace_begin(MASSV_K_ACCEPT_STATS, st);
     hipLaunchKernelGGL(accept_stats_kernel, dim3(C, rows), dim3(kAccThreads), 0, st,
                        target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
+    trace_end(MASSV_K_ACCEPT_STATS, st);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kWave), 0, st,
                        target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
                        greedy, part, sel, n_accepted, out_tokens);
     if (!greedy) {
+        trace_begin(MASSV_K_RESIDUAL_MASS, st);
         hipLaunchKernelGGL(residual_mass_kernel, dim3(C, B), dim3(kAccThreads), 0, st,
                            target_logits, draft_logits, gamma, V, C, ts, vec, sel, mass);
+        trace_end(MASSV_K_RESIDUAL_MASS, st);
         hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,
                            target_logits, draft_logits, uniforms, gamma, V, C, ts, sel, mass, out_tokens);
     }

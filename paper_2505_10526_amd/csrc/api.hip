@@ -1,5 +1,5 @@
 // Status strings and ABI version of libmassv_verify.
-#include "common.h"
+#include "kernels.h"
 
 extern "C" const char* massv_status_string(int status) {
     switch (status) {
@@ -13,3 +13,18 @@ extern "C" const char* massv_status_string(int status) {
 }
 
 extern "C" int massv_abi_version(void) { return 1; }
+
+namespace massv {
+TraceRequest& trace_request() {
+    static thread_local TraceRequest req = {-1, nullptr, nullptr};
+    return req;
+}
+}  // namespace massv
+
+extern "C" int massv_trace_kernel(int kernel_id, void* start_event, void* stop_event) {
+    massv::TraceRequest& t = massv::trace_request();
+    if (kernel_id < 0) { t.kid = -1; return MASSV_OK; }
+    if (kernel_id > MASSV_K_RESIDUAL_MASS || !start_event || !stop_event) return MASSV_EINVAL;
+    t.kid = kernel_id; t.start = (hipEvent_t)start_event; t.stop = (hipEvent_t)stop_event;
+    return MASSV_OK;
+}

@@ -34,7 +34,7 @@ struct GemmDev {
     const bf16_t* residual;
     void* y;
     int M, K, ldy;           // ldy: elements per output row
-    int epilogue, act;
+    int act;
 };
 
 __device__ inline float gemm_act(float x, int act) {
@@ -48,14 +48,14 @@ __device__ inline bf16x8 ld8(const bf16_t* p, bool ok) {
     return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
 }
 
-template <int MT, int NT, int WK>
+template <int MT, int NT, int WK, int EPI>
 __global__ __launch_bounds__(WK * kWave)
 void gemm_skinny_kernel(GemmDev g) {
     extern __shared__ floatx4 red[];                 // [WK][NT*MT][64]
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int lr = lane % 16, lc = lane / 16;
     const int K = g.K;
-    const bool gated = (g.epilogue == EPI_GATED);
+    constexpr bool gated = (EPI == EPI_GATED);
 
     // ---- which feature tiles this workgroup owns ----
     const bf16_t* wrow[NT];
@@ -160,7 +160,7 @@ void gemm_skinny_kernel(GemmDev g) {
                     *reinterpret_cast<bf16x4*>((bf16_t*)g.y + (size_t)m * g.ldy + col) = o;
                 }
             } else if (m < g.M) {
-                if (g.epilogue == EPI_LOGITS) {
+                if (EPI == EPI_LOGITS) {
                     *reinterpret_cast<floatx4*>((float*)g.y + (size_t)m * g.ldy + col) = s;
                 } else {
                     const bf16_t* bias = g.bias[seg_of[nt]];
@@ -169,7 +169,7 @@ void gemm_skinny_kernel(GemmDev g) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) s[i] += (float)bv[i];
                     }
-                    if (g.epilogue == EPI_RESIDUAL) {
+                    if (EPI == EPI_RESIDUAL) {
                         const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.residual + (size_t)m * g.ldy + col);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) s[i] += (float)rv[i];
@@ -236,29 +236,46 @@ int gemm_supported(const GemmArgs& g) {
     return MASSV_OK;
 }
 
-template <int MT, int NT, int WK>
+template <int MT, int NT, int WK, int EPI>
 static void launch_skinny(const GemmDev& d, int work_tiles, hipStream_t st) {
-    const int per_wg = (d.epilogue == EPI_GATED) ? NT / 2 : NT;
+    constexpr int per_wg = (EPI == EPI_GATED) ? NT / 2 : NT;
     const int grid = (work_tiles + per_wg - 1) / per_wg;
     const size_t lds = (size_t)WK * NT * MT * kWave * sizeof(floatx4);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, WK>), dim3(grid), dim3(WK * kWave), lds, st, d);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, WK, EPI>), dim3(grid), dim3(WK * kWave), lds, st, d);
 }
 
-template <int MT>
+// Tile shape per launch.  work_tiles: 16-feature tiles (tile PAIRS for the gated
+// epilogue).  Wide outputs give each wave 4 or 2 tiles so that X is re-read
+// less; narrow outputs (O, down) keep one tile per wave and raise the number of
+// waves that split K until the grid holds about 2048 waves.
+template <int MT, int EPI>
 static void launch_skinny_mt(const GemmDev& d, int work_tiles, hipStream_t st) {
-    // work_tiles: feature tiles (tile PAIRS for the gated epilogue)
-    const bool gated = d.epilogue == EPI_GATED;
+    constexpr bool gated = (EPI == EPI_GATED);
     const int chunks = (d.K + 127) / 128;
     int nt = 1;
     if (gated) nt = (work_tiles / 2 >= 448 && MT <= 3) ? 4 : 2;
     else if (work_tiles / 4 >= 448 && MT <= 3) nt = 4;
     else if (work_tiles / 2 >= 448) nt = 2;
-    if (nt == 4) { launch_skinny<MT, 4, 4>(d, work_tiles, st); return; }
-    if (nt == 2) { launch_skinny<MT, 2, 4>(d, work_tiles, st); return; }
-    if constexpr (MT <= 2) {                          // 16 waves leave 128 VGPRs each: enough for two row tiles
-        if (work_tiles * 8 < 2048 && chunks >= 32) { launch_skinny<MT, 1, 16>(d, work_tiles, st); return; }
+    if (nt == 4) { launch_skinny<MT, 4, 4, EPI>(d, work_tiles, st); return; }
+    if (nt == 2) { launch_skinny<MT, 2, 4, EPI>(d, work_tiles, st); return; }
+    if constexpr (!gated) {
+        if constexpr (MT <= 2) {                      // 16 waves leave 128 VGPRs each: enough for two row tiles
+            if (work_tiles * 8 < 2048 && chunks >= 32) { launch_skinny<MT, 1, 16, EPI>(d, work_tiles, st); return; }
+        }
+        launch_skinny<MT, 1, 8, EPI>(d, work_tiles, st);
     }
-    launch_skinny<MT, 1, 8>(d, work_tiles, st);
+}
+
+template <int EPI>
+static int launch_skinny_epi(const GemmDev& d, int M, int work_tiles, hipStream_t st) {
+    switch ((M + 15) / 16) {
+        case 1: launch_skinny_mt<1, EPI>(d, work_tiles, st); break;
+        case 2: launch_skinny_mt<2, EPI>(d, work_tiles, st); break;
+        case 3: launch_skinny_mt<3, EPI>(d, work_tiles, st); break;
+        case 4: launch_skinny_mt<4, EPI>(d, work_tiles, st); break;
+        default: return MASSV_EUNSUPPORTED;
+    }
+    return MASSV_OK;
 }
 
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
@@ -295,15 +312,18 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
     d.y = g.y;
     d.M = g.M; d.K = g.K;
     d.ldy = (g.epilogue == EPI_GATED) ? g.n[0] : N;
-    d.epilogue = g.epilogue; d.act = g.act;
+    d.act = g.act;
     const int work = (g.epilogue == EPI_GATED) ? d.tiles[0] : N / 16;
-    switch ((g.M + 15) / 16) {
-        case 1: launch_skinny_mt<1>(d, work, st); break;
-        case 2: launch_skinny_mt<2>(d, work, st); break;
-        case 3: launch_skinny_mt<3>(d, work, st); break;
-        case 4: launch_skinny_mt<4>(d, work, st); break;
-        default: return MASSV_EUNSUPPORTED;
+    int rc2 = MASSV_EUNSUPPORTED;
+    trace_begin(g.kid, st);
+    switch (g.epilogue) {
+        case EPI_STORE: rc2 = launch_skinny_epi<EPI_STORE>(d, g.M, work, st); break;
+        case EPI_RESIDUAL: rc2 = launch_skinny_epi<EPI_RESIDUAL>(d, g.M, work, st); break;
+        case EPI_GATED: rc2 = launch_skinny_epi<EPI_GATED>(d, g.M, work, st); break;
+        case EPI_LOGITS: rc2 = launch_skinny_epi<EPI_LOGITS>(d, g.M, work, st); break;
     }
+    trace_end(g.kid, st);
+    if (rc2 != MASSV_OK) return rc2;
     return launch_status();
 }
 

@@ -6,6 +6,20 @@
 
 namespace massv {
 
+// ---- one-shot kernel timing hook (api.hip) ----
+// massv_trace_kernel() arms a request on the calling thread; the next launch
+// of that kernel records the caller's two events around it and disarms.
+struct TraceRequest { int kid; hipEvent_t start, stop; };
+TraceRequest& trace_request();
+inline void trace_begin(int kid, hipStream_t st) {
+    TraceRequest& t = trace_request();
+    if (t.kid == kid && kid >= 0) (void)hipEventRecord(t.start, st);
+}
+inline void trace_end(int kid, hipStream_t st) {
+    TraceRequest& t = trace_request();
+    if (t.kid == kid && kid >= 0) { (void)hipEventRecord(t.stop, st); t.kid = -1; }
+}
+
 // ---- small row-wise kernels (elementwise.hip) ----
 // y[m,:] = x[m,:] * g / sqrt(mean(x[m,:]^2) + eps)
 int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st);
@@ -35,6 +49,7 @@ struct GemmArgs {
     void* scratch;            // f32 + EPI_GATED only: [M][2*n0] floats
     int M, K;
     int epilogue, act, dtype;
+    int kid;                  // massv_kernel_id bracketed by a pending trace request
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
 // Whether launch_gemm can run this problem (host-side shape check only).

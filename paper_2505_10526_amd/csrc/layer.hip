@@ -72,20 +72,20 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
     qkv.w[0] = w->wq; qkv.w[1] = w->wk; qkv.w[2] = w->wv;
     qkv.bias[0] = bias ? w->bq : nullptr; qkv.bias[1] = bias ? w->bk : nullptr; qkv.bias[2] = bias ? w->bv : nullptr;
     qkv.n[0] = nq; qkv.n[1] = nkv; qkv.n[2] = nkv;
-    qkv.y = ws + lay.qkv; qkv.M = M; qkv.K = H; qkv.epilogue = EPI_STORE; qkv.act = desc->act; qkv.dtype = a.dtype;
+    qkv.y = ws + lay.qkv; qkv.M = M; qkv.K = H; qkv.epilogue = EPI_STORE; qkv.kid = MASSV_K_QKV; qkv.act = desc->act; qkv.dtype = a.dtype;
 
     GemmArgs op = {};
     op.x = ws + lay.attn; op.w[0] = w->wo; op.n[0] = H; op.residual = x; op.y = x;
-    op.M = M; op.K = nq; op.epilogue = EPI_RESIDUAL; op.act = desc->act; op.dtype = a.dtype;
+    op.M = M; op.K = nq; op.epilogue = EPI_RESIDUAL; op.kid = MASSV_K_OPROJ; op.act = desc->act; op.dtype = a.dtype;
 
     GemmArgs gu = {};
     gu.x = ws + lay.xn; gu.w[0] = w->wg; gu.w[1] = w->wu; gu.n[0] = F; gu.n[1] = F;
     gu.y = ws + lay.h; gu.scratch = ws + lay.gu;
-    gu.M = M; gu.K = H; gu.epilogue = EPI_GATED; gu.act = desc->act; gu.dtype = a.dtype;
+    gu.M = M; gu.K = H; gu.epilogue = EPI_GATED; gu.kid = MASSV_K_GATEUP; gu.act = desc->act; gu.dtype = a.dtype;
 
     GemmArgs dn = {};
     dn.x = ws + lay.h; dn.w[0] = w->wd; dn.n[0] = H; dn.residual = x; dn.y = x;
-    dn.M = M; dn.K = F; dn.epilogue = EPI_RESIDUAL; dn.act = desc->act; dn.dtype = a.dtype;
+    dn.M = M; dn.K = F; dn.epilogue = EPI_RESIDUAL; dn.kid = MASSV_K_DOWN; dn.act = desc->act; dn.dtype = a.dtype;
 
     // shape checks for every projection before the first launch
     if ((rc = gemm_supported(qkv)) != MASSV_OK) return rc;
@@ -131,6 +131,6 @@ extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const
         g.x = workspace;
     }
     g.w[0] = w_lm; g.n[0] = V; g.y = logits; g.M = M; g.K = H;
-    g.epilogue = EPI_LOGITS; g.dtype = dtype;
+    g.epilogue = EPI_LOGITS; g.dtype = dtype; g.kid = MASSV_K_LMHEAD;
     return launch_gemm(g, st);
 }
