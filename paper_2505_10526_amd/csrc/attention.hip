@@ -119,6 +119,7 @@ struct AttnParams {
     bf16_t* out;                 // used when n_split == 1
     float* part_o; float* part_ml;   // [B][n_kv][S][rows_pad][D], [B][n_kv][S][rows_pad][2]
     int Q, n_q, n_kv, l_max, n_split;
+    int out_mt;                  // > 0: out is written in operand order with this many row tiles
     float scale_log2;            // scale * log2(e)
 };
 
@@ -293,7 +294,10 @@ void attention_mfma_kernel(AttnParams p) {
             const floatx4 v = *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
             const float inv = 1.0f / s_lt[r];
             bf16x4 o = {(bf16_t)(v[0] * inv), (bf16_t)(v[1] * inv), (bf16_t)(v[2] * inv), (bf16_t)(v[3] * inv)};
-            *reinterpret_cast<bf16x4*>(p.out + (((size_t)b * p.Q + i) * p.n_q + g * G + hh) * D + c4 * 4) = o;
+            const int mrow = b * p.Q + i, col = (g * G + hh) * D + c4 * 4;
+            bf16_t* dst = p.out_mt > 0 ? p.out + packed_index(mrow, col, p.out_mt)
+                                       : p.out + (size_t)mrow * p.n_q * D + col;
+            *reinterpret_cast<bf16x4*>(dst) = o;
         }
     } else {
         const size_t slot = (bg * p.n_split + split) * ROWS;
@@ -315,7 +319,7 @@ void attention_mfma_kernel(AttnParams p) {
 // Merge of the key-range splits: one workgroup of D/4 threads per output row.
 template <int D>
 __global__ void attention_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                         bf16_t* __restrict__ out, int Q, int n_q, int n_kv, int n_split, int rows_pad) {
+                                         bf16_t* __restrict__ out, int Q, int n_q, int n_kv, int n_split, int rows_pad, int out_mt) {
     const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, t = threadIdx.x;
     const int G = n_q / n_kv, g = h / G, r = i * G + (h % G);
     const size_t slot0 = ((size_t)b * n_kv + g) * n_split * rows_pad;
@@ -333,7 +337,9 @@ __global__ void attention_combine_kernel(const float* __restrict__ part_o, const
     }
     const float inv = 1.0f / l;
     bf16x4 ob = {(bf16_t)(o[0] * inv), (bf16_t)(o[1] * inv), (bf16_t)(o[2] * inv), (bf16_t)(o[3] * inv)};
-    *reinterpret_cast<bf16x4*>(out + (((size_t)b * Q + i) * n_q + h) * D + t * 4) = ob;
+    const int mrow = b * Q + i, col = h * D + t * 4;
+    bf16_t* dst = out_mt > 0 ? out + packed_index(mrow, col, out_mt) : out + (size_t)mrow * n_q * D + col;
+    *reinterpret_cast<bf16x4*>(dst) = ob;
 }
 
 // ---------------------------------------------------------------------------
@@ -393,7 +399,7 @@ static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
     if (p.n_split > 1) {
         trace_begin(MASSV_K_ATTN_COMBINE, st);
         hipLaunchKernelGGL((attention_combine_kernel<D>), dim3(a.n_q_heads, a.n_query, a.batch), dim3(D / 4), 0, st,
-                           p.part_o, p.part_ml, p.out, a.n_query, a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16);
+                           p.part_o, p.part_ml, p.out, a.n_query, a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16, p.out_mt);
         trace_end(MASSV_K_ATTN_COMBINE, st);
     }
     return launch_status();
@@ -411,7 +417,7 @@ static int launch_mfma_d(const massv_attn_desc& a, AttnParams p, int mt, hipStre
 }
 
 int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cache, const void* v_cache,
-                     const int32_t* kv_len, void* out, void* ws, hipStream_t st) {
+                     const int32_t* kv_len, void* out, void* ws, bool out_packed, hipStream_t st) {
     const float scale = a.scale > 0.f ? a.scale : 1.0f / sqrtf((float)a.head_dim);
     if (a.dtype == MASSV_F32) {
         hipLaunchKernelGGL(attention_generic_kernel<float>, dim3(a.n_query, a.n_q_heads, a.batch), dim3(256), 0, st,
@@ -424,6 +430,7 @@ int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cach
     p.out = (bf16_t*)out;
     p.Q = a.n_query; p.n_q = a.n_q_heads; p.n_kv = a.n_kv_heads; p.l_max = a.l_max;
     p.n_split = n_split_of(a);
+    p.out_mt = out_packed ? (a.batch * a.n_query + 15) / 16 : 0;
     p.scale_log2 = scale * 1.4426950408889634f;
     const int rp = rows_pad_of(a);
     const size_t slots = (size_t)a.batch * a.n_kv_heads * p.n_split * rp;
@@ -454,5 +461,5 @@ extern "C" int massv_verify_attention(const massv_attn_desc* desc, const void* q
     if (rc != MASSV_OK) return rc;
     if (!q || !k_cache || !v_cache || !kv_len || !out) return MASSV_EINVAL;
     if (!workspace || workspace_bytes < attention_workspace(*desc)) return MASSV_EWORKSPACE;
-    return launch_attention(*desc, q, k_cache, v_cache, kv_len, out, workspace, (hipStream_t)stream);
+    return launch_attention(*desc, q, k_cache, v_cache, kv_len, out, workspace, false, (hipStream_t)stream);
 }

@@ -37,6 +37,18 @@ template <> struct ElemOf<bf16_t> {
 template <typename T> __device__ inline float ldf(const T* p) { return ElemOf<T>::load(p); }
 template <typename T> __device__ inline void stf(T* p, float v) { ElemOf<T>::store(p, v); }
 
+// ---- operand-order ("packed") activations ----
+// The bf16 projections read their activation matrix X[M][K] as the B operand
+// of v_mfma_f32_16x16x32_bf16: lane l of a wave needs the 8 values
+// X[16*mt + l%16][32*ks + 8*(l/16) .. +8].  Producers store X in exactly that
+// order, [K/32][MT][64 lanes][8], MT = ceil(M/16), so that a wave's operand
+// load is one contiguous 1 KB read (8 full cache lines instead of 16 half
+// lines).  Rows M .. 16*MT-1 are padding and are never read back into results.
+__host__ __device__ inline size_t packed_index(int m, int k, int mt_count) {
+    return (((size_t)(k >> 5) * mt_count + (m >> 4)) * 64 + ((m & 15) + 16 * ((k & 31) >> 3))) * 8 + (k & 7);
+}
+__host__ __device__ inline size_t packed_elems(int M, int K) { return (size_t)((M + 15) / 16) * 16 * K; }
+
 // ---- wavefront reductions (all 64 lanes take part, all receive the result) ----
 __device__ inline float wave_max(float v) {
 #pragma unroll

@@ -26,6 +26,45 @@ void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restr
     for (int k = tid; k < H; k += 256) stf(yr + k, ldf(xr + k) * rstd * ldf(g + k));
 }
 
+// bf16 rows -> RMSNorm -> operand-order output (see packed_index).  g == nullptr: no
+// normalisation, the row is only re-laid out.  H % 8 == 0.
+__global__ __launch_bounds__(256)
+void rmsnorm_pack_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g, bf16_t* __restrict__ y,
+                         int H, float eps, int mt_count) {
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const bf16x8* xr = reinterpret_cast<const bf16x8*>(x + (size_t)m * H);
+    const int groups = H / 8;
+    float rstd = 1.f;
+    if (g) {
+        float ss = 0.f;
+        for (int k8 = tid; k8 < groups; k8 += 256) {
+            const bf16x8 v = xr[k8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ss += f * f; }
+        }
+        ss = wave_sum(ss);
+        __shared__ float part[4];
+        if ((tid & 63) == 0) part[tid >> 6] = ss;
+        __syncthreads();
+        rstd = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)H + eps);
+    }
+    for (int k8 = tid; k8 < groups; k8 += 256) {
+        bf16x8 v = xr[k8];
+        if (g) {
+            const bf16x8 gv = reinterpret_cast<const bf16x8*>(g)[k8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = (bf16_t)((float)v[e] * rstd * (float)gv[e]);
+        }
+        *reinterpret_cast<bf16x8*>(y + packed_index(m, k8 * 8, mt_count)) = v;
+    }
+}
+
+int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(M), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y,
+                       H, eps, (M + 15) / 16);
+    return launch_status();
+}
+
 int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st) {
     if (dtype == MASSV_F32)
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y, H, eps);

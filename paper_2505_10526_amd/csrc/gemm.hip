@@ -17,7 +17,10 @@
 //     second pass over HBM partials.
 //   * Loads of the next chunk are issued before the matrix instructions of the
 //     current one (two register buffers).
-//   * X (M x K bf16, at most a few MB) is re-read by every workgroup from L2.
+//   * X (M x K bf16, at most a few MB) is re-read by every workgroup from L2.  It
+//     is kept in operand order (packed_index) so that these reads are contiguous
+//     1 KB blocks; its producers (RMSNorm, attention, the gated epilogue) write
+//     that order directly.
 //   * Epilogues: bias + store, residual add, act(gate)*up for interleaved
 //     gate/up tiles, fp32 logits.
 // f32 kernel: one wave per output feature, plain FMAs, for the small fp32
@@ -81,14 +84,9 @@ void gemm_skinny_kernel(GemmDev g) {
         seg_of[nt] = seg; wfeat[nt] = local * 16;
         wrow[nt] = g.w[seg] + (size_t)(local * 16 + lr) * K + lc * 8;
     }
-    const bf16_t* xrow[MT];
-    bool mvalid[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 16 + lr;
-        mvalid[mt] = m < g.M;
-        xrow[mt] = g.x + (size_t)(mvalid[mt] ? m : 0) * K + lc * 8;
-    }
+    // X is stored in operand order: the B operand of (k-step ks, row tile mt) is the 1 KB block
+    // ((ks * MT + mt) * 64 + lane) * 8.
+    const bf16_t* xlane = g.x + (size_t)lane * 8;
 
     floatx4 acc[NT][MT];
 #pragma unroll
@@ -107,7 +105,7 @@ void gemm_skinny_kernel(GemmDev g) {
             _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                             \
                 A[nt][j] = ld8(wrow[nt] + k0 + j * 32, kok && nvalid[nt]);                \
             _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                             \
-                B[mt][j] = ld8(xrow[mt] + k0 + j * 32, kok && mvalid[mt]);                \
+                B[mt][j] = ld8(xlane + (size_t)(((CH) * 4 + j) * MT + mt) * 512, kok);    \
         }                                                                                 \
     }
 #define MASSV_GEMM_MMA(A, B)                                                              \
@@ -157,7 +155,7 @@ void gemm_skinny_kernel(GemmDev g) {
                     bf16x4 o;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(gemm_act(s[i], g.act) * u[i]);
-                    *reinterpret_cast<bf16x4*>((bf16_t*)g.y + (size_t)m * g.ldy + col) = o;
+                    *reinterpret_cast<bf16x4*>((bf16_t*)g.y + packed_index(m, col, MT)) = o;
                 }
             } else if (m < g.M) {
                 if (EPI == EPI_LOGITS) {

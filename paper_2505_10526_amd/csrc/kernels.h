@@ -23,6 +23,8 @@ inline void trace_end(int kid, hipStream_t st) {
 // ---- small row-wise kernels (elementwise.hip) ----
 // y[m,:] = x[m,:] * g / sqrt(mean(x[m,:]^2) + eps)
 int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st);
+// bf16 only: same, output in operand order (packed_index); g == nullptr re-lays the rows out without normalising.
+int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st);
 // Rotates the q and k heads of qkv[M][(n_q+2n_kv)*d] by pos[m], writes q to
 // q_out[M][n_q][d] and the k / v rows of token (b,i) to cache row kv_len[b]+i.
 int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
@@ -36,11 +38,11 @@ int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int
 enum Epilogue {
     EPI_STORE = 0,      // y = acc (+ bias), stored in the activation dtype
     EPI_RESIDUAL = 1,   // y = acc + residual (residual may alias y), activation dtype
-    EPI_GATED = 2,      // two matrices (gate, up) of equal size: y = act(gate) * up
+    EPI_GATED = 2,      // two matrices (gate, up) of equal size: y = act(gate) * up (bf16: y in operand order)
     EPI_LOGITS = 3      // y = acc stored as float32
 };
 struct GemmArgs {
-    const void* x;            // [M][K]
+    const void* x;            // f32: [M][K] row-major; bf16: operand order (packed_index), packed_elems(M,K) elements
     const void* w[3];         // [n_i][K]
     const void* bias[3];      // [n_i] or nullptr
     int n[3];                 // rows of each matrix (0 = unused)
@@ -58,7 +60,8 @@ int gemm_supported(const GemmArgs& g);
 // ---- attention (attention.hip) ----
 size_t attention_workspace(const massv_attn_desc& a);
 int check_attn_desc(const massv_attn_desc* a);
+// out_packed (bf16 only): write out[B*Q][n_q*d] in operand order for the output projection.
 int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cache, const void* v_cache,
-                     const int32_t* kv_len, void* out, void* ws, hipStream_t st);
+                     const int32_t* kv_len, void* out, void* ws, bool out_packed, hipStream_t st);
 
 }  // namespace massv

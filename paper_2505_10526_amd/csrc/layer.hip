@@ -14,11 +14,13 @@ static LayerLayout layer_layout(const massv_layer_desc& d) {
     const size_t nq = (size_t)a.n_q_heads * a.head_dim, nkv = (size_t)a.n_kv_heads * a.head_dim;
     LayerLayout l;
     size_t o = 0;
-    l.xn = o;   o = align_up(o + M * d.hidden * es, 256);
+    const bool bf = a.dtype == MASSV_BF16;          // bf16 activations that feed a projection are kept in operand order
+    const size_t Mp = bf ? (M + 15) / 16 * 16 : M;
+    l.xn = o;   o = align_up(o + Mp * d.hidden * es, 256);
     l.qkv = o;  o = align_up(o + M * (nq + 2 * nkv) * es, 256);
     l.qrot = o; o = align_up(o + M * nq * es, 256);
-    l.attn = o; o = align_up(o + M * nq * es, 256);
-    l.h = o;    o = align_up(o + M * d.mlp * es, 256);
+    l.attn = o; o = align_up(o + Mp * nq * es, 256);
+    l.h = o;    o = align_up(o + Mp * d.mlp * es, 256);
     l.gu = o;   o = align_up(o + (a.dtype == MASSV_F32 ? M * 2 * d.mlp * 4 : 0), 256);
     l.attn_ws = o; o = align_up(o + attention_workspace(a), 256);
     l.total = o;
@@ -93,12 +95,17 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
     if ((rc = gemm_supported(gu)) != MASSV_OK) return rc;
     if ((rc = gemm_supported(dn)) != MASSV_OK) return rc;
 
-    if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+    const bool bf = a.dtype == MASSV_BF16;
+    rc = bf ? launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)
+            : launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st);
+    if (rc != MASSV_OK) return rc;
     if ((rc = launch_gemm(qkv, st)) != MASSV_OK) return rc;
     if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a, desc->rope_theta, st)) != MASSV_OK) return rc;
-    if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, st)) != MASSV_OK) return rc;
+    if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, bf, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(op, st)) != MASSV_OK) return rc;
-    if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+    rc = bf ? launch_rmsnorm_packed(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, st)
+            : launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st);
+    if (rc != MASSV_OK) return rc;
     if ((rc = launch_gemm(gu, st)) != MASSV_OK) return rc;
     return launch_gemm(dn, st);
 }
@@ -112,7 +119,7 @@ static int check_lm_head(int32_t M, int32_t H, int32_t V, int32_t dtype) {
 
 extern "C" size_t massv_lm_head_logits_workspace(int32_t M, int32_t H, int32_t V, int32_t dtype) {
     if (check_lm_head(M, H, V, dtype) != MASSV_OK) return 0;
-    return align_up((size_t)M * H * (dtype == MASSV_F32 ? 4 : 2), 256);
+    return dtype == MASSV_F32 ? align_up((size_t)M * H * 4, 256) : align_up(packed_elems(M, H) * 2, 256);
 }
 
 extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const void* w_lm, float* logits,
@@ -126,7 +133,10 @@ extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const
     hipStream_t st = (hipStream_t)stream;
     GemmArgs g = {};
     g.x = x;
-    if (final_norm) {
+    if (dtype == MASSV_BF16) {                  // normalise (or only re-lay out) into operand order
+        if ((rc = launch_rmsnorm_packed(x, final_norm, workspace, M, H, norm_eps, st)) != MASSV_OK) return rc;
+        g.x = workspace;
+    } else if (final_norm) {
         if ((rc = launch_rmsnorm(x, final_norm, workspace, M, H, norm_eps, dtype, st)) != MASSV_OK) return rc;
         g.x = workspace;
     }
