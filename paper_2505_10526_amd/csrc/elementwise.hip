@@ -131,6 +131,118 @@ int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_le
     return launch_status();
 }
 
+// bf16 path: the q/k/v projection leaves fp32 partial sums per K slab; this kernel sums them, adds the
+// bias, applies the rotary embedding and scatters q / k / v.  Same grid as rope_append_kernel.
+__global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
+                                  const bf16_t* __restrict__ bq, const bf16_t* __restrict__ bk,
+                                  const bf16_t* __restrict__ bv, const int32_t* __restrict__ pos,
+                                  const int32_t* __restrict__ kv_len, bf16_t* __restrict__ q_out,
+                                  bf16_t* __restrict__ k_cache, bf16_t* __restrict__ v_cache,
+                                  int Q, int n_q, int n_kv, int d, int l_max, double log2_theta) {
+    const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
+    const int half = d / 2;
+    if (j >= half) return;
+    const int b = m / Q, i = m % Q;
+    const int width = (n_q + 2 * n_kv) * d;
+    const size_t col = (size_t)head * d + j;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s = 0; s < n_slabs; ++s) {                 // fixed order: deterministic
+        const float* p = partial + s * slab_stride + (size_t)m * width + col;
+        x1 += p[0]; x2 += p[half];
+    }
+    const bf16_t* bias = head < n_q ? bq : head < n_q + n_kv ? bk : bv;
+    if (bias) {
+        const int hb = head < n_q ? head : head < n_q + n_kv ? head - n_q : head - n_q - n_kv;
+        x1 += (float)bias[hb * d + j]; x2 += (float)bias[hb * d + j + half];
+    }
+    int row = kv_len[b];
+    row = (row < 0 ? 0 : row) + i;
+    if (head < n_q + n_kv) {
+        const double ang = (double)pos[m] * exp2(-2.0 * (double)j / (double)d * log2_theta);
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        const float y1 = (float)((double)x1 * cs - (double)x2 * sn);
+        const float y2 = (float)((double)x2 * cs + (double)x1 * sn);
+        if (head < n_q) {
+            bf16_t* dst = q_out + ((size_t)m * n_q + head) * d;
+            dst[j] = (bf16_t)y1; dst[j + half] = (bf16_t)y2;
+        } else if (row < l_max) {
+            bf16_t* dst = k_cache + (((size_t)b * n_kv + (head - n_q)) * l_max + row) * d;
+            dst[j] = (bf16_t)y1; dst[j + half] = (bf16_t)y2;
+        }
+    } else if (row < l_max) {
+        const size_t bg = (size_t)b * n_kv + (head - n_q - n_kv);
+        v_cache[v_cache_index(bg, l_max, d, row, j)] = (bf16_t)x1;
+        v_cache[v_cache_index(bg, l_max, d, row, j + half)] = (bf16_t)x2;
+    }
+}
+
+int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, const void* bq, const void* bk,
+                      const void* bv, const int32_t* pos, const int32_t* kv_len, void* q_out, void* k_cache,
+                      void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st) {
+    const int M = a.batch * a.n_query;
+    dim3 grid(M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
+    hipLaunchKernelGGL(qkv_finish_kernel, grid, block, 0, st, partial, n_slabs, slab_stride, (const bf16_t*)bq,
+                       (const bf16_t*)bk, (const bf16_t*)bv, pos, kv_len, (bf16_t*)q_out, (bf16_t*)k_cache,
+                       (bf16_t*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, log2((double)theta));
+    return launch_status();
+}
+
+// bf16 path: residual add of a projection's partial sums, optionally followed by RMSNorm into operand
+// order.  One workgroup per row; a thread owns up to 4 groups of 8 consecutive features (H <= 8192).
+__global__ __launch_bounds__(256)
+void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
+                            bf16_t* __restrict__ x, const bf16_t* __restrict__ ln, bf16_t* __restrict__ xn,
+                            int H, float eps, int mt_count) {
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const int groups = H / 8;
+    float v[4][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int k8 = tid + r * 256;
+        if (k8 < groups) {
+            const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
+            float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < n_slabs; ++s) {
+                const floatx4* p = reinterpret_cast<const floatx4*>(partial + s * slab_stride + (size_t)m * H + k8 * 8);
+                const floatx4 p0 = p[0], p1 = p[1];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { add[e] += p0[e]; add[4 + e] += p1[e]; }
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { v[r][e] = (float)xv[e] + add[e]; o[e] = (bf16_t)v[r][e]; ss += v[r][e] * v[r][e]; }
+            *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
+        }
+    }
+    if (!ln) return;
+    ss = wave_sum(ss);
+    __shared__ float part[4];
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)H + eps);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int k8 = tid + r * 256;
+        if (k8 < groups) {
+            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(ln + k8 * 8);
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(v[r][e] * rstd * (float)gv[e]);
+            *reinterpret_cast<bf16x8*>(xn + packed_index(m, k8 * 8, mt_count)) = o;
+        }
+    }
+}
+
+int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* ln,
+                           void* xn_packed, int M, int H, float eps, hipStream_t st) {
+    if (H % 8 || H > 8192) return MASSV_EUNSUPPORTED;
+    hipLaunchKernelGGL(residual_finish_kernel, dim3(M), dim3(256), 0, st, partial, n_slabs, slab_stride, (bf16_t*)x,
+                       (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
+    return launch_status();
+}
+
 // ---------------------------------------------------------------------------
 // h = act(g) * u
 // ---------------------------------------------------------------------------

@@ -4,40 +4,50 @@
 // STREAMERS: the job is to pull W through HBM once at full bandwidth; the
 // matrix cores only have to keep up.
 //
-// bf16 kernel (gemm_skinny_kernel):
+// bf16 kernel (gemm_stream_kernel), shaped by measurements on MI355X:
 //   * v_mfma_f32_16x16x32_bf16 with W as the A operand (16 output features x
-//     32 k) and X as the B operand (32 k x 16 rows): every lane's operand is one
-//     16-byte global load from a row of W (or X); four lanes cover 64
-//     contiguous bytes of a row and the four k-steps of a chunk cover 256.
-//   * A wave owns NT feature tiles x all MT row tiles; the WK waves of a
-//     workgroup split K in interleaved 128-element chunks (so the workgroup
-//     reads contiguous row segments) and are summed through LDS in wave order
-//     (deterministic).  WK is raised for the projections with few output
-//     features (O, down) so that the grid still fills 256 CUs without a
-//     second pass over HBM partials.
-//   * Loads of the next chunk are issued before the matrix instructions of the
-//     current one (two register buffers).
-//   * X (M x K bf16, at most a few MB) is re-read by every workgroup from L2.  It
-//     is kept in operand order (packed_index) so that these reads are contiguous
-//     1 KB blocks; its producers (RMSNorm, attention, the gated epilogue) write
-//     that order directly.
-//   * Epilogues: bias + store, residual add, act(gate)*up for interleaved
-//     gate/up tiles, fp32 logits.
+//     32 k) and X as the B operand (32 k x 16 rows): every lane's W operand is
+//     one 16-byte global load from a row of W; four lanes cover 64 contiguous
+//     bytes of a row and the four k-steps of a 128-element chunk cover 256.
+//   * X comes from L2, and those reads -- not HBM -- were the first limiter.
+//     Two remedies: X is kept in operand order (packed_index) so a wave reads it
+//     as contiguous 1 KB blocks, and a wave owns NT = 4..10 feature tiles per
+//     chunk so that each X block it loads is used NT times.
+//   * Each of the wave's NT tiles has its own register slot: right after the
+//     matrix instructions of tile t for chunk c have been issued, the loads of
+//     tile t for the wave's next chunk go out.  This keeps about NT-1 tile
+//     loads (4 KB each) in flight per wave with ONE set of W registers; X is
+//     double-buffered.
+//   * A workgroup is 4 waves that split its K range in interleaved chunks (so
+//     the workgroup reads contiguous row segments) and are summed through LDS
+//     in wave order (deterministic).
+//   * The grid is sized to at most one workgroup per CU (256) wherever
+//     possible: with a register-heavy streaming kernel a second partial round
+//     of workgroups costs as much as a full one.  Wide outputs (gate/up,
+//     lm_head) choose NT for that; narrow outputs (q/k/v, O, down) split K
+//     over gridDim.y slabs, write fp32 partial sums and leave the slab sum to
+//     the row-wise kernel that follows anyway (bias + rotary + cache append,
+//     residual + RMSNorm).
+//   * Epilogues: fp32 partial sums, act(gate)*up for interleaved gate/up tiles
+//     (written in operand order for the down projection), fp32 logits.
 // f32 kernel: one wave per output feature, plain FMAs, for the small fp32
 // configuration.
 #include "kernels.h"
 
 namespace massv {
 
+constexpr int kGemmWaves = 4;            // waves per workgroup (K split)
+constexpr int kCUs = 256;
+
 struct GemmDev {
     const bf16_t* x;
     const bf16_t* w[3];
-    const bf16_t* bias[3];
     int tiles[3];            // 16-feature tiles per matrix
-    const bf16_t* residual;
     void* y;
     int M, K, ldy;           // ldy: elements per output row
     int act;
+    int chunks_per_slab;
+    size_t slab_stride;      // elements between the partial sums of consecutive K slabs
 };
 
 __device__ inline float gemm_act(float x, int act) {
@@ -51,29 +61,37 @@ __device__ inline bf16x8 ld8(const bf16_t* p, bool ok) {
     return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
 }
 
-template <int MT, int NT, int WK, int EPI>
-__global__ __launch_bounds__(WK * kWave)
-void gemm_skinny_kernel(GemmDev g) {
-    extern __shared__ floatx4 red[];                 // [WK][NT*MT][64]
+// Tiles of LDS reduced per round: at most 48 KB of fp32 fragments at a time.
+template <int MT, int NT>
+struct ReduceGroup {
+    static constexpr int kMax = 48 / (MT * kGemmWaves);
+    static constexpr int raw = (NT < kMax) ? NT : kMax;
+    static constexpr int value = (raw >= 2) ? (raw / 2) * 2 : 1;     // even, so gate/up pairs stay together
+};
+
+template <int MT, int NT, int EPI>
+__global__ __launch_bounds__(kGemmWaves * kWave)
+void gemm_stream_kernel(GemmDev g) {
+    constexpr int WK = kGemmWaves;
+    constexpr bool gated = (EPI == EPI_GATED);
+    extern __shared__ floatx4 red[];                 // [WK][GRP*MT][64]
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int lr = lane % 16, lc = lane / 16;
     const int K = g.K;
-    constexpr bool gated = (EPI == EPI_GATED);
 
-    // ---- which feature tiles this workgroup owns ----
+    // ---- the NT feature tiles of this workgroup ----
     const bf16_t* wrow[NT];
     bool nvalid[NT];
-    int seg_of[NT], ocol[NT], wfeat[NT];             // matrix, output column of the tile, first feature within its matrix
+    int ocol[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
+        const int t = blockIdx.x * NT + nt;
         int seg, local;
-        if (gated) {
-            seg = nt & 1;
-            local = blockIdx.x * (NT / 2) + nt / 2;
+        if (gated) {                                  // tiles alternate gate, up of one 16-feature group
+            seg = t & 1; local = t >> 1;
             nvalid[nt] = local < g.tiles[0];
             ocol[nt] = local * 16;
         } else {
-            const int t = blockIdx.x * NT + nt;
             if (t < g.tiles[0]) { seg = 0; local = t; }
             else if (t < g.tiles[0] + g.tiles[1]) { seg = 1; local = t - g.tiles[0]; }
             else { seg = 2; local = t - g.tiles[0] - g.tiles[1]; }
@@ -81,11 +99,9 @@ void gemm_skinny_kernel(GemmDev g) {
             ocol[nt] = t * 16;
         }
         if (!nvalid[nt]) { seg = 0; local = 0; }
-        seg_of[nt] = seg; wfeat[nt] = local * 16;
         wrow[nt] = g.w[seg] + (size_t)(local * 16 + lr) * K + lc * 8;
     }
-    // X is stored in operand order: the B operand of (k-step ks, row tile mt) is the 1 KB block
-    // ((ks * MT + mt) * 64 + lane) * 8.
+    // X in operand order: the B operand of (k-step ks, row tile mt) is the 1 KB block ((ks*MT + mt)*64 + lane)*8
     const bf16_t* xlane = g.x + (size_t)lane * 8;
 
     floatx4 acc[NT][MT];
@@ -95,85 +111,83 @@ void gemm_skinny_kernel(GemmDev g) {
         for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int n_chunks = (K + 127) / 128;
-    bf16x8 a0[NT][4], b0[MT][4], a1[NT][4], b1[MT][4];
+    const int c_begin = blockIdx.y * g.chunks_per_slab;
+    const int c_end = (c_begin + g.chunks_per_slab < n_chunks) ? c_begin + g.chunks_per_slab : n_chunks;
 
-#define MASSV_GEMM_LOAD(A, B, CH)                                                         \
-    {                                                                                     \
-        const int k0 = (CH) * 128;                                                        \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                   \
-            const bool kok = k0 + j * 32 < K;                                             \
-            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                             \
-                A[nt][j] = ld8(wrow[nt] + k0 + j * 32, kok && nvalid[nt]);                \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                             \
-                B[mt][j] = ld8(xlane + (size_t)(((CH) * 4 + j) * MT + mt) * 512, kok);    \
-        }                                                                                 \
+    bf16x8 a[NT][4];
+    bf16x8 xb[2][MT][4];
+    auto wload = [&](int nt, int ch) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[nt][j] = ld8(wrow[nt] + ch * 128 + j * 32, nvalid[nt] && (ch * 128 + j * 32 < K));
+    };
+    auto xload = [&](int buf, int ch) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                xb[buf][mt][j] = ld8(xlane + (size_t)((ch * 4 + j) * MT + mt) * 512, ch * 128 + j * 32 < K);
+    };
+    int ch = c_begin + wave;
+    if (ch < c_end) {
+        xload(0, ch);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wload(nt, ch);
     }
-#define MASSV_GEMM_MMA(A, B)                                                              \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                         \
-        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                 \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                             \
-                acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[nt][j], B[mt][j], acc[nt][mt], 0, 0, 0);
-
-    int ch = wave;
-    if (ch < n_chunks) MASSV_GEMM_LOAD(a0, b0, ch)
-    while (ch < n_chunks) {
-        if (ch + WK < n_chunks) MASSV_GEMM_LOAD(a1, b1, ch + WK)
-        MASSV_GEMM_MMA(a0, b0)
-        ch += WK;
-        if (ch >= n_chunks) break;
-        if (ch + WK < n_chunks) MASSV_GEMM_LOAD(a0, b0, ch + WK)
-        MASSV_GEMM_MMA(a1, b1)
-        ch += WK;
+    int par = 0;
+    for (; ch < c_end; ch += WK, par ^= 1) {
+        const int nx = ch + WK;
+        const bool more = nx < c_end;
+        if (more) { if (par) xload(0, nx); else xload(1, nx); }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt][j], par ? xb[1][mt][j] : xb[0][mt][j],
+                                                                         acc[nt][mt], 0, 0, 0);
+            if (more) wload(nt, nx);                  // refill this tile's slot for the wave's next chunk
+        }
     }
-#undef MASSV_GEMM_LOAD
-#undef MASSV_GEMM_MMA
 
-    // ---- sum the K-splits of the workgroup through LDS, in wave order ----
+    // ---- sum the waves through LDS in wave order, GRP tiles per round ----
+    constexpr int GRP = ReduceGroup<MT, NT>::value;
+    for (int g0 = 0; g0 < NT; g0 += GRP) {
+        if (g0) __syncthreads();
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
+            if (nt >= g0 && nt < g0 + GRP)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) red[(wave * NT * MT + nt * MT + mt) * kWave + lane] = acc[nt][mt];
-    __syncthreads();
-
+                for (int mt = 0; mt < MT; ++mt)
+                    red[(wave * GRP * MT + (nt - g0) * MT + mt) * kWave + lane] = acc[nt][mt];
+        __syncthreads();
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NT; ++nt) {
+            if (nt < g0 || nt >= g0 + GRP) continue;
+            if (gated && (nt & 1)) continue;                    // the up tile is consumed with its gate tile
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (gated && (nt & 1)) continue;                 // the up tile is consumed with its gate tile
-            const int item = gated ? (nt / 2) * MT + mt : nt * MT + mt;
-            if (item % WK != wave || !nvalid[nt]) continue;  // items are dealt round-robin to the waves
-            floatx4 s = red[(nt * MT + mt) * kWave + lane];
-            for (int w = 1; w < WK; ++w) s += red[(w * NT * MT + nt * MT + mt) * kWave + lane];
-            const int m = mt * 16 + lr;
-            const int col = ocol[nt] + lc * 4;               // 4 consecutive output features
-            if (gated) {
-                constexpr int NTU = (NT > 1) ? 1 : 0;        // NT >= 2 whenever the epilogue is gated
-                const int nu = nt + NTU;
-                floatx4 u = red[(nu * MT + mt) * kWave + lane];
-                for (int w = 1; w < WK; ++w) u += red[(w * NT * MT + nu * MT + mt) * kWave + lane];
-                if (m < g.M) {
-                    bf16x4 o;
+            for (int mt = 0; mt < MT; ++mt) {
+                const int item = gated ? ((nt - g0) / 2) * MT + mt : (nt - g0) * MT + mt;
+                if (item % WK != wave || !nvalid[nt]) continue;  // items are dealt round-robin to the waves
+                const int f = (nt - g0) * MT + mt;
+                floatx4 s = red[f * kWave + lane];
+                for (int w = 1; w < WK; ++w) s += red[(w * GRP * MT + f) * kWave + lane];
+                const int m = mt * 16 + lr;
+                const int col = ocol[nt] + lc * 4;               // 4 consecutive output features
+                if (gated) {
+                    constexpr int UP = (NT > 1) ? MT : 0;        // fragment of the paired up tile
+                    floatx4 u = red[(f + UP) * kWave + lane];
+                    for (int w = 1; w < WK; ++w) u += red[(w * GRP * MT + f + UP) * kWave + lane];
+                    if (m < g.M) {
+                        bf16x4 o;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(gemm_act(s[i], g.act) * u[i]);
-                    *reinterpret_cast<bf16x4*>((bf16_t*)g.y + packed_index(m, col, MT)) = o;
-                }
-            } else if (m < g.M) {
-                if (EPI == EPI_LOGITS) {
-                    *reinterpret_cast<floatx4*>((float*)g.y + (size_t)m * g.ldy + col) = s;
-                } else {
-                    const bf16_t* bias = g.bias[seg_of[nt]];
-                    if (bias) {
-                        const bf16x4 bv = *reinterpret_cast<const bf16x4*>(bias + wfeat[nt] + lc * 4);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) s[i] += (float)bv[i];
+                        for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(gemm_act(s[i], g.act) * u[i]);
+                        *reinterpret_cast<bf16x4*>((bf16_t*)g.y + packed_index(m, col, MT)) = o;
                     }
-                    if (EPI == EPI_RESIDUAL) {
-                        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.residual + (size_t)m * g.ldy + col);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) s[i] += (float)rv[i];
-                    }
-                    bf16x4 o = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
-                    *reinterpret_cast<bf16x4*>((bf16_t*)g.y + (size_t)m * g.ldy + col) = o;
+                } else if (m < g.M) {
+                    float* dst = (float*)g.y + (EPI == EPI_PARTIAL ? (size_t)blockIdx.y * g.slab_stride : 0) +
+                                 (size_t)m * g.ldy + col;
+                    *reinterpret_cast<floatx4*>(dst) = s;
                 }
             }
         }
@@ -226,7 +240,8 @@ static int n_total(const GemmArgs& g) { return g.n[0] + g.n[1] + g.n[2]; }
 int gemm_supported(const GemmArgs& g) {
     if (g.M < 1 || g.K < 1 || g.n[0] < 1) return MASSV_EINVAL;
     if (g.epilogue == EPI_GATED && (g.n[1] != g.n[0] || g.n[2] != 0)) return MASSV_EINVAL;
-    if (g.dtype == MASSV_F32) return MASSV_OK;
+    if (g.dtype == MASSV_F32) return (g.epilogue == EPI_PARTIAL) ? MASSV_EINVAL : MASSV_OK;
+    if (g.epilogue == EPI_STORE || g.epilogue == EPI_RESIDUAL) return MASSV_EINVAL;   // bf16 goes through partial sums
     if (g.M > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
     if (g.K % 32) return MASSV_EUNSUPPORTED;
     for (int s = 0; s < 3; ++s)
@@ -234,46 +249,74 @@ int gemm_supported(const GemmArgs& g) {
     return MASSV_OK;
 }
 
-template <int MT, int NT, int WK, int EPI>
-static void launch_skinny(const GemmDev& d, int work_tiles, hipStream_t st) {
-    constexpr int per_wg = (EPI == EPI_GATED) ? NT / 2 : NT;
-    const int grid = (work_tiles + per_wg - 1) / per_wg;
-    const size_t lds = (size_t)WK * NT * MT * kWave * sizeof(floatx4);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, WK, EPI>), dim3(grid), dim3(WK * kWave), lds, st, d);
+// Tiles per wave and K slabs for one launch.  T: 16-feature tiles to produce.
+//   wide output  (>= 256 groups): slabs = 1, NT chosen so that the last round of workgroups is as full as possible;
+//   narrow output: K is cut into slabs (at least one 128-chunk per wave each) so that groups*slabs approaches 256.
+GemmPlan gemm_plan(const GemmArgs& g) {
+    GemmPlan best = {0, 1, 0, 0};
+    if (g.dtype != MASSV_BF16) return best;
+    const int mt = (g.M + 15) / 16;
+    const int T = (g.epilogue == EPI_GATED) ? 2 * (g.n[0] / 16) : n_total(g) / 16;
+    const int n_chunks = (g.K + 127) / 128;
+    static const int cand_partial[] = {8, 7, 4}, cand_gated[] = {10, 8, 4}, cand_logits[] = {10, 8, 4};
+    const int* cand = g.epilogue == EPI_GATED ? cand_gated : g.epilogue == EPI_LOGITS ? cand_logits : cand_partial;
+    double best_score = -1.0;
+    for (int i = 0; i < 3; ++i) {
+        int nt = cand[i];
+        if (mt == 4 && nt > 4) continue;                       // register budget of four row tiles
+        const int groups = (T + nt - 1) / nt;
+        int slabs = 1, cps = n_chunks;
+        double eff;
+        if (groups >= kCUs || g.epilogue != EPI_PARTIAL) {
+            const int rounds = (groups + kCUs - 1) / kCUs;
+            eff = (double)T / ((double)nt * rounds * kCUs);
+        } else {
+            int max_slabs = n_chunks / kGemmWaves; if (max_slabs < 1) max_slabs = 1;
+            slabs = kCUs / groups; if (slabs > max_slabs) slabs = max_slabs; if (slabs > 32) slabs = 32;
+            cps = (n_chunks + slabs - 1) / slabs;
+            slabs = (n_chunks + cps - 1) / cps;
+            eff = (double)T * slabs / ((double)nt * kCUs) ;
+            if (eff > 1.0) eff = 1.0;
+        }
+        const double score = eff + 0.004 * nt;                 // near ties go to the larger tile count (less X traffic)
+        if (score > best_score) { best_score = score; best.nt = nt; best.slabs = slabs; best.chunks_per_slab = cps; best.groups = groups; }
+    }
+    return best;
 }
 
-// Tile shape per launch.  work_tiles: 16-feature tiles (tile PAIRS for the gated
-// epilogue).  Wide outputs give each wave 4 or 2 tiles so that X is re-read
-// less; narrow outputs (O, down) keep one tile per wave and raise the number of
-// waves that split K until the grid holds about 2048 waves.
+size_t gemm_partial_bytes(const GemmArgs& g) {
+    if (g.dtype != MASSV_BF16 || g.epilogue != EPI_PARTIAL) return 0;
+    const GemmPlan p = gemm_plan(g);
+    return (size_t)p.slabs * ((g.M + 15) / 16 * 16) * n_total(g) * sizeof(float);
+}
+
+template <int MT, int NT, int EPI>
+static void launch_stream(const GemmDev& d, const GemmPlan& p, hipStream_t st) {
+    constexpr int GRP = ReduceGroup<MT, NT>::value;
+    const size_t lds = (size_t)kGemmWaves * GRP * MT * kWave * sizeof(floatx4);
+    hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, EPI>), dim3(p.groups, p.slabs), dim3(kGemmWaves * kWave), lds, st, d);
+}
+
 template <int MT, int EPI>
-static void launch_skinny_mt(const GemmDev& d, int work_tiles, hipStream_t st) {
-    constexpr bool gated = (EPI == EPI_GATED);
-    const int chunks = (d.K + 127) / 128;
-    int nt = 1;
-    if (gated) nt = (work_tiles / 2 >= 448 && MT <= 3) ? 4 : 2;
-    else if (work_tiles / 4 >= 448 && MT <= 3) nt = 4;
-    else if (work_tiles / 2 >= 448) nt = 2;
-    if (nt == 4) { launch_skinny<MT, 4, 4, EPI>(d, work_tiles, st); return; }
-    if (nt == 2) { launch_skinny<MT, 2, 4, EPI>(d, work_tiles, st); return; }
-    if constexpr (!gated) {
-        if constexpr (MT <= 2) {                      // 16 waves leave 128 VGPRs each: enough for two row tiles
-            if (work_tiles * 8 < 2048 && chunks >= 32) { launch_skinny<MT, 1, 16, EPI>(d, work_tiles, st); return; }
-        }
-        launch_skinny<MT, 1, 8, EPI>(d, work_tiles, st);
+static int launch_stream_nt(const GemmDev& d, const GemmPlan& p, hipStream_t st) {
+    switch (p.nt) {
+        case 4: launch_stream<MT, 4, EPI>(d, p, st); return MASSV_OK;
+        case 7: if constexpr (EPI == EPI_PARTIAL && MT <= 3) { launch_stream<MT, 7, EPI>(d, p, st); return MASSV_OK; } break;
+        case 8: if constexpr (MT <= 3) { launch_stream<MT, 8, EPI>(d, p, st); return MASSV_OK; } break;
+        case 10: if constexpr (EPI != EPI_PARTIAL && MT <= 3) { launch_stream<MT, 10, EPI>(d, p, st); return MASSV_OK; } break;
     }
+    return MASSV_EUNSUPPORTED;
 }
 
 template <int EPI>
-static int launch_skinny_epi(const GemmDev& d, int M, int work_tiles, hipStream_t st) {
+static int launch_stream_epi(const GemmDev& d, int M, const GemmPlan& p, hipStream_t st) {
     switch ((M + 15) / 16) {
-        case 1: launch_skinny_mt<1, EPI>(d, work_tiles, st); break;
-        case 2: launch_skinny_mt<2, EPI>(d, work_tiles, st); break;
-        case 3: launch_skinny_mt<3, EPI>(d, work_tiles, st); break;
-        case 4: launch_skinny_mt<4, EPI>(d, work_tiles, st); break;
-        default: return MASSV_EUNSUPPORTED;
+        case 1: return launch_stream_nt<1, EPI>(d, p, st);
+        case 2: return launch_stream_nt<2, EPI>(d, p, st);
+        case 3: return launch_stream_nt<3, EPI>(d, p, st);
+        case 4: return launch_stream_nt<4, EPI>(d, p, st);
     }
-    return MASSV_OK;
+    return MASSV_EUNSUPPORTED;
 }
 
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
@@ -299,26 +342,22 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
         }
         return launch_status();
     }
+    const GemmPlan p = gemm_plan(g);
     GemmDev d;
     d.x = (const bf16_t*)g.x;
-    for (int s = 0; s < 3; ++s) {
-        d.w[s] = (const bf16_t*)g.w[s];
-        d.bias[s] = (const bf16_t*)g.bias[s];
-        d.tiles[s] = g.n[s] / 16;
-    }
-    d.residual = (const bf16_t*)g.residual;
+    for (int s = 0; s < 3; ++s) { d.w[s] = (const bf16_t*)g.w[s]; d.tiles[s] = g.n[s] / 16; }
     d.y = g.y;
     d.M = g.M; d.K = g.K;
     d.ldy = (g.epilogue == EPI_GATED) ? g.n[0] : N;
     d.act = g.act;
-    const int work = (g.epilogue == EPI_GATED) ? d.tiles[0] : N / 16;
+    d.chunks_per_slab = p.chunks_per_slab;
+    d.slab_stride = (size_t)((g.M + 15) / 16 * 16) * N;
     int rc2 = MASSV_EUNSUPPORTED;
     trace_begin(g.kid, st);
     switch (g.epilogue) {
-        case EPI_STORE: rc2 = launch_skinny_epi<EPI_STORE>(d, g.M, work, st); break;
-        case EPI_RESIDUAL: rc2 = launch_skinny_epi<EPI_RESIDUAL>(d, g.M, work, st); break;
-        case EPI_GATED: rc2 = launch_skinny_epi<EPI_GATED>(d, g.M, work, st); break;
-        case EPI_LOGITS: rc2 = launch_skinny_epi<EPI_LOGITS>(d, g.M, work, st); break;
+        case EPI_PARTIAL: rc2 = launch_stream_epi<EPI_PARTIAL>(d, g.M, p, st); break;
+        case EPI_GATED: rc2 = launch_stream_epi<EPI_GATED>(d, g.M, p, st); break;
+        case EPI_LOGITS: rc2 = launch_stream_epi<EPI_LOGITS>(d, g.M, p, st); break;
     }
     trace_end(g.kid, st);
     if (rc2 != MASSV_OK) return rc2;

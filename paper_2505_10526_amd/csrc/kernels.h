@@ -30,17 +30,29 @@ int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, f
 int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
                        void* k_cache, void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st);
 int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int dtype, hipStream_t st);
+// bf16: sums the K slabs of the q/k/v projection's partial sums [slabs][Mp][(n_q+2n_kv)*d], adds the biases
+// (nullptr = none), rotates q and k, writes q to q_out[M][n_q][d] and k / v to their cache rows.
+int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, const void* bq, const void* bk,
+                      const void* bv, const int32_t* pos, const int32_t* kv_len, void* q_out, void* k_cache,
+                      void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st);
+// bf16: x[m,:] += sum over slabs of partial[s][m,:]; if ln != nullptr also writes rmsnorm(x, ln) in operand
+// order to xn_packed.
+int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* ln,
+                           void* xn_packed, int M, int H, float eps, hipStream_t st);
 
 // ---- projections (gemm.hip) ----
 // One linear map Y = X W^T over M rows.  Up to three weight matrices that share
 // X are applied in one launch; their outputs are laid side by side in Y
 // ([M][n0+n1+n2]).
 enum Epilogue {
-    EPI_STORE = 0,      // y = acc (+ bias), stored in the activation dtype
-    EPI_RESIDUAL = 1,   // y = acc + residual (residual may alias y), activation dtype
+    EPI_STORE = 0,      // f32 only: y = acc (+ bias)
+    EPI_RESIDUAL = 1,   // f32 only: y = acc + residual (residual may alias y)
     EPI_GATED = 2,      // two matrices (gate, up) of equal size: y = act(gate) * up (bf16: y in operand order)
-    EPI_LOGITS = 3      // y = acc stored as float32
+    EPI_LOGITS = 3,     // y = acc stored as float32 [M][N]
+    EPI_PARTIAL = 4     // bf16 only: fp32 partial sums y[slab][16*ceil(M/16)][N], one slab per K range;
+                        // bias / residual are applied by the kernel that sums the slabs
 };
+struct GemmPlan { int nt, slabs, chunks_per_slab, groups; };
 struct GemmArgs {
     const void* x;            // f32: [M][K] row-major; bf16: operand order (packed_index), packed_elems(M,K) elements
     const void* w[3];         // [n_i][K]
@@ -54,6 +66,9 @@ struct GemmArgs {
     int kid;                  // massv_kernel_id bracketed by a pending trace request
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
+// bf16: tile count per wave and number of K slabs launch_gemm will use; bytes of the EPI_PARTIAL output.
+GemmPlan gemm_plan(const GemmArgs& g);
+size_t gemm_partial_bytes(const GemmArgs& g);
 // Whether launch_gemm can run this problem (host-side shape check only).
 int gemm_supported(const GemmArgs& g);
 

@@ -5,23 +5,47 @@
 
 namespace massv {
 
-struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, attn_ws, total; };
+struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, partial, attn_ws, total; };
+
+// The four projections of a layer as launch_gemm sees them (pointers filled in by the caller).
+struct LayerGemms { GemmArgs qkv, op, gu, dn; };
+
+static LayerGemms layer_gemms(const massv_layer_desc& d) {
+    const massv_attn_desc& a = d.attn;
+    const int M = a.batch * a.n_query, H = d.hidden, F = d.mlp;
+    const int nq = a.n_q_heads * a.head_dim, nkv = a.n_kv_heads * a.head_dim;
+    const bool bf = a.dtype == MASSV_BF16;
+    LayerGemms g = {};
+    g.qkv.n[0] = nq; g.qkv.n[1] = nkv; g.qkv.n[2] = nkv; g.qkv.M = M; g.qkv.K = H;
+    g.qkv.epilogue = bf ? EPI_PARTIAL : EPI_STORE; g.qkv.kid = MASSV_K_QKV;
+    g.op.n[0] = H; g.op.M = M; g.op.K = nq; g.op.epilogue = bf ? EPI_PARTIAL : EPI_RESIDUAL; g.op.kid = MASSV_K_OPROJ;
+    g.gu.n[0] = F; g.gu.n[1] = F; g.gu.M = M; g.gu.K = H; g.gu.epilogue = EPI_GATED; g.gu.kid = MASSV_K_GATEUP;
+    g.dn.n[0] = H; g.dn.M = M; g.dn.K = F; g.dn.epilogue = bf ? EPI_PARTIAL : EPI_RESIDUAL; g.dn.kid = MASSV_K_DOWN;
+    GemmArgs* all[4] = {&g.qkv, &g.op, &g.gu, &g.dn};
+    for (GemmArgs* p : all) { p->act = d.act; p->dtype = a.dtype; }
+    return g;
+}
 
 static LayerLayout layer_layout(const massv_layer_desc& d) {
     const massv_attn_desc& a = d.attn;
     const size_t es = a.dtype == MASSV_F32 ? 4 : 2;
     const size_t M = (size_t)a.batch * a.n_query;
     const size_t nq = (size_t)a.n_q_heads * a.head_dim, nkv = (size_t)a.n_kv_heads * a.head_dim;
-    LayerLayout l;
-    size_t o = 0;
     const bool bf = a.dtype == MASSV_BF16;          // bf16 activations that feed a projection are kept in operand order
     const size_t Mp = bf ? (M + 15) / 16 * 16 : M;
+    const LayerGemms g = layer_gemms(d);
+    size_t part = gemm_partial_bytes(g.qkv);
+    if (gemm_partial_bytes(g.op) > part) part = gemm_partial_bytes(g.op);
+    if (gemm_partial_bytes(g.dn) > part) part = gemm_partial_bytes(g.dn);
+    LayerLayout l;
+    size_t o = 0;
     l.xn = o;   o = align_up(o + Mp * d.hidden * es, 256);
-    l.qkv = o;  o = align_up(o + M * (nq + 2 * nkv) * es, 256);
+    l.qkv = o;  o = align_up(o + (bf ? 0 : M * (nq + 2 * nkv) * es), 256);
     l.qrot = o; o = align_up(o + M * nq * es, 256);
     l.attn = o; o = align_up(o + Mp * nq * es, 256);
     l.h = o;    o = align_up(o + Mp * d.mlp * es, 256);
-    l.gu = o;   o = align_up(o + (a.dtype == MASSV_F32 ? M * 2 * d.mlp * 4 : 0), 256);
+    l.gu = o;   o = align_up(o + (bf ? 0 : M * 2 * d.mlp * 4), 256);
+    l.partial = o; o = align_up(o + part, 256);
     l.attn_ws = o; o = align_up(o + attention_workspace(a), 256);
     l.total = o;
     return l;
@@ -38,6 +62,7 @@ static int check_layer_desc(const massv_layer_desc* d) {
         const int M = d->attn.batch * d->attn.n_query;
         if (M > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
         if (d->hidden % 32 || d->mlp % 32 || (d->attn.n_q_heads * d->attn.head_dim) % 32) return MASSV_EUNSUPPORTED;
+        if (d->hidden > 8192) return MASSV_EUNSUPPORTED;
     }
     return MASSV_OK;
 }
@@ -65,49 +90,52 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
     const massv_attn_desc& a = desc->attn;
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
-    const int M = a.batch * a.n_query, H = desc->hidden, F = desc->mlp;
-    const int nq = a.n_q_heads * a.head_dim, nkv = a.n_kv_heads * a.head_dim;
+    const int M = a.batch * a.n_query, H = desc->hidden;
     const bool bias = desc->qkv_bias != 0;
+    const bool bf = a.dtype == MASSV_BF16;
+    const size_t Mp = (size_t)(M + 15) / 16 * 16;
+    float* partial = (float*)(ws + lay.partial);
 
-    GemmArgs qkv = {};
-    qkv.x = ws + lay.xn;
-    qkv.w[0] = w->wq; qkv.w[1] = w->wk; qkv.w[2] = w->wv;
-    qkv.bias[0] = bias ? w->bq : nullptr; qkv.bias[1] = bias ? w->bk : nullptr; qkv.bias[2] = bias ? w->bv : nullptr;
-    qkv.n[0] = nq; qkv.n[1] = nkv; qkv.n[2] = nkv;
-    qkv.y = ws + lay.qkv; qkv.M = M; qkv.K = H; qkv.epilogue = EPI_STORE; qkv.kid = MASSV_K_QKV; qkv.act = desc->act; qkv.dtype = a.dtype;
-
-    GemmArgs op = {};
-    op.x = ws + lay.attn; op.w[0] = w->wo; op.n[0] = H; op.residual = x; op.y = x;
-    op.M = M; op.K = nq; op.epilogue = EPI_RESIDUAL; op.kid = MASSV_K_OPROJ; op.act = desc->act; op.dtype = a.dtype;
-
-    GemmArgs gu = {};
-    gu.x = ws + lay.xn; gu.w[0] = w->wg; gu.w[1] = w->wu; gu.n[0] = F; gu.n[1] = F;
-    gu.y = ws + lay.h; gu.scratch = ws + lay.gu;
-    gu.M = M; gu.K = H; gu.epilogue = EPI_GATED; gu.kid = MASSV_K_GATEUP; gu.act = desc->act; gu.dtype = a.dtype;
-
-    GemmArgs dn = {};
-    dn.x = ws + lay.h; dn.w[0] = w->wd; dn.n[0] = H; dn.residual = x; dn.y = x;
-    dn.M = M; dn.K = F; dn.epilogue = EPI_RESIDUAL; dn.kid = MASSV_K_DOWN; dn.act = desc->act; dn.dtype = a.dtype;
+    LayerGemms g = layer_gemms(*desc);
+    g.qkv.x = ws + lay.xn;
+    g.qkv.w[0] = w->wq; g.qkv.w[1] = w->wk; g.qkv.w[2] = w->wv;
+    if (!bf) { g.qkv.bias[0] = bias ? w->bq : nullptr; g.qkv.bias[1] = bias ? w->bk : nullptr; g.qkv.bias[2] = bias ? w->bv : nullptr; }
+    g.qkv.y = bf ? (void*)partial : (void*)(ws + lay.qkv);
+    g.op.x = ws + lay.attn; g.op.w[0] = w->wo; g.op.residual = x; g.op.y = bf ? (void*)partial : x;
+    g.gu.x = ws + lay.xn; g.gu.w[0] = w->wg; g.gu.w[1] = w->wu; g.gu.y = ws + lay.h; g.gu.scratch = ws + lay.gu;
+    g.dn.x = ws + lay.h; g.dn.w[0] = w->wd; g.dn.residual = x; g.dn.y = bf ? (void*)partial : x;
 
     // shape checks for every projection before the first launch
-    if ((rc = gemm_supported(qkv)) != MASSV_OK) return rc;
-    if ((rc = gemm_supported(op)) != MASSV_OK) return rc;
-    if ((rc = gemm_supported(gu)) != MASSV_OK) return rc;
-    if ((rc = gemm_supported(dn)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(g.qkv)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(g.op)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(g.gu)) != MASSV_OK) return rc;
+    if ((rc = gemm_supported(g.dn)) != MASSV_OK) return rc;
 
-    const bool bf = a.dtype == MASSV_BF16;
-    rc = bf ? launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)
-            : launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st);
-    if (rc != MASSV_OK) return rc;
-    if ((rc = launch_gemm(qkv, st)) != MASSV_OK) return rc;
-    if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a, desc->rope_theta, st)) != MASSV_OK) return rc;
-    if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, bf, st)) != MASSV_OK) return rc;
-    if ((rc = launch_gemm(op, st)) != MASSV_OK) return rc;
-    rc = bf ? launch_rmsnorm_packed(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, st)
-            : launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st);
-    if (rc != MASSV_OK) return rc;
-    if ((rc = launch_gemm(gu, st)) != MASSV_OK) return rc;
-    return launch_gemm(dn, st);
+    if (!bf) {
+        if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+        if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a, desc->rope_theta, st)) != MASSV_OK) return rc;
+        if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, false, st)) != MASSV_OK) return rc;
+        if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+        if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
+        return launch_gemm(g.dn, st);
+    }
+    // bf16: the narrow projections leave fp32 partial sums per K slab; the row-wise kernel that has to
+    // run next anyway (rotary + append, residual + norm) sums them.
+    const size_t wq = (size_t)(a.n_q_heads + 2 * a.n_kv_heads) * a.head_dim;
+    if ((rc = launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
+    if ((rc = launch_qkv_finish(partial, gemm_plan(g.qkv).slabs, Mp * wq, bias ? w->bq : nullptr, bias ? w->bk : nullptr,
+                                bias ? w->bv : nullptr, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a,
+                                desc->rope_theta, st)) != MASSV_OK) return rc;
+    if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, true, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
+    if ((rc = launch_residual_finish(partial, gemm_plan(g.op).slabs, Mp * H, x, w->ln2, ws + lay.xn, M, H,
+                                     desc->norm_eps, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
+    if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
+    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, nullptr, nullptr, M, H, desc->norm_eps, st);
 }
 
 static int check_lm_head(int32_t M, int32_t H, int32_t V, int32_t dtype) {
