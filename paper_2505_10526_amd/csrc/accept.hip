@@ -30,7 +30,7 @@ struct RowPartial { float m; int arg; double s; };
 struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d; };
 struct ChunkMass { double r, p; };
 
-struct TempScale { float hi, lo; double inv; };   // 1/T split so that d*hi + d*lo is d/T to ~1 ulp
+struct TempScale { float hi, lo; double inv; };   // log2(e)/T split in two floats: d*hi + d*lo is d*log2(e)/T to ~1 ulp; inv = 1/T
 
 // d is a logit minus the row maximum (<= 0, possibly -inf for padding or a
 // zero-probability token); clamping to the largest finite value keeps
@@ -103,7 +103,7 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
         float acc = 0.f;
         if (m > -INFINITY) {
 #pragma unroll
-            for (int k = 0; k < kAccPerThread; ++k) acc += expf(scaled(x[k] - m, ts));
+            for (int k = 0; k < kAccPerThread; ++k) acc += exp2f(scaled(x[k] - m, ts));
         }
         s = wave_sum((double)acc);
         if ((tid & (kWave - 1)) == 0) ss[w] = s;
@@ -118,29 +118,41 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
     }
 }
 
-__global__ __launch_bounds__(kWave)
+constexpr int kDecideThreads = 256;
+
+__global__ __launch_bounds__(kDecideThreads)
 void accept_decide_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                           const int* __restrict__ tokens, const float* __restrict__ uniforms,
                           int B, int gamma, int V, int C, double inv_t, int greedy,
                           const RowPartial* __restrict__ part, SeqSel* __restrict__ sel,
                           int* __restrict__ n_accepted, int* __restrict__ out_tokens) {
-    const int b = blockIdx.x, t = threadIdx.x, Q = gamma + 1;
+    const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
+    const int wave = tid / kWave, lane = tid % kWave;
     __shared__ double row_m[2 * kMaxGamma + 1], row_s[2 * kMaxGamma + 1];
     __shared__ int row_arg[2 * kMaxGamma + 1];
     const int nrows = greedy ? Q : Q + gamma;
-    if (t < nrows) {
+    // one wave per row: lanes take the chunk partials, merged by a fixed shuffle tree
+    for (int t = wave; t < nrows; t += kDecideThreads / kWave) {
         const int r = (t < Q) ? b * Q + t : B * Q + b * gamma + (t - Q);
         const RowPartial* p = part + (size_t)r * C;
-        float m = p[0].m; int am = p[0].arg;
-        for (int c = 1; c < C; ++c) if (p[c].m > m) { m = p[c].m; am = p[c].arg; }   // ascending chunks: first index wins
+        float m = -INFINITY; int am = INT_MAX;
+        for (int c = lane; c < C; c += kWave) argmax_merge(m, am, p[c].m, p[c].arg);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(m, o, kWave);
+            const int oi = __shfl_xor(am, o, kWave);
+            argmax_merge(m, am, ov, oi);
+        }
         double s = 0.0;
-        if (!greedy)
-            for (int c = 0; c < C; ++c)
+        if (!greedy) {
+            for (int c = lane; c < C; c += kWave)
                 if (p[c].m > -INFINITY) s += p[c].s * exp(((double)p[c].m - (double)m) * inv_t);
-        row_m[t] = (double)m; row_s[t] = s; row_arg[t] = am;
+            s = wave_sum(s);
+        }
+        if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
     }
     __syncthreads();
-    if (t != 0) return;
+    if (tid != 0) return;
 
     int n = 0;
     for (; n < gamma; ++n) {
@@ -176,7 +188,7 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
 
 // Unnormalised-to-normalised probability of one logit in double.
 __device__ inline double prob_of(float logit, double m, double inv_s, TempScale ts) {
-    return (double)expf(scaled(logit - (float)m, ts)) * inv_s;
+    return (double)exp2f(scaled(logit - (float)m, ts)) * inv_s;
 }
 
 __global__ __launch_bounds__(kAccThreads)
@@ -212,6 +224,25 @@ void residual_mass_kernel(const float* __restrict__ target, const float* __restr
     }
 }
 
+// Inclusive scan of one double per thread over the 256 threads of the workgroup (thread order).
+// Returns the inclusive prefix; *total receives the sum over all threads.
+__device__ inline double block_scan_incl(double v, double* wave_tot, double* total) {
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const double t = __shfl_up(v, o, kWave);
+        if (lane >= o) v += t;
+    }
+    __syncthreads();                                  // wave_tot may still be read from a previous call
+    if (lane == kWave - 1) wave_tot[wave] = v;
+    __syncthreads();
+    double off = 0.0, tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < kAccThreads / kWave; ++w) { if (w < wave) off += wave_tot[w]; tot += wave_tot[w]; }
+    *total = tot;
+    return v + off;
+}
+
 __global__ __launch_bounds__(kAccThreads)
 void residual_pick_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                           const float* __restrict__ uniforms, int gamma, int V, int C, TempScale ts,
@@ -219,34 +250,47 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
                           int* __restrict__ out_tokens) {
     const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
     const SeqSel s = sel[b];
-    __shared__ int sh_chunk, sh_use_p, sh_first, sh_last;
-    __shared__ double sh_prefix, sh_thr;
-    __shared__ double sh_tot[kAccThreads];
-    if (tid == 0) {
-        const ChunkMass* m = mass + (size_t)b * C;
-        double tr = 0.0, tp = 0.0;
-        for (int c = 0; c < C; ++c) { tr += m[c].r; tp += m[c].p; }
-        const int use_p = s.bonus || !(tr > 0.0);
-        const double total = use_p ? tp : tr;
-        const double thr = (double)uniforms[b * Q + gamma] * total;
-        double run = 0.0; int chunk = -1, last_pos = 0;
-        for (int c = 0; c < C; ++c) {
+    __shared__ double wave_tot[kAccThreads / kWave];
+    __shared__ int sh_chunk, sh_lastpos, sh_first, sh_last;
+    __shared__ double sh_prefix;
+    if (tid == 0) { sh_chunk = INT_MAX; sh_lastpos = -1; sh_first = INT_MAX; sh_last = -1; }
+
+    // ---- which chunk: every thread owns `per` consecutive chunks ----
+    const ChunkMass* m = mass + (size_t)b * C;
+    const int per = (C + kAccThreads - 1) / kAccThreads;
+    double my_r = 0.0, my_p = 0.0;
+    for (int i = 0; i < per; ++i) { const int c = tid * per + i; if (c < C) { my_r += m[c].r; my_p += m[c].p; } }
+    double tot_r, tot_p;
+    const double incl_r = block_scan_incl(my_r, wave_tot, &tot_r);
+    const double incl_p = block_scan_incl(my_p, wave_tot, &tot_p);
+    const int use_p = s.bonus || !(tot_r > 0.0);
+    const double total = use_p ? tot_p : tot_r;
+    const double thr = (double)uniforms[b * Q + gamma] * total;
+    {
+        double run = (use_p ? incl_p - my_p : incl_r - my_r);      // mass ahead of this thread's chunks
+        for (int i = 0; i < per; ++i) {
+            const int c = tid * per + i;
+            if (c >= C) break;
             const double v = use_p ? m[c].p : m[c].r;
-            if (v > 0.0) last_pos = c;
-            if (run + v > thr) { chunk = c; break; }
+            if (v > 0.0) atomicMax(&sh_lastpos, c);
+            if (run + v > thr) { atomicMin(&sh_chunk, c); break; }
             run += v;
         }
-        if (chunk < 0) {                      // rounding kept the sum from crossing: last chunk with mass
-            chunk = last_pos;
-            run = 0.0;
-            for (int c = 0; c < chunk; ++c) run += use_p ? m[c].p : m[c].r;
-        }
-        sh_chunk = chunk; sh_use_p = use_p; sh_prefix = run; sh_thr = thr;
-        sh_first = INT_MAX; sh_last = -1;
     }
     __syncthreads();
-    const int base = sh_chunk * kAccChunk + tid * kAccPerThread;
-    const int use_p = sh_use_p;
+    const int chunk = (sh_chunk != INT_MAX) ? sh_chunk : (sh_lastpos >= 0 ? sh_lastpos : 0);
+    {   // mass ahead of the chosen chunk, recomputed by its owner in the same order as above
+        const int owner = chunk / per;
+        if (tid == owner) {
+            double run = (use_p ? incl_p - my_p : incl_r - my_r);
+            for (int c = owner * per; c < chunk; ++c) run += use_p ? m[c].p : m[c].r;
+            sh_prefix = run;
+        }
+    }
+    __syncthreads();
+
+    // ---- which token inside the chunk: every thread owns 16 consecutive tokens ----
+    const int base = chunk * kAccChunk + tid * kAccPerThread;
     const float* trow = target + ((size_t)b * Q + s.n) * V;
     const float* drow = draft + ((size_t)b * gamma + (s.bonus ? 0 : s.n)) * V;
     const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
@@ -262,17 +306,14 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
         }
         r[k] = v; tot += v;
     }
-    sh_tot[tid] = tot;
-    __syncthreads();
-    double before = sh_prefix;                // mass of everything ahead of this thread's 16 tokens
-    for (int i = 0; i < tid; ++i) before += sh_tot[i];
+    double chunk_total;
+    double run = block_scan_incl(tot, wave_tot, &chunk_total) - tot + sh_prefix;
     int first = INT_MAX, last = -1;
-    double run = before;
 #pragma unroll
     for (int k = 0; k < kAccPerThread; ++k) {
         run += r[k];
         if (r[k] > 0.0) last = base + k;
-        if (first == INT_MAX && run > sh_thr && base + k < V) first = base + k;
+        if (first == INT_MAX && run > thr && base + k < V) first = base + k;
     }
     if (first != INT_MAX) atomicMin(&sh_first, first);
     if (last >= 0) atomicMax(&sh_last, last);
@@ -327,8 +368,9 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     TempScale ts; ts.hi = 1.f; ts.lo = 0.f; ts.inv = 1.0;
     if (!greedy) {
         ts.inv = 1.0 / (double)temperature;
-        ts.hi = (float)ts.inv;
-        ts.lo = (float)(ts.inv - (double)ts.hi);
+        const double k2 = ts.inv * 1.4426950408889634074;      // log2(e) / T
+        ts.hi = (float)k2;
+        ts.lo = (float)(k2 - (double)ts.hi);
     }
     const int vec = (V % 4 == 0) && ((uintptr_t)target_logits % 16 == 0) &&
                     (greedy || (uintptr_t)draft_logits % 16 == 0);
@@ -338,7 +380,7 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     hipLaunchKernelGGL(accept_stats_kernel, dim3(C, rows), dim3(kAccThreads), 0, st,
                        target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
     trace_end(MASSV_K_ACCEPT_STATS, st);
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kWave), 0, st,
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
                        target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
                        greedy, part, sel, n_accepted, out_tokens);
     if (!greedy) {

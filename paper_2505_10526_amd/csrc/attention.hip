@@ -126,6 +126,7 @@ struct AttnParams {
 template <int D, int MT>
 __global__ __launch_bounds__(kAttnThreads)
 void attention_mfma_kernel(AttnParams p) {
+    constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);   // two K/V register sets fit beside Q and the accumulators
     constexpr int KS = D / 32;          // k-steps of the score product
     constexpr int NT = D / 16;          // 16-dim tiles of the output
     constexpr int ROWS = MT * 16;
@@ -172,9 +173,8 @@ void attention_mfma_kernel(AttnParams p) {
     const bf16_t* kbase = p.kc + bg * (size_t)p.l_max * D;
     const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D;
 
-    for (int blk = blk_begin + wave; blk < blk_end; blk += kAttnWaves) {
-        // ---- loads: K tile t holds keys {8c + 4t + i}; lane lr = 4c + i ----
-        bf16x8 kreg[2][KS], vreg[NT];
+    // ---- loads of one 32-key block: K tile t holds keys {8c + 4t + i}; lane lr = 4c + i ----
+    auto load_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int key = blk * kBlk + (lr / 4) * 8 + t * 4 + (lr % 4);
@@ -186,7 +186,9 @@ void attention_mfma_kernel(AttnParams p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             vreg[nt] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kBlk);
+    };
 
+    auto process_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
         const bool tail = (blk + 1) * kBlk > n_total;         // block reaches past the valid rows
         if (tail) {
 #pragma unroll
@@ -240,6 +242,29 @@ void attention_mfma_kernel(AttnParams p) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[nt], pv, acc[mt][nt], 0, 0, 0);
+        }
+    };
+
+    // The wave's blocks are blk_begin + wave, + 4, ...; the loads of the next one are in flight while
+    // the current one is processed (two register sets), unless the tile shape leaves no registers.
+    if constexpr (PREFETCH) {
+        bf16x8 k0[2][KS], v0[NT], k1[2][KS], v1[NT];
+        int blk = blk_begin + wave;
+        if (blk < blk_end) load_block(blk, k0, v0);
+        while (blk < blk_end) {
+            int nb = blk + kAttnWaves;
+            if (nb < blk_end) load_block(nb, k1, v1);
+            process_block(blk, k0, v0);
+            if (nb >= blk_end) break;
+            blk = nb + kAttnWaves;
+            if (blk < blk_end) load_block(blk, k0, v0);
+            process_block(nb, k1, v1);
+        }
+    } else {
+        bf16x8 k0[2][KS], v0[NT];
+        for (int blk = blk_begin + wave; blk < blk_end; blk += kAttnWaves) {
+            load_block(blk, k0, v0);
+            process_block(blk, k0, v0);
         }
     }
 
