@@ -48,7 +48,7 @@ __device__ inline void load_chunk_interleaved(const float* __restrict__ row, int
     for (int j = 0; j < 4; ++j) {
         int idx = base + (j * kAccThreads + tid) * 4;
         if (vec && idx + 3 < V) {
-            float4 v = *reinterpret_cast<const float4*>(row + idx);
+            float4 v = ldg_stream(reinterpret_cast<const float4*>(row + idx));
             x[j * 4 + 0] = v.x; x[j * 4 + 1] = v.y; x[j * 4 + 2] = v.z; x[j * 4 + 3] = v.w;
         } else {
 #pragma unroll
@@ -152,26 +152,30 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
         if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
     }
     __syncthreads();
-    if (tid != 0) return;
+    if (wave != 0) return;
 
-    int n = 0;
-    for (; n < gamma; ++n) {
-        const int tok = tokens[b * gamma + n];
-        if (tok < 0 || tok >= V) break;
-        bool ok;
-        if (greedy) {
-            ok = (tok == row_arg[n]);
+    // lane i examines draft i: all gathers and comparisons in parallel, then the first failure ends the chain
+    bool ok = true;
+    int tok = 0;
+    if (lane < gamma) {
+        tok = tokens[b * gamma + lane];
+        if (tok < 0 || tok >= V) {
+            ok = false;
+        } else if (greedy) {
+            ok = (tok == row_arg[lane]);
         } else {
-            const double lt = (double)target[((size_t)b * Q + n) * V + tok];
-            const double ld = (double)draft[((size_t)b * gamma + n) * V + tok];
-            const double p = exp((lt - row_m[n]) * inv_t) / row_s[n];
-            const double q = exp((ld - row_m[Q + n]) * inv_t) / row_s[Q + n];
-            const double u = (double)uniforms[b * Q + n];
+            const double lt = (double)target[((size_t)b * Q + lane) * V + tok];
+            const double ld = (double)draft[((size_t)b * gamma + lane) * V + tok];
+            const double p = exp((lt - row_m[lane]) * inv_t) / row_s[lane];
+            const double q = exp((ld - row_m[Q + lane]) * inv_t) / row_s[Q + lane];
+            const double u = (double)uniforms[b * Q + lane];
             ok = (p >= q) || (u * q < p);
         }
-        if (!ok) break;
-        out_tokens[b * Q + n] = tok;
     }
+    const unsigned long long fail = __ballot(!ok);
+    const int n = fail ? __ffsll((long long)fail) - 1 : gamma;      // gamma <= 15 < 64
+    if (lane < n) out_tokens[b * Q + lane] = tok;
+    if (lane != 0) return;
     n_accepted[b] = n;
     for (int i = n + 1; i < Q; ++i) out_tokens[b * Q + i] = -1;
     if (greedy) {

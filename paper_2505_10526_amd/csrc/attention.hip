@@ -185,7 +185,7 @@ void attention_mfma_kernel(AttnParams p) {
         const bf16_t* vb = vbase + (size_t)blk * D * kBlk + lc * 8;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-            vreg[nt] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kBlk);
+            vreg[nt] = ldg_stream(reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kBlk));
     };
 
     auto process_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {

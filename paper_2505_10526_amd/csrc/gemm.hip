@@ -9,6 +9,8 @@
 //     32 k) and X as the B operand (32 k x 16 rows): every lane's W operand is
 //     one 16-byte global load from a row of W; four lanes cover 64 contiguous
 //     bytes of a row and the four k-steps of a 128-element chunk cover 256.
+//     (Plain cached loads: consecutive k-steps share 128-byte lines, and the
+//     non-temporal hint made this kernel slower.)
 //   * X comes from L2, and those reads -- not HBM -- were the first limiter.
 //     Two remedies: X is kept in operand order (packed_index) so a wave reads it
 //     as contiguous 1 KB blocks, and a wave owns NT = 4..10 feature tiles per
@@ -60,6 +62,7 @@ __device__ inline bf16x8 ld8(const bf16_t* p, bool ok) {
     bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
 }
+
 
 // Tiles of LDS reduced per round: at most 48 KB of fp32 fragments at a time.
 template <int MT, int NT>
