@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-extra", action="store_true", help="skip the attention/accept bandwidth section")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU checker timing")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device copies (a kernel of known traffic, for scaling profiler byte counters)")
     return ap.parse_args()
 
 
@@ -180,7 +182,7 @@ def main():
     gateup_bytes = 2 * F * H * 2 + M * H * 2 + M * F * 2          # Wg, Wu (bf16) + X read + H written
     weight_bytes_step = N * (nq * H + 2 * nkv * H + H * nq + 3 * F * H) * 2 + V * H * 2
     achieved = gateup_bytes / (k_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<MT,NT,WK,EPI_GATED> (gate/up projection + activation)",
+    roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel<MT,NT,EPI_GATED> (gate/up projection + activation)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "bytes_per_launch": gateup_bytes, "avg_launch_us": round(k_ms * 1e3, 2),
@@ -200,6 +202,13 @@ def main():
         "roofline": roofline,
     }
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_extra:
         result["extra"] = extra_bandwidth(torch, binding, synth, dev, gen)
     if not args.no_cpu:
