@@ -114,9 +114,10 @@ def main():
         vc = binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d))
         for b in range(B):                       # image rows carry a wider spread (input recipe)
             kc[b, :, : int(n_img_h[b])] *= 1.5
+        w = binding.pack_layer_weights(w)           # projection matrices -> streaming layout (load-time step)
         layers.append((w, binding.layer_weights(w), kc, vc))
     final_norm = randn(H, std=0.1, mean=1.0)
-    w_lm = randn(V, H, std=0.02)
+    w_lm = binding.weight_pack(randn(V, H, std=0.02))
     x0 = randn(B, Q, H)
     x = torch.empty_like(x0)
     logits = torch.empty((M, V), dtype=torch.float32, device=dev)

@@ -43,6 +43,17 @@
  *   row-major [B][n_kv][L_max][d] tensor into this layout.
  *   The leading rows of a sequence's cache are its image-token positions
  *   followed by text positions (Section 2.2); the kernels treat both alike.
+ *
+ * Weight layout
+ *   Every projection matrix W[N][K] (wq, wk, wv, wo, wg, wu, wd, w_lm) is passed in the library's
+ *   STREAMING layout, produced once per matrix by massv_weight_pack() from the usual row-major
+ *   [out][in] tensor (weights are static during decoding, so this is a load-time step):
+ *     f32   row-major, unchanged;
+ *     bf16  [N/16][K/32][64][8]: for each tile of 16 output features and each step of 32 inputs, the
+ *           64 lanes' matrix-instruction operands back to back -- element (n, k) at
+ *           (((n/16)*(K/32) + k/32)*64 + (n%16) + 16*((k%32)/8))*8 + k%8 -- so that a wavefront
+ *           streams a tile as one contiguous run of whole cache lines.  Needs N % 16 == 0, K % 32 == 0.
+ *   Norm gains and biases are plain vectors.
  */
 #ifndef MASSV_VERIFY_H
 #define MASSV_VERIFY_H
@@ -112,6 +123,10 @@ int massv_v_cache_pack(const void* src_row_major, void* dst_blocked,
                        int32_t batch, int32_t n_kv_heads, int32_t l_max, int32_t head_dim,
                        int32_t dtype, void* stream);
 
+/* Row-major W[N][K] -> streaming layout (see "Weight layout").  src and dst hold N*K elements and
+ * must not overlap.  bf16: MASSV_EUNSUPPORTED unless N % 16 == 0 and K % 32 == 0. */
+int massv_weight_pack(const void* src_row_major, void* dst, int32_t N, int32_t K, int32_t dtype, void* stream);
+
 /* ------------------------------------------------------------------------- */
 /* verify_layer: one pre-norm decoder layer of the parallel forward over the  */
 /* M = B*Q new positions ("one forward call" of Section 2.1; the paper does    */
@@ -133,7 +148,8 @@ typedef struct {
     float   rope_theta;
 } massv_layer_desc;
 
-/* All weights are DEVICE pointers of the layer's dtype, row-major [out][in]. */
+/* All weights are DEVICE pointers of the layer's dtype; matrices in the streaming layout of
+ * massv_weight_pack(), shapes given as [out][in]. */
 typedef struct {
     const void* ln1;          /* [H] */
     const void* wq;           /* [n_q*d][H] */
@@ -172,7 +188,7 @@ int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* 
 /* ------------------------------------------------------------------------- */
 size_t massv_lm_head_logits_workspace(int32_t M, int32_t H, int32_t V, int32_t dtype);
 
-/* x [M][H] (dtype) in; final_norm [H] (dtype) or NULL; w_lm [V][H] (dtype) in;
+/* x [M][H] (dtype) in; final_norm [H] (dtype) or NULL; w_lm [V][H] (dtype, streaming layout) in;
  * logits [M][V] float32 out.  bf16 path: M <= MASSV_MAX_ROWS, H % 32 == 0, V % 16 == 0. */
 int massv_lm_head_logits(const void* x, const void* final_norm, const void* w_lm,
                          float* logits, int32_t M, int32_t H, int32_t V,

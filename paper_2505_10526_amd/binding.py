@@ -27,7 +27,7 @@ EXPORTS = [
     "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack",
     "massv_verify_layer_workspace", "massv_verify_layer",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
-    "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel",
+    "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS = range(9)
 
@@ -91,6 +91,8 @@ def load():
     lib.massv_spec_accept_workspace.argtypes = [i32, i32, i32]
     lib.massv_spec_accept.restype = C.c_int
     lib.massv_spec_accept.argtypes = [vp, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.massv_weight_pack.restype = C.c_int
+    lib.massv_weight_pack.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.massv_trace_kernel.restype = C.c_int
     lib.massv_trace_kernel.argtypes = [C.c_int, vp, vp]
     _lib = lib
@@ -202,9 +204,28 @@ def layer_desc(cfg: LayerConfig, batch, n_query, l_max, dtype) -> LayerDesc:
     return LayerDesc(a, cfg.hidden, cfg.mlp, cfg.act, int(bool(cfg.qkv_bias)), cfg.norm_eps, cfg.rope_theta)
 
 
+MATRIX_FIELDS = ["wq", "wk", "wv", "wo", "wg", "wu", "wd"]
+
+
+def weight_pack(w: torch.Tensor) -> torch.Tensor:
+    """Row-major [N, K] projection matrix -> the library's streaming layout (same shape and dtype on
+    the torch side; the element order is the library's).  Done by the library's own kernel."""
+    _need(w, "w")
+    N, K = w.shape
+    out = torch.empty_like(w)
+    _check(load().massv_weight_pack(_ptr(w), _ptr(out), N, K, dtype_code(w), _stream()), "massv_weight_pack")
+    return out
+
+
+def pack_layer_weights(w: dict) -> dict:
+    """Copy of a layer's weight dict with every projection matrix in streaming layout."""
+    return {k: (weight_pack(v) if (k in MATRIX_FIELDS and v is not None) else v) for k, v in w.items()}
+
+
 def layer_weights(w: dict) -> LayerWeights:
-    """dict of CUDA tensors (keys ln1, wq, ... wd; biases may be None) -> struct of device pointers.
-    The caller keeps the tensors alive."""
+    """dict of CUDA tensors (keys ln1, wq, ... wd; matrices already in streaming layout, see
+    pack_layer_weights; biases may be None) -> struct of device pointers.  The caller keeps the
+    tensors alive."""
     lw = LayerWeights()
     for name in WEIGHT_FIELDS:
         t = w.get(name)
@@ -220,8 +241,8 @@ def verify_layer_workspace(desc: LayerDesc) -> int:
 
 def verify_layer(cfg: LayerConfig, w, x, pos, k_cache, v_cache, kv_len, ws=None, desc=None, lw=None):
     """One decoder layer over the new positions; x [B,Q,H] is updated in place
-    and the caches receive the new rows.  `w` is a dict of tensors or a prebuilt
-    LayerWeights."""
+    and the caches receive the new rows.  `w` is a dict of tensors (matrices in
+    streaming layout, see pack_layer_weights) or a prebuilt LayerWeights."""
     lib = load()
     _need(x, "x")
     _need(pos, "pos", torch.int32)
@@ -241,7 +262,7 @@ def verify_layer(cfg: LayerConfig, w, x, pos, k_cache, v_cache, kv_len, ws=None,
 
 
 def lm_head_logits(x, final_norm, w_lm, norm_eps=1e-6, out=None, ws=None):
-    """x [M,H] (or [B,Q,H]); w_lm [V,H]; returns float32 logits [M,V]."""
+    """x [M,H] (or [B,Q,H]); w_lm [V,H] in streaming layout (weight_pack); returns float32 logits [M,V]."""
     lib = load()
     _need(x, "x")
     _need(w_lm, "w_lm", x.dtype)

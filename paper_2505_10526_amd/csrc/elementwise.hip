@@ -28,7 +28,7 @@ void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g, T* __restr
 
 // bf16 rows -> RMSNorm -> operand-order output (see packed_index).  g == nullptr: no
 // normalisation, the row is only re-laid out.  H % 8 == 0.
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(1024)
 void rmsnorm_pack_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g, bf16_t* __restrict__ y,
                          int H, float eps, int mt_count) {
     const int m = blockIdx.x, tid = threadIdx.x;
@@ -37,18 +37,21 @@ void rmsnorm_pack_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict_
     float rstd = 1.f;
     if (g) {
         float ss = 0.f;
-        for (int k8 = tid; k8 < groups; k8 += 256) {
+        for (int k8 = tid; k8 < groups; k8 += 1024) {
             const bf16x8 v = xr[k8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ss += f * f; }
         }
         ss = wave_sum(ss);
-        __shared__ float part[4];
+        __shared__ float part[16];
         if ((tid & 63) == 0) part[tid >> 6] = ss;
         __syncthreads();
-        rstd = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)H + eps);
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += part[w];
+        rstd = 1.0f / sqrtf(tot / (float)H + eps);
     }
-    for (int k8 = tid; k8 < groups; k8 += 256) {
+    for (int k8 = tid; k8 < groups; k8 += 1024) {
         bf16x8 v = xr[k8];
         if (g) {
             const bf16x8 gv = reinterpret_cast<const bf16x8*>(g)[k8];
@@ -60,7 +63,7 @@ void rmsnorm_pack_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict_
 }
 
 int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(M), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y,
+    hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(M), dim3(1024), 0, st, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y,
                        H, eps, (M + 15) / 16);
     return launch_status();
 }
@@ -146,9 +149,16 @@ __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs
     const int width = (n_q + 2 * n_kv) * d;
     const size_t col = (size_t)head * d + j;
     float x1 = 0.f, x2 = 0.f;
-    for (int s = 0; s < n_slabs; ++s) {                 // fixed order: deterministic
-        const float* p = partial + s * slab_stride + (size_t)m * width + col;
-        x1 += p[0]; x2 += p[half];
+    for (int s0 = 0; s0 < n_slabs; s0 += 8) {           // 8 slabs' loads in flight at once; summed in slab order
+        float t1[8], t2[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = s0 + u < n_slabs;
+            const float* p = partial + (size_t)(ok ? s0 + u : 0) * slab_stride + (size_t)m * width + col;
+            t1[u] = ok ? p[0] : 0.f; t2[u] = ok ? p[half] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { x1 += t1[u]; x2 += t2[u]; }
     }
     const bf16_t* bias = head < n_q ? bq : head < n_q + n_kv ? bk : bv;
     if (bias) {
@@ -189,57 +199,65 @@ int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, con
 }
 
 // bf16 path: residual add of a projection's partial sums, optionally followed by RMSNorm into operand
-// order.  One workgroup per row; a thread owns up to 4 groups of 8 consecutive features (H <= 8192).
-__global__ __launch_bounds__(256)
+// order.  One workgroup of 1024 threads per row; a thread owns one group of 8 consecutive features
+// (H <= 8192), so a row's loads are all in flight at once.
+constexpr int kFinishThreads = 1024;
+
+__global__ __launch_bounds__(kFinishThreads)
 void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
                             bf16_t* __restrict__ x, const bf16_t* __restrict__ ln, bf16_t* __restrict__ xn,
                             int H, float eps, int mt_count) {
     const int m = blockIdx.x, tid = threadIdx.x;
-    const int groups = H / 8;
-    float v[4][8];
+    const int k8 = tid;
+    const bool live = k8 < H / 8;
+    float v[8];
     float ss = 0.f;
+    if (live) {
+        const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
+        float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < n_slabs; s0 += 4) {              // 4 slabs' loads in flight at once; summed in slab order
+            floatx4 p0[4], p1[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int k8 = tid + r * 256;
-        if (k8 < groups) {
-            const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
-            float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < n_slabs; ++s) {
-                const floatx4* p = reinterpret_cast<const floatx4*>(partial + s * slab_stride + (size_t)m * H + k8 * 8);
-                const floatx4 p0 = p[0], p1 = p[1];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { add[e] += p0[e]; add[4 + e] += p1[e]; }
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = s0 + u < n_slabs;
+                const floatx4* p = reinterpret_cast<const floatx4*>(partial + (size_t)(ok ? s0 + u : 0) * slab_stride +
+                                                                    (size_t)m * H + k8 * 8);
+                p0[u] = ok ? p[0] : floatx4{0.f, 0.f, 0.f, 0.f};
+                p1[u] = ok ? p[1] : floatx4{0.f, 0.f, 0.f, 0.f};
             }
-            bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { v[r][e] = (float)xv[e] + add[e]; o[e] = (bf16_t)v[r][e]; ss += v[r][e] * v[r][e]; }
-            *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { add[e] += p0[u][e]; add[4 + e] += p1[u][e]; }
         }
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { v[e] = (float)xv[e] + add[e]; o[e] = (bf16_t)v[e]; ss += v[e] * v[e]; }
+        *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
     }
     if (!ln) return;
     ss = wave_sum(ss);
-    __shared__ float part[4];
+    __shared__ float part[kFinishThreads / kWave];
     if ((tid & 63) == 0) part[tid >> 6] = ss;
     __syncthreads();
-    const float rstd = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)H + eps);
+    float tot = 0.f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int k8 = tid + r * 256;
-        if (k8 < groups) {
-            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(ln + k8 * 8);
-            bf16x8 o;
+    for (int w = 0; w < kFinishThreads / kWave; ++w) tot += part[w];
+    const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+    if (live) {
+        const bf16x8 gv = *reinterpret_cast<const bf16x8*>(ln + k8 * 8);
+        bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(v[r][e] * rstd * (float)gv[e]);
-            *reinterpret_cast<bf16x8*>(xn + packed_index(m, k8 * 8, mt_count)) = o;
-        }
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(v[e] * rstd * (float)gv[e]);
+        *reinterpret_cast<bf16x8*>(xn + packed_index(m, k8 * 8, mt_count)) = o;
     }
 }
 
 int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* ln,
                            void* xn_packed, int M, int H, float eps, hipStream_t st) {
-    if (H % 8 || H > 8192) return MASSV_EUNSUPPORTED;
-    hipLaunchKernelGGL(residual_finish_kernel, dim3(M), dim3(256), 0, st, partial, n_slabs, slab_stride, (bf16_t*)x,
-                       (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
+    if (H % 8 || H > 8 * kFinishThreads) return MASSV_EUNSUPPORTED;
+    hipLaunchKernelGGL(residual_finish_kernel, dim3(M), dim3(kFinishThreads), 0, st, partial, n_slabs, slab_stride,
+                       (bf16_t*)x, (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
     return launch_status();
 }
 
@@ -285,9 +303,37 @@ __global__ void v_pack_kernel(const T* __restrict__ src, T* __restrict__ dst, si
     dst[o] = src[(bg * l_max + j) * d + c];
 }
 
+// Row-major bf16 W[N][K] -> streaming layout: one thread per 16-byte destination chunk.
+__global__ void weight_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, size_t chunks, int K) {
+    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= chunks) return;
+    const int lane = (int)(o % 64);
+    const size_t t2 = o / 64;
+    const int ksteps = K / 32;
+    const int ks = (int)(t2 % ksteps);
+    const size_t tile = t2 / ksteps;
+    const size_t n = tile * 16 + (lane % 16);
+    const int k = ks * 32 + (lane / 16) * 8;
+    *reinterpret_cast<bf16x8*>(dst + o * 8) = *reinterpret_cast<const bf16x8*>(src + n * K + k);
+}
+
 }  // namespace massv
 
 using namespace massv;
+
+extern "C" int massv_weight_pack(const void* src, void* dst, int32_t N, int32_t K, int32_t dtype, void* stream) {
+    if (!src || !dst || N < 1 || K < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == MASSV_F32)
+        return hipMemcpyAsync(dst, src, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st) == hipSuccess ? MASSV_OK : MASSV_ELAUNCH;
+    if (N % 16 || K % 32) return MASSV_EUNSUPPORTED;
+    const size_t chunks = (size_t)N * K / 8;
+    const size_t blocks = (chunks + 255) / 256;
+    if (blocks > 0x7fffffffu) return MASSV_EUNSUPPORTED;
+    hipLaunchKernelGGL(weight_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, chunks, K);
+    return launch_status();
+}
 
 extern "C" int massv_v_cache_pack(const void* src, void* dst, int32_t batch, int32_t n_kv_heads,
                                   int32_t l_max, int32_t head_dim, int32_t dtype, void* stream) {

@@ -27,7 +27,7 @@ def run_layer(s, B, Q, kv_len, n_img, seed, kv_std=1.0, compress=True, w_std=0.0
     lm = round_up(kv.l_max, 32)
     kd = to_dev(pad_rows(kv.k, lm), s.dtype)
     vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype))
-    wd = {k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()}
+    wd = binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()})
     xd = to_dev(x, s.dtype)
     binding.verify_layer(cfg_of(s), wd, xd, i32(pos), kd, vd, i32(kv.kv_len))
     torch.cuda.synchronize()
@@ -79,10 +79,10 @@ def test_lm_head_small(shape, M):
     x = synth.normal((M, shape.hidden), 1.0, 7, 60, dtype=shape.dtype)
     ref = O.lm_head_logits(x, lw["final_norm"], lw["w_lm"], shape.norm_eps)
     got = binding.lm_head_logits(to_dev(x, shape.dtype), to_dev(lw["final_norm"], shape.dtype),
-                                 to_dev(lw["w_lm"], shape.dtype), shape.norm_eps)
+                                 binding.weight_pack(to_dev(lw["w_lm"], shape.dtype)), shape.norm_eps)
     assert_close(got.cpu().numpy(), ref, TOL_BF16 if shape.dtype == "bf16" else TOL_F32, "logits")
     ref2 = O.lm_head_logits(x, None, lw["w_lm"], shape.norm_eps)
-    got2 = binding.lm_head_logits(to_dev(x, shape.dtype), None, to_dev(lw["w_lm"], shape.dtype))
+    got2 = binding.lm_head_logits(to_dev(x, shape.dtype), None, binding.weight_pack(to_dev(lw["w_lm"], shape.dtype)))
     assert_close(got2.cpu().numpy(), ref2, TOL_BF16 if shape.dtype == "bf16" else TOL_F32, "logits no norm")
 
 
@@ -93,13 +93,13 @@ def test_lm_head_full_vocab(shape, M):
     x = synth.normal((M, shape.hidden), 1.0, 8, 60, dtype=shape.dtype)
     ref = O.lm_head_logits(x, lw["final_norm"], lw["w_lm"], shape.norm_eps)
     got = binding.lm_head_logits(to_dev(x, shape.dtype), to_dev(lw["final_norm"], shape.dtype),
-                                 to_dev(lw["w_lm"], shape.dtype), shape.norm_eps)
+                                 binding.weight_pack(to_dev(lw["w_lm"], shape.dtype)), shape.norm_eps)
     assert_close(got.cpu().numpy(), ref, TOL_BF16, "logits")
 
 
 def test_layer_repeatable_bits():
     s = synth.QWEN7B
-    w = {k: (None if v is None else to_dev(v, s.dtype)) for k, v in synth.layer_weights(s, 9).items()}
+    w = binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in synth.layer_weights(s, 9).items()})
     kv = synth.kv_cache(s, 2, 6, [64, 200], [10, 50], 9, junk_tail=False)
     pos = i32(synth.positions(kv.kv_len, kv.n_img, 6))
     outs = []
