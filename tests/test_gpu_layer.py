@@ -68,6 +68,18 @@ def test_qwen7b_layer_b8_ragged():
     run_layer(synth.QWEN7B, 8, 6, rng.integers(100, 400, 8), rng.integers(20, 100, 8), seed=5)
 
 
+def test_qwen7b_layer_b8_full_lengths():
+    """Config 3's layer at its real sizes: B=8, gamma=5, per-sequence lengths U[1024, 2048] with 256-1024
+    image rows -- the launch configuration bench.py times (same tile counts, K slabs and attention splits)."""
+    rng = np.random.default_rng(0)
+    run_layer(synth.QWEN7B, 8, 6, rng.integers(1024, 2049, 8), rng.integers(256, 1025, 8), seed=10)
+
+
+def test_gemma12b_layer_b4_full_length():
+    """Config 4 at its real sizes: B=4, KV length 4096 with 256 leading image rows."""
+    run_layer(synth.GEMMA12B, 4, 6, [4096] * 4, [256] * 4, seed=11)
+
+
 def test_gemma12b_layer_b4():
     """Config 4's layer: hidden 3840, 16/8 heads, d=256, GeGLU 15360, no bias, B=4 (M=24)."""
     run_layer(synth.GEMMA12B, 4, 6, [300, 256, 50, 411], [256, 200, 10, 256], seed=6)
