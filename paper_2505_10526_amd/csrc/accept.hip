@@ -3,8 +3,10 @@
 //
 // The work is a stream over the logits, bound by HBM bandwidth:
 //   pass 1  accept_stats   every target row (and, at T > 0, every draft row) is
-//                          cut into chunks of 4096 logits; one workgroup per
-//                          (row, chunk) produces {max, first arg-max, sum exp}.
+//                          cut into chunks of 1024 logits; one WAVE per (row,
+//                          chunk) produces {max, first arg-max, sum exp} with
+//                          shuffles only -- no LDS, no barriers, waves retire
+//                          independently.
 //           accept_decide  one wave per sequence merges the chunk partials in
 //                          chunk order, gathers the logits of the drafted
 //                          tokens and walks the accept chain.
@@ -21,9 +23,10 @@
 
 namespace massv {
 
-constexpr int kAccThreads = 256;
-constexpr int kAccPerThread = 16;
-constexpr int kAccChunk = kAccThreads * kAccPerThread;   // 4096 logits
+constexpr int kAccThreads = 256;                          // 4 waves, one chunk each
+constexpr int kAccPerLane = 16;                           // 4 float4 loads per lane
+constexpr int kAccChunk = kWave * kAccPerLane;            // 1024 logits per wave
+constexpr int kPickPerThread = kAccChunk / kAccThreads;   // 4 consecutive logits per thread when locating the token
 constexpr int kMaxGamma = 15;
 
 struct RowPartial { float m; int arg; double s; };
@@ -40,13 +43,13 @@ __device__ inline float scaled(float d, TempScale ts) {
     return fmaf(d, ts.lo, d * ts.hi);
 }
 
-// Interleaved, coalesced read of one chunk: x[j*4+e] is element
-// base + (j*256 + tid)*4 + e; out-of-range elements read as -inf.
-__device__ inline void load_chunk_interleaved(const float* __restrict__ row, int V, int base,
-                                              int tid, int vec, float (&x)[kAccPerThread]) {
+// Coalesced read of one chunk by one wave: x[j*4+e] is element base + (j*64 + lane)*4 + e;
+// out-of-range elements read as -inf.
+__device__ inline void load_chunk(const float* __restrict__ row, int V, int base, int lane, int vec,
+                                  float (&x)[kAccPerLane]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        int idx = base + (j * kAccThreads + tid) * 4;
+        int idx = base + (j * kWave + lane) * 4;
         if (vec && idx + 3 < V) {
             float4 v = ldg_stream(reinterpret_cast<const float4*>(row + idx));
             x[j * 4 + 0] = v.x; x[j * 4 + 1] = v.y; x[j * 4 + 2] = v.z; x[j * 4 + 3] = v.w;
@@ -57,8 +60,8 @@ __device__ inline void load_chunk_interleaved(const float* __restrict__ row, int
     }
 }
 
-__device__ inline int interleaved_index(int base, int tid, int k) {
-    return base + ((k >> 2) * kAccThreads + tid) * 4 + (k & 3);
+__device__ inline int chunk_index(int base, int lane, int k) {
+    return base + ((k >> 2) * kWave + lane) * 4 + (k & 3);
 }
 
 // (value, index) ordering: larger value first, then smaller index.
@@ -70,60 +73,47 @@ __global__ __launch_bounds__(kAccThreads)
 void accept_stats_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                          int n_target_rows, int V, int C, TempScale ts, int greedy, int vec,
                          RowPartial* __restrict__ part) {
-    const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    const int c = blockIdx.x * (kAccThreads / kWave) + threadIdx.x / kWave, r = blockIdx.y;
+    if (c >= C) return;                                      // whole wave leaves together
     const float* row = (r < n_target_rows) ? target + (size_t)r * V
                                            : draft + (size_t)(r - n_target_rows) * V;
     const int base = c * kAccChunk;
-    float x[kAccPerThread];
-    load_chunk_interleaved(row, V, base, tid, vec, x);
+    float x[kAccPerLane];
+    load_chunk(row, V, base, lane, vec, x);
 
     float m = x[0];
-    int am = interleaved_index(base, tid, 0);
+    int am = chunk_index(base, lane, 0);
 #pragma unroll
-    for (int k = 1; k < kAccPerThread; ++k)
-        if (x[k] > m) { m = x[k]; am = interleaved_index(base, tid, k); }
+    for (int k = 1; k < kAccPerLane; ++k)
+        if (x[k] > m) { m = x[k]; am = chunk_index(base, lane, k); }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         float ov = __shfl_xor(m, o, kWave);
         int oi = __shfl_xor(am, o, kWave);
         argmax_merge(m, am, ov, oi);
     }
-    __shared__ float sm[kAccThreads / kWave];
-    __shared__ int sa[kAccThreads / kWave];
-    __shared__ double ss[kAccThreads / kWave];
-    const int w = tid / kWave;
-    if ((tid & (kWave - 1)) == 0) { sm[w] = m; sa[w] = am; }
-    __syncthreads();
-    m = sm[0]; am = sa[0];
-#pragma unroll
-    for (int i = 1; i < kAccThreads / kWave; ++i) argmax_merge(m, am, sm[i], sa[i]);
-
     double s = 0.0;
     if (!greedy) {
         float acc = 0.f;
         if (m > -INFINITY) {
 #pragma unroll
-            for (int k = 0; k < kAccPerThread; ++k) acc += exp2f(scaled(x[k] - m, ts));
+            for (int k = 0; k < kAccPerLane; ++k) acc += exp2f(scaled(x[k] - m, ts));
         }
         s = wave_sum((double)acc);
-        if ((tid & (kWave - 1)) == 0) ss[w] = s;
-        __syncthreads();
-        s = ss[0];
-#pragma unroll
-        for (int i = 1; i < kAccThreads / kWave; ++i) s += ss[i];
     }
-    if (tid == 0) {
+    if (lane == 0) {
         RowPartial p; p.m = m; p.arg = am; p.s = s;
         part[(size_t)r * C + c] = p;
     }
 }
 
-constexpr int kDecideThreads = 256;
+constexpr int kDecideThreads = 1024;                      // 16 waves: one row of the sequence each
 
 __global__ __launch_bounds__(kDecideThreads)
 void accept_decide_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                           const int* __restrict__ tokens, const float* __restrict__ uniforms,
-                          int B, int gamma, int V, int C, double inv_t, int greedy,
+                          int B, int gamma, int V, int C, double inv_t, float scale2, int greedy,
                           const RowPartial* __restrict__ part, SeqSel* __restrict__ sel,
                           int* __restrict__ n_accepted, int* __restrict__ out_tokens) {
     const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
@@ -146,7 +136,7 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
         double s = 0.0;
         if (!greedy) {
             for (int c = lane; c < C; c += kWave)
-                if (p[c].m > -INFINITY) s += p[c].s * exp(((double)p[c].m - (double)m) * inv_t);
+                if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
             s = wave_sum(s);
         }
         if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
@@ -199,16 +189,18 @@ __global__ __launch_bounds__(kAccThreads)
 void residual_mass_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                           int gamma, int V, int C, TempScale ts, int vec,
                           const SeqSel* __restrict__ sel, ChunkMass* __restrict__ mass) {
-    const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, Q = gamma + 1;
+    const int lane = threadIdx.x % kWave, Q = gamma + 1;
+    const int c = blockIdx.x * (kAccThreads / kWave) + threadIdx.x / kWave, b = blockIdx.y;
+    if (c >= C) return;
     const SeqSel s = sel[b];
     const int base = c * kAccChunk;
-    float xt[kAccPerThread], xd[kAccPerThread];
-    load_chunk_interleaved(target + ((size_t)b * Q + s.n) * V, V, base, tid, vec, xt);
-    if (!s.bonus) load_chunk_interleaved(draft + ((size_t)b * gamma + s.n) * V, V, base, tid, vec, xd);
+    float xt[kAccPerLane], xd[kAccPerLane];
+    load_chunk(target + ((size_t)b * Q + s.n) * V, V, base, lane, vec, xt);
+    if (!s.bonus) load_chunk(draft + ((size_t)b * gamma + s.n) * V, V, base, lane, vec, xd);
     const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
     double sr = 0.0, sp = 0.0;
 #pragma unroll
-    for (int k = 0; k < kAccPerThread; ++k) {
+    for (int k = 0; k < kAccPerLane; ++k) {
         const double p = prob_of(xt[k], s.m_t, inv_st, ts);
         sp += p;
         if (!s.bonus) {
@@ -217,13 +209,8 @@ void residual_mass_kernel(const float* __restrict__ target, const float* __restr
         }
     }
     sr = wave_sum(sr); sp = wave_sum(sp);
-    __shared__ double s_r[kAccThreads / kWave], s_p[kAccThreads / kWave];
-    const int w = tid / kWave;
-    if ((tid & (kWave - 1)) == 0) { s_r[w] = sr; s_p[w] = sp; }
-    __syncthreads();
-    if (tid == 0) {
-        ChunkMass m; m.r = 0.0; m.p = 0.0;
-        for (int i = 0; i < kAccThreads / kWave; ++i) { m.r += s_r[i]; m.p += s_p[i]; }
+    if (lane == 0) {
+        ChunkMass m; m.r = sr; m.p = sp;
         mass[(size_t)b * C + c] = m;
     }
 }
@@ -293,15 +280,15 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
     }
     __syncthreads();
 
-    // ---- which token inside the chunk: every thread owns 16 consecutive tokens ----
-    const int base = chunk * kAccChunk + tid * kAccPerThread;
+    // ---- which token inside the chunk: every thread owns 4 consecutive tokens ----
+    const int base = chunk * kAccChunk + tid * kPickPerThread;
     const float* trow = target + ((size_t)b * Q + s.n) * V;
     const float* drow = draft + ((size_t)b * gamma + (s.bonus ? 0 : s.n)) * V;
     const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
-    double r[kAccPerThread];
+    double r[kPickPerThread];
     double tot = 0.0;
 #pragma unroll
-    for (int k = 0; k < kAccPerThread; ++k) {
+    for (int k = 0; k < kPickPerThread; ++k) {
         const int idx = base + k;
         double v = 0.0;
         if (idx < V) {
@@ -314,7 +301,7 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
     double run = block_scan_incl(tot, wave_tot, &chunk_total) - tot + sh_prefix;
     int first = INT_MAX, last = -1;
 #pragma unroll
-    for (int k = 0; k < kAccPerThread; ++k) {
+    for (int k = 0; k < kPickPerThread; ++k) {
         run += r[k];
         if (r[k] > 0.0) last = base + k;
         if (first == INT_MAX && run > thr && base + k < V) first = base + k;
@@ -381,15 +368,15 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     const int rows = greedy ? B * Q : B * (Q + gamma);
 
     trace_begin(MASSV_K_ACCEPT_STATS, st);
-    hipLaunchKernelGGL(accept_stats_kernel, dim3(C, rows), dim3(kAccThreads), 0, st,
+    hipLaunchKernelGGL(accept_stats_kernel, dim3((C + 3) / 4, rows), dim3(kAccThreads), 0, st,
                        target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
     trace_end(MASSV_K_ACCEPT_STATS, st);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
                        target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
-                       greedy, part, sel, n_accepted, out_tokens);
+                       ts.hi, greedy, part, sel, n_accepted, out_tokens);
     if (!greedy) {
         trace_begin(MASSV_K_RESIDUAL_MASS, st);
-        hipLaunchKernelGGL(residual_mass_kernel, dim3(C, B), dim3(kAccThreads), 0, st,
+        hipLaunchKernelGGL(residual_mass_kernel, dim3((C + 3) / 4, B), dim3(kAccThreads), 0, st,
                            target_logits, draft_logits, gamma, V, C, ts, vec, sel, mass);
         trace_end(MASSV_K_RESIDUAL_MASS, st);
         hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,

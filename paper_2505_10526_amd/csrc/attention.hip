@@ -126,7 +126,10 @@ struct AttnParams {
 template <int D, int MT>
 __global__ __launch_bounds__(kAttnThreads)
 void attention_mfma_kernel(AttnParams p) {
-    constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);   // two K/V register sets fit beside Q and the accumulators
+    // Two K/V register sets (the next block's loads fly while this one is used) only where they fit:
+    // with 3-4 row tiles at d = 128 the second set spilled and the kernel ran 30 % slower.
+    constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);
+    constexpr bool QLDS = false;                   // Q operand tiles in LDS instead of registers (measured: no gain)
     constexpr int KS = D / 32;          // k-steps of the score product
     constexpr int NT = D / 16;          // 16-dim tiles of the output
     constexpr int ROWS = MT * 16;
@@ -145,7 +148,9 @@ void attention_mfma_kernel(AttnParams p) {
     const int first_masked_blk = L / kBlk;      // blocks before it hold cached positions only
 
     // ---- Q operand: lane (lr, lc) holds Q[row = 16 mt + lr][32 ks + 8 lc .. +8] ----
-    bf16x8 qreg[MT][KS];
+    extern __shared__ float s_dyn[];             // [ROWS][LDS_STRIDE] merge buffer, then (QLDS) the Q operand tiles
+    bf16x8* q_lds = reinterpret_cast<bf16x8*>(s_dyn + ROWS * LDS_STRIDE);      // [MT][KS][64]
+    bf16x8 qreg[QLDS ? 1 : MT][QLDS ? 1 : KS];
     int qi[MT];                                 // query position of this lane's row in tile mt (clamped)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -153,13 +158,20 @@ void attention_mfma_kernel(AttnParams p) {
         const int i = r / G, hh = r % G;
         qi[mt] = i < p.Q ? i : p.Q - 1;
         const bf16_t* qr = p.q + (((size_t)b * p.Q + (i < p.Q ? i : 0)) * p.n_q + g * G + hh) * D;
+        if (QLDS && (mt % kAttnWaves) != wave) continue;          // each tile is fetched by one wave
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
             if (r < rows) v = *reinterpret_cast<const bf16x8*>(qr + ks * 32 + lc * 8);
-            qreg[mt][ks] = v;
+            if constexpr (QLDS) q_lds[(mt * KS + ks) * kWave + lane] = v;
+            else qreg[mt][ks] = v;
         }
     }
+    if constexpr (QLDS) __syncthreads();
+    auto q_operand = [&](int mt, int ks) -> bf16x8 {
+        if constexpr (QLDS) return q_lds[(mt * KS + ks) * kWave + lane];
+        else return qreg[mt][ks];
+    };
 
     floatx4 acc[MT][NT];
     float m_run[MT], l_run[MT];
@@ -205,8 +217,9 @@ void attention_mfma_kernel(AttnParams p) {
             floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qreg[mt][ks], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qreg[mt][ks], s1, 0, 0, 0);
+                const bf16x8 qv = q_operand(mt, ks);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qv, s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qv, s1, 0, 0, 0);
             }
             float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
 #pragma unroll
@@ -248,17 +261,20 @@ void attention_mfma_kernel(AttnParams p) {
     // The wave's blocks are blk_begin + wave, + 4, ...; the loads of the next one are in flight while
     // the current one is processed (two register sets), unless the tile shape leaves no registers.
     if constexpr (PREFETCH) {
-        bf16x8 k0[2][KS], v0[NT], k1[2][KS], v1[NT];
+        bf16x8 kc[2][KS], vc[NT], kn[2][KS], vn[NT];
         int blk = blk_begin + wave;
-        if (blk < blk_end) load_block(blk, k0, v0);
-        while (blk < blk_end) {
-            int nb = blk + kAttnWaves;
-            if (nb < blk_end) load_block(nb, k1, v1);
-            process_block(blk, k0, v0);
-            if (nb >= blk_end) break;
-            blk = nb + kAttnWaves;
-            if (blk < blk_end) load_block(blk, k0, v0);
-            process_block(nb, k1, v1);
+        if (blk < blk_end) load_block(blk, kc, vc);
+#pragma unroll 1
+        for (; blk < blk_end; blk += kAttnWaves) {
+            const int nb = blk + kAttnWaves;
+            if (nb < blk_end) load_block(nb, kn, vn);
+            process_block(blk, kc, vc);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) vc[nt] = vn[nt];
         }
     } else {
         bf16x8 k0[2][KS], v0[NT];
@@ -272,7 +288,7 @@ void attention_mfma_kernel(AttnParams p) {
     __shared__ float s_m[kAttnWaves][ROWS];
     __shared__ float s_l[kAttnWaves][ROWS];
     __shared__ float s_lt[ROWS];
-    extern __shared__ float s_o[];               // [ROWS][LDS_STRIDE]
+    float* s_o = s_dyn;                          // [ROWS][LDS_STRIDE]
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const float l = xor16_sum(l_run[mt]);
@@ -416,7 +432,7 @@ size_t attention_workspace(const massv_attn_desc& a) {
 
 template <int D, int MT>
 static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
-    const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float);
+    const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) ;
     trace_begin(MASSV_K_ATTENTION, st);
     hipLaunchKernelGGL((attention_mfma_kernel<D, MT>), dim3(p.n_split, a.n_kv_heads, a.batch), dim3(kAttnThreads),
                        lds, st, p);
