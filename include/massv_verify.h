@@ -229,10 +229,11 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
 /* Timing hook (diagnostic; for callers that want one kernel's duration        */
 /* without a profiler).  Arms a one-shot request on the CALLING THREAD: the    */
 /* next launch of kernel `kernel_id` made by a library call from this thread   */
-/* is bracketed by hipEventRecord(start_event) / hipEventRecord(stop_event) on */
-/* that call's stream, after which the request is gone.  Events are            */
-/* hipEvent_t created by the caller with timing enabled; the caller            */
-/* synchronises and reads hipEventElapsedTime.  kernel_id < 0 disarms.         */
+/* is issued with hipExtLaunchKernelGGL(start_event, stop_event), so the two   */
+/* events carry that kernel's own begin and end timestamps; the request is     */
+/* then gone.  Events are hipEvent_t created by the caller with timing         */
+/* enabled; the caller synchronises and reads hipEventElapsedTime.             */
+/* kernel_id < 0 disarms.                                                      */
 /* Do not arm while the stream is being captured into a graph.                 */
 /* ------------------------------------------------------------------------- */
 typedef enum {

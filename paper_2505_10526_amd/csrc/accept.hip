@@ -367,18 +367,14 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
                     (greedy || (uintptr_t)draft_logits % 16 == 0);
     const int rows = greedy ? B * Q : B * (Q + gamma);
 
-    trace_begin(MASSV_K_ACCEPT_STATS, st);
-    hipLaunchKernelGGL(accept_stats_kernel, dim3((C + 3) / 4, rows), dim3(kAccThreads), 0, st,
-                       target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
-    trace_end(MASSV_K_ACCEPT_STATS, st);
+    launch_traced(MASSV_K_ACCEPT_STATS, accept_stats_kernel, dim3((C + 3) / 4, rows), dim3(kAccThreads), 0, st,
+                  target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
                        target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
                        ts.hi, greedy, part, sel, n_accepted, out_tokens);
     if (!greedy) {
-        trace_begin(MASSV_K_RESIDUAL_MASS, st);
-        hipLaunchKernelGGL(residual_mass_kernel, dim3((C + 3) / 4, B), dim3(kAccThreads), 0, st,
-                           target_logits, draft_logits, gamma, V, C, ts, vec, sel, mass);
-        trace_end(MASSV_K_RESIDUAL_MASS, st);
+        launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + 3) / 4, B), dim3(kAccThreads), 0, st,
+                      target_logits, draft_logits, gamma, V, C, ts, vec, (const SeqSel*)sel, mass);
         hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,
                            target_logits, draft_logits, uniforms, gamma, V, C, ts, sel, mass, out_tokens);
     }

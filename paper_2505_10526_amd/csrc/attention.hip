@@ -433,16 +433,12 @@ size_t attention_workspace(const massv_attn_desc& a) {
 template <int D, int MT>
 static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
     const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) ;
-    trace_begin(MASSV_K_ATTENTION, st);
-    hipLaunchKernelGGL((attention_mfma_kernel<D, MT>), dim3(p.n_split, a.n_kv_heads, a.batch), dim3(kAttnThreads),
-                       lds, st, p);
-    trace_end(MASSV_K_ATTENTION, st);
-    if (p.n_split > 1) {
-        trace_begin(MASSV_K_ATTN_COMBINE, st);
-        hipLaunchKernelGGL((attention_combine_kernel<D>), dim3(a.n_q_heads, a.n_query, a.batch), dim3(D / 4), 0, st,
-                           p.part_o, p.part_ml, p.out, a.n_query, a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16, p.out_mt);
-        trace_end(MASSV_K_ATTN_COMBINE, st);
-    }
+    launch_traced(MASSV_K_ATTENTION, attention_mfma_kernel<D, MT>, dim3(p.n_split, a.n_kv_heads, a.batch),
+                  dim3(kAttnThreads), lds, st, p);
+    if (p.n_split > 1)
+        launch_traced(MASSV_K_ATTN_COMBINE, attention_combine_kernel<D>, dim3(a.n_q_heads, a.n_query, a.batch),
+                      dim3(D / 4), 0, st, (const float*)p.part_o, (const float*)p.part_ml, p.out, a.n_query,
+                      a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16, p.out_mt);
     return launch_status();
 }
 

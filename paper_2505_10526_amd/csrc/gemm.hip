@@ -301,30 +301,30 @@ size_t gemm_partial_bytes(const GemmArgs& g) {
 }
 
 template <int MT, int NT, int EPI>
-static void launch_stream(const GemmDev& d, const GemmPlan& p, hipStream_t st) {
+static void launch_stream(const GemmDev& d, const GemmPlan& p, int kid, hipStream_t st) {
     constexpr int GRP = ReduceGroup<MT, NT>::value;
     const size_t lds = (size_t)kGemmWaves * GRP * MT * kWave * sizeof(floatx4);
-    hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, EPI>), dim3(p.groups, p.slabs), dim3(kGemmWaves * kWave), lds, st, d);
+    launch_traced(kid, gemm_stream_kernel<MT, NT, EPI>, dim3(p.groups, p.slabs), dim3(kGemmWaves * kWave), lds, st, d);
 }
 
 template <int MT, int EPI>
-static int launch_stream_nt(const GemmDev& d, const GemmPlan& p, hipStream_t st) {
+static int launch_stream_nt(const GemmDev& d, const GemmPlan& p, int kid, hipStream_t st) {
     switch (p.nt) {
-        case 4: launch_stream<MT, 4, EPI>(d, p, st); return MASSV_OK;
-        case 7: if constexpr (EPI == EPI_PARTIAL && MT <= 3) { launch_stream<MT, 7, EPI>(d, p, st); return MASSV_OK; } break;
-        case 8: if constexpr (MT <= 3) { launch_stream<MT, 8, EPI>(d, p, st); return MASSV_OK; } break;
-        case 10: if constexpr (EPI != EPI_PARTIAL && MT <= 3) { launch_stream<MT, 10, EPI>(d, p, st); return MASSV_OK; } break;
+        case 4: launch_stream<MT, 4, EPI>(d, p, kid, st); return MASSV_OK;
+        case 7: if constexpr (EPI == EPI_PARTIAL && MT <= 3) { launch_stream<MT, 7, EPI>(d, p, kid, st); return MASSV_OK; } break;
+        case 8: if constexpr (MT <= 3) { launch_stream<MT, 8, EPI>(d, p, kid, st); return MASSV_OK; } break;
+        case 10: if constexpr (EPI != EPI_PARTIAL && MT <= 3) { launch_stream<MT, 10, EPI>(d, p, kid, st); return MASSV_OK; } break;
     }
     return MASSV_EUNSUPPORTED;
 }
 
 template <int EPI>
-static int launch_stream_epi(const GemmDev& d, int M, const GemmPlan& p, hipStream_t st) {
+static int launch_stream_epi(const GemmDev& d, int M, const GemmPlan& p, int kid, hipStream_t st) {
     switch ((M + 15) / 16) {
-        case 1: return launch_stream_nt<1, EPI>(d, p, st);
-        case 2: return launch_stream_nt<2, EPI>(d, p, st);
-        case 3: return launch_stream_nt<3, EPI>(d, p, st);
-        case 4: return launch_stream_nt<4, EPI>(d, p, st);
+        case 1: return launch_stream_nt<1, EPI>(d, p, kid, st);
+        case 2: return launch_stream_nt<2, EPI>(d, p, kid, st);
+        case 3: return launch_stream_nt<3, EPI>(d, p, kid, st);
+        case 4: return launch_stream_nt<4, EPI>(d, p, kid, st);
     }
     return MASSV_EUNSUPPORTED;
 }
@@ -363,13 +363,11 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
     d.chunks_per_slab = p.chunks_per_slab;
     d.slab_stride = (size_t)((g.M + 15) / 16 * 16) * N;
     int rc2 = MASSV_EUNSUPPORTED;
-    trace_begin(g.kid, st);
     switch (g.epilogue) {
-        case EPI_PARTIAL: rc2 = launch_stream_epi<EPI_PARTIAL>(d, g.M, p, st); break;
-        case EPI_GATED: rc2 = launch_stream_epi<EPI_GATED>(d, g.M, p, st); break;
-        case EPI_LOGITS: rc2 = launch_stream_epi<EPI_LOGITS>(d, g.M, p, st); break;
+        case EPI_PARTIAL: rc2 = launch_stream_epi<EPI_PARTIAL>(d, g.M, p, g.kid, st); break;
+        case EPI_GATED: rc2 = launch_stream_epi<EPI_GATED>(d, g.M, p, g.kid, st); break;
+        case EPI_LOGITS: rc2 = launch_stream_epi<EPI_LOGITS>(d, g.M, p, g.kid, st); break;
     }
-    trace_end(g.kid, st);
     if (rc2 != MASSV_OK) return rc2;
     return launch_status();
 }

@@ -3,21 +3,26 @@
 #pragma once
 
 #include "common.h"
+#include <hip/hip_ext.h>
 
 namespace massv {
 
 // ---- one-shot kernel timing hook (api.hip) ----
-// massv_trace_kernel() arms a request on the calling thread; the next launch
-// of that kernel records the caller's two events around it and disarms.
+// massv_trace_kernel() arms a request on the calling thread; the next launch of that kernel goes out
+// through hipExtLaunchKernelGGL with the caller's two events, which then carry the kernel's own begin
+// and end timestamps (the same clock a profiler's kernel trace reports), and the request is disarmed.
 struct TraceRequest { int kid; hipEvent_t start, stop; };
 TraceRequest& trace_request();
-inline void trace_begin(int kid, hipStream_t st) {
+
+template <typename K, typename... Args>
+inline void launch_traced(int kid, K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
     TraceRequest& t = trace_request();
-    if (t.kid == kid && kid >= 0) (void)hipEventRecord(t.start, st);
-}
-inline void trace_end(int kid, hipStream_t st) {
-    TraceRequest& t = trace_request();
-    if (t.kid == kid && kid >= 0) { (void)hipEventRecord(t.stop, st); t.kid = -1; }
+    if (kid >= 0 && t.kid == kid) {
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, t.start, t.stop, 0, args...);
+        t.kid = -1;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+    }
 }
 
 // ---- small row-wise kernels (elementwise.hip) ----
