@@ -25,6 +25,31 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gateup_kernel_hbm_traffic.json")
+KERNEL_SOURCES = ["paper_2505_10526_amd/csrc/gemm.hip", "paper_2505_10526_amd/csrc/common.h",
+                  "paper_2505_10526_amd/csrc/kernels.h"]
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the gate/up kernel from the stored FETCH_SIZE / WRITE_SIZE counter runs
+    (profiles/), or None when they were taken for another workload or the kernel's sources have changed."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+        if t.get("workload") != workload or t.get("kernel_source_sha256") != kernel_source_hash():
+            return None
+        return int(t["fetch_kib_per_dispatch"] * 1024 * t["fetch_scale"] + t["write_kib_per_dispatch"] * 1024 * t["write_scale"])
+    except Exception:
+        return None
 
 
 def parse():
@@ -185,7 +210,7 @@ def main():
     achieved = gateup_bytes / (k_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel<MT,NT,EPI_GATED> (gate/up projection + activation)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
                 "bytes_per_launch": gateup_bytes, "avg_launch_us": round(k_ms * 1e3, 2),
                 "launches_timed": len(ev),
                 "step_weight_stream_GBps": round(weight_bytes_step / (ms_per_step * 1e-3) / 1e9, 1)}
