@@ -129,6 +129,7 @@ void attention_mfma_kernel(AttnParams p) {
     // Two K/V register sets (the next block's loads fly while this one is used) only where they fit:
     // with 3-4 row tiles at d = 128 the second set spilled and the kernel ran 30 % slower.
     constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);
+    constexpr bool PIPE_K = !PREFETCH && (D * MT <= 512) && !(D == 256 && MT == 2);
     constexpr bool QLDS = false;                   // Q operand tiles in LDS instead of registers (measured: no gain)
     constexpr int KS = D / 32;          // k-steps of the score product
     constexpr int NT = D / 16;          // 16-dim tiles of the output
@@ -186,7 +187,7 @@ void attention_mfma_kernel(AttnParams p) {
     const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D;
 
     // ---- loads of one 32-key block: K tile t holds keys {8c + 4t + i}; lane lr = 4c + i ----
-    auto load_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
+    auto load_k = [&](int blk, bf16x8 (&kreg)[2][KS]) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int key = blk * kBlk + (lr / 4) * 8 + t * 4 + (lr % 4);
@@ -194,12 +195,27 @@ void attention_mfma_kernel(AttnParams p) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kreg[t][ks] = *reinterpret_cast<const bf16x8*>(kr + ks * 32);
         }
+    };
+    auto load_v = [&](int blk, bf16x8 (&vreg)[NT]) {
         const bf16_t* vb = vbase + (size_t)blk * D * kBlk + lc * 8;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             vreg[nt] = ldg_stream(reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kBlk));
     };
+    auto load_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
+        load_k(blk, kreg);
+        load_v(blk, vreg);
+    };
 
+    // One 32-key block.  Instruction count matters here: at 56-64 stacked rows the kernel was issuing
+    // VALU / MFMA instructions half of the time.  Hence
+    //   * all score products first, k-step outermost, so the 2*MT accumulators form independent chains;
+    //   * the exponent uses ONE fma per score (s*c - m) and the raw v_exp_f32;
+    //   * the running reference exponent m of a row is only raised when the block's maximum exceeds it
+    //     by more than kLazy (probabilities then stay <= 2^kLazy, harmless in bf16 / fp32): the common
+    //     block needs no cross-lane maximum and no rescaling of the output accumulators.  The result
+    //     acc / l does not depend on which reference is used.
+    constexpr float kLazy = 8.0f;
     auto process_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
         const bool tail = (blk + 1) * kBlk > n_total;         // block reaches past the valid rows
         if (tail) {
@@ -211,51 +227,57 @@ void attention_mfma_kernel(AttnParams p) {
         }
         const bool masked = blk >= first_masked_blk;
 
+        // ---- S^T tile pairs: lane holds keys 8 lc + (0..7) of query row 16 mt + lr ----
+        floatx4 s0[MT], s1[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { s0[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; s1[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const bf16x8 qv = q_operand(mt, ks);
+                s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qv, s0[mt], 0, 0, 0);
+                s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qv, s1[mt], 0, 0, 0);
+            }
+
+        bf16x8 pv[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            // ---- S^T tile pair: lane holds keys 8 lc + (0..7) of query row 16 mt + lr ----
-            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 qv = q_operand(mt, ks);
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qv, s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qv, s1, 0, 0, 0);
-            }
-            float sv[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sv[e] *= p.scale_log2;
+            float sv[8] = {s0[mt][0], s0[mt][1], s0[mt][2], s0[mt][3], s1[mt][0], s1[mt][1], s1[mt][2], s1[mt][3]};
             if (masked) {
                 const int last_visible = L + qi[mt];
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     if (blk * kBlk + lc * 8 + e > last_visible) sv[e] = -INFINITY;
             }
-            float mx = sv[0];
+            float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            mx *= p.scale_log2;                                // scale > 0: the maximum commutes with it
+            if (__any(mx > m_run[mt] + kLazy)) {               // some row of this tile needs a new reference
+                mx = xor16_max(mx);
+                if (mx > m_run[mt] + kLazy) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - mx);     // m_run = -inf gives 0
+                    l_run[mt] *= alpha;
 #pragma unroll
-            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-            mx = xor16_max(mx);
-            const float m_new = fmaxf(m_run[mt], mx);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m_run[mt] - m_safe);
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= alpha;
+                    m_run[mt] = mx;
+                }
+            }
+            const float neg_m = (m_run[mt] == -INFINITY) ? 0.f : -m_run[mt];
             float ps = 0.f;
-            bf16x8 pv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float pe = exp2f(sv[e] - m_safe);
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], p.scale_log2, neg_m));
                 ps += pe;
-                pv[e] = (bf16_t)pe;
+                pv[mt][e] = (bf16_t)pe;
             }
-            l_run[mt] = l_run[mt] * alpha + ps;
-            m_run[mt] = m_new;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= alpha;
-            }
-            // ---- O^T += V^T P^T ----
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[nt], pv, acc[mt][nt], 0, 0, 0);
+            l_run[mt] += ps;
         }
+        // ---- O^T += V^T P^T ----
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[nt], pv[mt], acc[mt][nt], 0, 0, 0);
     };
 
     // The wave's blocks are blk_begin + wave, + 4, ...; the loads of the next one are in flight while
@@ -275,6 +297,23 @@ void attention_mfma_kernel(AttnParams p) {
                 for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) vc[nt] = vn[nt];
+        }
+    } else if constexpr (PIPE_K) {
+        // Big tiles: only K is double-buffered.  V of this block is requested first, then K of the next
+        // block; the scores of this block (K already here) are formed while V is on its way.
+        bf16x8 kc[2][KS], kn[2][KS], v0[NT];
+        int blk = blk_begin + wave;
+        if (blk < blk_end) load_k(blk, kc);
+#pragma unroll 1
+        for (; blk < blk_end; blk += kAttnWaves) {
+            load_v(blk, v0);
+            const int nb = blk + kAttnWaves;
+            if (nb < blk_end) load_k(nb, kn);
+            process_block(blk, kc, v0);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
         }
     } else {
         bf16x8 k0[2][KS], v0[NT];
