@@ -127,9 +127,10 @@ template <int D, int MT>
 __global__ __launch_bounds__(kAttnThreads)
 void attention_mfma_kernel(AttnParams p) {
     // Two K/V register sets (the next block's loads fly while this one is used) only where they fit:
-    // with 3-4 row tiles at d = 128 the second set spilled and the kernel ran 30 % slower.
+    // with 3-4 row tiles at d = 128 a second set (or even a second K set alone) cost more in register
+    // shuffling than it hid -- the plain loop measured 95 us, K double-buffering 101 us, full double
+    // buffering 124 us on the 56-row, 8192-key shape.
     constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);
-    constexpr bool PIPE_K = !PREFETCH && (D * MT <= 512) && !(D == 256 && MT == 2);
     constexpr bool QLDS = false;                   // Q operand tiles in LDS instead of registers (measured: no gain)
     constexpr int KS = D / 32;          // k-steps of the score product
     constexpr int NT = D / 16;          // 16-dim tiles of the output
@@ -297,23 +298,6 @@ void attention_mfma_kernel(AttnParams p) {
                 for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) vc[nt] = vn[nt];
-        }
-    } else if constexpr (PIPE_K) {
-        // Big tiles: only K is double-buffered.  V of this block is requested first, then K of the next
-        // block; the scores of this block (K already here) are formed while V is on its way.
-        bf16x8 kc[2][KS], kn[2][KS], v0[NT];
-        int blk = blk_begin + wave;
-        if (blk < blk_end) load_k(blk, kc);
-#pragma unroll 1
-        for (; blk < blk_end; blk += kAttnWaves) {
-            load_v(blk, v0);
-            const int nb = blk + kAttnWaves;
-            if (nb < blk_end) load_k(nb, kn);
-            process_block(blk, kc, v0);
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
         }
     } else {
         bf16x8 k0[2][KS], v0[NT];
