@@ -2,8 +2,8 @@
 """Benchmark of the speculative-decoding verify step on one MI355X.
 
 One "step" is one whole verify step: 28 decoder layers over the B*(gamma+1)
-new positions, the vocabulary projection, and accept / resample -- every call
-goes through the C ABI of libmassv_verify.so.  Inputs are synthetic and
+new positions (massv_verify_layers), the vocabulary projection (massv_lm_head_logits) and accept /
+resample (massv_spec_accept) -- every call goes through the C ABI of libmassv_verify.so.  Inputs are synthetic and
 resident in HBM before the timed region.
 
     python bench.py [--steps K] [--warmup W] [--workload NAME] [--no-extra] [--no-cpu]
@@ -158,10 +158,12 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     T = wl["temperature"]
 
+    stack = binding.LayerStack([lw for (_, lw, _, _) in layers], [kc for (_, _, kc, _) in layers],
+                               [vc for (_, _, _, vc) in layers])
+
     def forward():
         x.copy_(x0)
-        for (w, lw, kc, vc) in layers:
-            binding.verify_layer(cfg, w, x, pos, kc, vc, kv_len, ws=ws, desc=desc, lw=lw)
+        binding.verify_layers(cfg, stack, x, pos, kv_len, l_max, ws=ws, desc=desc)      # all N layers, one call
         binding.lm_head_logits(x.view(M, H), final_norm, w_lm, shape.norm_eps, out=logits, ws=ws)
 
     # draft logits / tokens: the drafter's output is an INPUT of the verify step.  It is derived once from the
@@ -182,7 +184,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # one gate/up launch per step is bracketed by events (rotating over layers) -> live kernel duration
+    # one gate/up launch per step (the first layer's) carries the caller's events -> live kernel duration
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for a, b in ev:
         a.record(); b.record()
@@ -190,10 +192,8 @@ def main():
     t0 = time.perf_counter()
     for s in range(args.steps):
         x.copy_(x0)
-        for li, (w, lw, kc, vc) in enumerate(layers):
-            if li == s % N:
-                binding.trace_kernel(binding.K_GATEUP, ev[s][0], ev[s][1])
-            binding.verify_layer(cfg, w, x, pos, kc, vc, kv_len, ws=ws, desc=desc, lw=lw)
+        binding.trace_kernel(binding.K_GATEUP, ev[s][0], ev[s][1])
+        binding.verify_layers(cfg, stack, x, pos, kv_len, l_max, ws=ws, desc=desc)
         binding.lm_head_logits(x.view(M, H), final_norm, w_lm, shape.norm_eps, out=logits, ws=ws)
         binding.spec_accept(tl, draft_logits if T > 0 else None, draft_tokens, uniforms if T > 0 else None, T,
                             n_accepted=n_acc, out_tokens=out_tok, ws=ws)

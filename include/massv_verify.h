@@ -181,6 +181,15 @@ int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* 
                        const int32_t* kv_len,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same for n_layers consecutive layers that share one descriptor (a whole model's stack, or a
+ * slice of it): weights[l], k_caches[l], v_caches[l] belong to layer l; `weights`, `k_caches`,
+ * `v_caches` are HOST arrays (of structs / of device pointers) read before the call returns.  Equal to
+ * n_layers calls of massv_verify_layer, except that the norm opening layer l+1 is computed by the kernel
+ * that closes layer l from its un-rounded sum (one launch fewer per layer).  Workspace as for one layer. */
+int massv_verify_layers(const massv_layer_desc* desc, const massv_layer_weights* weights, int32_t n_layers,
+                        void* x, const int32_t* pos, void* const* k_caches, void* const* v_caches,
+                        const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------- */
 /* lm_head_logits: logits[m, v] = sum_k rmsnorm(x, final_norm)[m, k] * w_lm[v, k] */
 /* (no norm when final_norm == NULL).  Row i of sequence b gives the scores   */

@@ -25,7 +25,7 @@ MAX_ROWS = 64
 EXPORTS = [
     "massv_status_string", "massv_abi_version",
     "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack",
-    "massv_verify_layer_workspace", "massv_verify_layer",
+    "massv_verify_layer_workspace", "massv_verify_layer", "massv_verify_layers",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
     "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
 ]
@@ -83,6 +83,9 @@ def load():
     lib.massv_verify_layer.restype = C.c_int
     lib.massv_verify_layer.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    lib.massv_verify_layers.restype = C.c_int
+    lib.massv_verify_layers.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), i32, vp, vp,
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, vp, sz, vp]
     lib.massv_lm_head_logits_workspace.restype = sz
     lib.massv_lm_head_logits_workspace.argtypes = [i32, i32, i32, i32]
     lib.massv_lm_head_logits.restype = C.c_int
@@ -258,6 +261,37 @@ def verify_layer(cfg: LayerConfig, w, x, pos, k_cache, v_cache, kv_len, ws=None,
         ws = workspace(lib.massv_verify_layer_workspace(C.byref(desc)), x.device)
     _check(lib.massv_verify_layer(C.byref(desc), C.byref(lw), _ptr(x), _ptr(pos), _ptr(k_cache), _ptr(v_cache),
                                   _ptr(kv_len), _ptr(ws), ws.numel(), _stream()), "massv_verify_layer")
+    return x
+
+
+class LayerStack:
+    """Marshalled arguments of massv_verify_layers for a fixed stack of layers: arrays of weight
+    structs and cache pointers built once.  Keeps the tensors alive."""
+
+    def __init__(self, weights: list, k_caches: list, v_caches: list):
+        n = len(weights)
+        assert n == len(k_caches) == len(v_caches) and n >= 1
+        self.n = n
+        self._keep = (weights, k_caches, v_caches)
+        lws = [w if isinstance(w, LayerWeights) else layer_weights(w) for w in weights]
+        self.weights = (LayerWeights * n)(*lws)
+        self.k = (C.c_void_p * n)(*[t.data_ptr() for t in k_caches])
+        self.v = (C.c_void_p * n)(*[t.data_ptr() for t in v_caches])
+
+
+def verify_layers(cfg: LayerConfig, stack: LayerStack, x, pos, kv_len, l_max, ws=None, desc=None):
+    """All layers of `stack` over the new positions (one library call); x [B,Q,H] updated in place."""
+    lib = load()
+    _need(x, "x")
+    _need(pos, "pos", torch.int32)
+    _need(kv_len, "kv_len", torch.int32)
+    B, Q, _ = x.shape
+    if desc is None:
+        desc = layer_desc(cfg, B, Q, l_max, dtype_code(x))
+    if ws is None:
+        ws = workspace(lib.massv_verify_layer_workspace(C.byref(desc)), x.device)
+    _check(lib.massv_verify_layers(C.byref(desc), stack.weights, stack.n, _ptr(x), _ptr(pos), stack.k, stack.v,
+                                   _ptr(kv_len), _ptr(ws), ws.numel(), _stream()), "massv_verify_layers")
     return x
 
 

@@ -76,19 +76,21 @@ extern "C" size_t massv_verify_layer_workspace(const massv_layer_desc* desc) {
     return layer_layout(*desc).total;
 }
 
-extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
-                                  void* x, const int32_t* pos, void* k_cache, void* v_cache,
-                                  const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_layer_desc(desc);
-    if (rc != MASSV_OK) return rc;
-    if (!w || !x || !pos || !k_cache || !v_cache || !kv_len) return MASSV_EINVAL;
+static int check_layer_weights(const massv_layer_desc* desc, const massv_layer_weights* w) {
+    if (!w) return MASSV_EINVAL;
     if (!w->ln1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2 || !w->wg || !w->wu || !w->wd) return MASSV_EINVAL;
     if (desc->qkv_bias && (!w->bq || !w->bk || !w->bv)) return MASSV_EINVAL;
-    const LayerLayout lay = layer_layout(*desc);
-    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+    return MASSV_OK;
+}
 
+// One layer.  xn_ready: the workspace already holds rmsnorm(x, ln1) in operand order (written by the
+// previous layer's last kernel); next_ln: gains of the norm that follows this layer (the next layer's
+// ln1), fused into this layer's last kernel when not NULL.  Both are bf16-path options.
+static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w, void* x, const int32_t* pos,
+                     void* k_cache, void* v_cache, const int32_t* kv_len, void* workspace,
+                     const LayerLayout& lay, bool xn_ready, const void* next_ln, hipStream_t st) {
+    int rc;
     const massv_attn_desc& a = desc->attn;
-    hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
     const int M = a.batch * a.n_query, H = desc->hidden;
     const bool bias = desc->qkv_bias != 0;
@@ -124,7 +126,7 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
     // bf16: the narrow projections leave fp32 partial sums per K slab; the row-wise kernel that has to
     // run next anyway (rotary + append, residual + norm) sums them.
     const size_t wq = (size_t)(a.n_q_heads + 2 * a.n_kv_heads) * a.head_dim;
-    if ((rc = launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
+    if (!xn_ready && (rc = launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
     if ((rc = launch_qkv_finish(partial, gemm_plan(g.qkv).slabs, Mp * wq, bias ? w->bq : nullptr, bias ? w->bk : nullptr,
                                 bias ? w->bv : nullptr, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a,
@@ -135,7 +137,43 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
                                      desc->norm_eps, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
-    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, nullptr, nullptr, M, H, desc->norm_eps, st);
+    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, next_ln, next_ln ? ws + lay.xn : nullptr,
+                                  M, H, desc->norm_eps, st);
+}
+
+extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
+                                  void* x, const int32_t* pos, void* k_cache, void* v_cache,
+                                  const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer_desc(desc);
+    if (rc != MASSV_OK) return rc;
+    if (!x || !pos || !k_cache || !v_cache || !kv_len) return MASSV_EINVAL;
+    if ((rc = check_layer_weights(desc, w)) != MASSV_OK) return rc;
+    const LayerLayout lay = layer_layout(*desc);
+    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+    return run_layer(desc, w, x, pos, k_cache, v_cache, kv_len, workspace, lay, false, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int massv_verify_layers(const massv_layer_desc* desc, const massv_layer_weights* weights, int32_t n_layers,
+                                   void* x, const int32_t* pos, void* const* k_caches, void* const* v_caches,
+                                   const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer_desc(desc);
+    if (rc != MASSV_OK) return rc;
+    if (n_layers < 1 || !weights || !x || !pos || !k_caches || !v_caches || !kv_len) return MASSV_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        if ((rc = check_layer_weights(desc, weights + l)) != MASSV_OK) return rc;
+        if (!k_caches[l] || !v_caches[l]) return MASSV_EINVAL;
+    }
+    const LayerLayout lay = layer_layout(*desc);
+    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+    const bool bf = desc->attn.dtype == MASSV_BF16;
+    for (int l = 0; l < n_layers; ++l) {
+        // bf16: the norm that opens layer l+1 is computed by the kernel that closes layer l
+        const void* next_ln = (bf && l + 1 < n_layers) ? weights[l + 1].ln1 : nullptr;
+        rc = run_layer(desc, weights + l, x, pos, k_caches[l], v_caches[l], kv_len, workspace, lay,
+                       bf && l > 0, next_ln, (hipStream_t)stream);
+        if (rc != MASSV_OK) return rc;
+    }
+    return MASSV_OK;
 }
 
 static int check_lm_head(int32_t M, int32_t H, int32_t V, int32_t dtype) {

@@ -109,6 +109,47 @@ def test_lm_head_full_vocab(shape, M):
     assert_close(got.cpu().numpy(), ref, TOL_BF16, "logits")
 
 
+def run_stack(s, n_layers, B, Q, kv_len, n_img, seed, w_std=0.02):
+    """n_layers layers through ONE massv_verify_layers call against the checker's layer-by-layer chain."""
+    ws_h = [synth.layer_weights(s, seed, layer=l, std=w_std) for l in range(n_layers)]
+    kvs = [synth.kv_cache(s, B, Q, kv_len, n_img, seed, layer=l, hot_keys=1) for l in range(n_layers)]
+    x = synth.hidden_states(s, B, Q, seed)
+    pos = synth.positions(kvs[0].kv_len, kvs[0].n_img, Q, compress_image=True)
+    y_ref = x
+    k_refs, v_refs = [], []
+    for l in range(n_layers):
+        y_ref, k_ref, v_ref = O.verify_layer(s, ws_h[l], y_ref, pos, kvs[l].k, kvs[l].v, kvs[l].kv_len)
+        k_refs.append(k_ref); v_refs.append(v_ref)
+    lm = round_up(kvs[0].l_max, 32)
+    kds = [to_dev(pad_rows(kv.k, lm), s.dtype) for kv in kvs]
+    vds = [binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype)) for kv in kvs]
+    wds = [binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()}) for w in ws_h]
+    stack = binding.LayerStack(wds, kds, vds)
+    xd = to_dev(x, s.dtype)
+    binding.verify_layers(cfg_of(s), stack, xd, i32(pos), i32(kvs[0].kv_len), lm)
+    torch.cuda.synchronize()
+    tol = TOL_BF16 if s.dtype == "bf16" else TOL_F32 * n_layers
+    assert_close(xd.float().cpu().numpy(), y_ref, tol, "stack output")
+    for l in range(n_layers):
+        kg = kds[l].float().cpu().numpy()
+        vg = v_blocked_to_rows(vds[l]).float().cpu().numpy()
+        for b in range(B):
+            L = int(kvs[l].kv_len[b])
+            assert_close(kg[b, :, L:L + Q], k_refs[l][b, :, L:L + Q], tol, f"layer {l} appended keys")
+            assert_close(vg[b, :, L:L + Q], v_refs[l][b, :, L:L + Q], tol, f"layer {l} appended values")
+
+
+def test_layer_stack_tiny():
+    run_stack(synth.TINY, 3, 2, 6, [256, 100], [64, 30], seed=12, w_std=0.05)
+    run_stack(synth.TINY_BF16, 3, 2, 6, [256, 100], [64, 30], seed=13, w_std=0.05)
+
+
+def test_layer_stack_qwen7b_two_layers():
+    """Two Qwen2.5-VL-7B-shaped layers, B=8 (M=48), in one call: the fused norm between layers."""
+    rng = np.random.default_rng(14)
+    run_stack(synth.QWEN7B, 2, 8, 6, rng.integers(100, 400, 8), rng.integers(20, 100, 8), seed=14)
+
+
 def test_layer_repeatable_bits():
     s = synth.QWEN7B
     w = binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in synth.layer_weights(s, 9).items()})
