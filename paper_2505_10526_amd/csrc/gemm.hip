@@ -52,6 +52,7 @@ struct GemmDev {
     int M, K, ldy;           // ldy: elements per output row
     int act;
     int chunks_per_slab;
+    int unit_base, unit_rem; // balanced split of the tile units over gridDim.x: the first unit_rem workgroups own unit_base+1
     size_t slab_stride;      // elements between the partial sums of consecutive K slabs
 };
 
@@ -93,19 +94,26 @@ void gemm_stream_kernel(GemmDev g) {
     const bf16_t* wrow[NT];
     bool nvalid[NT];
     int ocol[NT];
+    // a unit is one tile (a gate/up tile pair for the gated epilogue); units are dealt to the workgroups
+    // as evenly as possible, so a workgroup may own fewer than its NT tile slots
+    constexpr int UT = gated ? 2 : 1;
+    const int bx = blockIdx.x;
+    const int unit0 = bx * g.unit_base + (bx < g.unit_rem ? bx : g.unit_rem);
+    const int n_units = g.unit_base + (bx < g.unit_rem ? 1 : 0);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int t = blockIdx.x * NT + nt;
+        const int t = unit0 * UT + nt;
+        const bool owned = nt < n_units * UT;
         int seg, local;
         if (gated) {                                  // tiles alternate gate, up of one 16-feature group
             seg = t & 1; local = t >> 1;
-            nvalid[nt] = local < g.tiles[0];
+            nvalid[nt] = owned && local < g.tiles[0];
             ocol[nt] = local * 16;
         } else {
             if (t < g.tiles[0]) { seg = 0; local = t; }
             else if (t < g.tiles[0] + g.tiles[1]) { seg = 1; local = t - g.tiles[0]; }
             else { seg = 2; local = t - g.tiles[0] - g.tiles[1]; }
-            nvalid[nt] = t < g.tiles[0] + g.tiles[1] + g.tiles[2];
+            nvalid[nt] = owned && t < g.tiles[0] + g.tiles[1] + g.tiles[2];
             ocol[nt] = t * 16;
         }
         if (!nvalid[nt]) { seg = 0; local = 0; }
@@ -274,7 +282,12 @@ GemmPlan gemm_plan(const GemmArgs& g) {
     for (int i = 0; i < 3; ++i) {
         int nt = cand[i];
         if (mt == 4 && nt > 4) continue;                       // register budget of four row tiles
-        const int groups = (T + nt - 1) / nt;
+        const int ut = (g.epilogue == EPI_GATED) ? 2 : 1;      // tiles per unit
+        int groups = (T + nt - 1) / nt;
+        if (groups < kCUs && g.epilogue != EPI_PARTIAL) {       // one round: spread the units over as many CUs as there are
+            const int units = T / ut;
+            groups = units < kCUs ? units : kCUs;
+        }
         int slabs = 1, cps = n_chunks;
         double eff;
         if (groups >= kCUs || g.epilogue != EPI_PARTIAL) {
@@ -361,6 +374,13 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
     d.ldy = (g.epilogue == EPI_GATED) ? g.n[0] : N;
     d.act = g.act;
     d.chunks_per_slab = p.chunks_per_slab;
+    {
+        const int ut = (g.epilogue == EPI_GATED) ? 2 : 1;
+        const int units = ((g.epilogue == EPI_GATED) ? 2 * d.tiles[0] : N / 16) / ut;
+        d.unit_base = units / p.groups;
+        d.unit_rem = units % p.groups;
+        if ((d.unit_base + (d.unit_rem ? 1 : 0)) * ut > p.nt) return MASSV_EUNSUPPORTED;     // cannot happen with gemm_plan's groups
+    }
     d.slab_stride = (size_t)((g.M + 15) / 16 * 16) * N;
     int rc2 = MASSV_EUNSUPPORTED;
     switch (g.epilogue) {
