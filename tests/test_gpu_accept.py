@@ -88,6 +88,14 @@ def test_long_context_stress_shape():
     check(a, 0.7)
 
 
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_extreme_sizes(temperature):
+    """Smallest and largest speculation lengths, vocabularies smaller than a wave / a chunk."""
+    for B, gamma, V, seed in ((1, 1, 3, 20), (2, 15, 700, 21), (5, 2, 63, 22), (1, 15, 1025, 23)):
+        a = synth.accept_inputs(B, gamma, V, temperature, seed=seed, noise_std=0.5, peak=3.0)
+        check(a, temperature, min_exact=0.0)
+
+
 def test_ties_resolve_to_lowest_index():
     a = synth.accept_inputs(4, 3, 20000, 0.0, seed=2)
     t = synth.bf16_representable(a.target_logits)         # bf16-valued logits tie often

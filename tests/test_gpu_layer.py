@@ -80,6 +80,20 @@ def test_gemma12b_layer_b4_full_length():
     run_layer(synth.GEMMA12B, 4, 6, [4096] * 4, [256] * 4, seed=11)
 
 
+def test_qwen7b_layer_max_rows():
+    """The largest row count the bf16 kernels take: B=8, gamma=7 -> M = 64 rows (four 16-row tiles),
+    56 stacked query rows per KV head."""
+    rng = np.random.default_rng(15)
+    run_layer(synth.QWEN7B, 8, 8, rng.integers(40, 300, 8), rng.integers(8, 40, 8), seed=15)
+
+
+def test_single_row_and_single_sequence():
+    """Degenerate sizes: one query position (plain decoding), one sequence."""
+    run_layer(synth.TINY_BF16, 1, 1, [33], [5], seed=16, w_std=0.05)
+    run_layer(synth.TINY, 1, 1, [0], [0], seed=17, w_std=0.05)
+    run_layer(synth.QWEN7B, 1, 1, [70], [20], seed=18)
+
+
 def test_gemma12b_layer_b4():
     """Config 4's layer: hidden 3840, 16/8 heads, d=256, GeGLU 15360, no bias, B=4 (M=24)."""
     run_layer(synth.GEMMA12B, 4, 6, [300, 256, 50, 411], [256, 200, 10, 256], seed=6)
