@@ -380,24 +380,46 @@ void attention_mfma_kernel(AttnParams p) {
     }
 }
 
-// Merge of the key-range splits: one workgroup of D/4 threads per output row.
+// Merge of the key-range splits.  D/4 threads own one output row (4 features each); a 256-thread
+// workgroup handles 1024/D rows.  Splits are taken 8 at a time with all their loads in flight, in split
+// order (deterministic).
 template <int D>
-__global__ void attention_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                         bf16_t* __restrict__ out, int Q, int n_q, int n_kv, int n_split, int rows_pad, int out_mt) {
-    const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z, t = threadIdx.x;
+__global__ __launch_bounds__(256)
+void attention_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                              bf16_t* __restrict__ out, int Q, int n_q, int n_kv, int n_split, int rows_pad,
+                              int out_mt, int total_rows) {
+    constexpr int TPR = D / 4;                       // threads per row
+    const int row_id = blockIdx.x * (256 / TPR) + threadIdx.x / TPR, t = threadIdx.x % TPR;
+    if (row_id >= total_rows) return;
+    const int h = row_id % n_q, i = (row_id / n_q) % Q, b = row_id / (n_q * Q);
     const int G = n_q / n_kv, g = h / G, r = i * G + (h % G);
     const size_t slot0 = ((size_t)b * n_kv + g) * n_split * rows_pad;
-    float m = -INFINITY;
-    for (int s = 0; s < n_split; ++s) m = fmaxf(m, part_ml[(slot0 + (size_t)s * rows_pad + r) * 2]);
+    float m = -INFINITY, l = 0.f;
     floatx4 o = {0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int s = 0; s < n_split; ++s) {
-        const size_t row = slot0 + (size_t)s * rows_pad + r;
-        const float ms = part_ml[row * 2];
-        if (ms == -INFINITY) continue;                      // split saw no visible key for this row
-        const float w = exp2f(ms - m);
-        l += part_ml[row * 2 + 1] * w;
-        o += *reinterpret_cast<const floatx4*>(part_o + row * D + t * 4) * w;
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float ms[8], ls[8];
+        floatx4 os[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = s0 + u < n_split;
+            const size_t row = slot0 + (size_t)(ok ? s0 + u : 0) * rows_pad + r;
+            ms[u] = ok ? part_ml[row * 2] : -INFINITY;
+            ls[u] = ok ? part_ml[row * 2 + 1] : 0.f;
+            os[u] = *reinterpret_cast<const floatx4*>(part_o + row * D + t * 4);
+        }
+        float mb = m;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mb = fmaxf(mb, ms[u]);
+        if (mb == -INFINITY) continue;               // no split so far saw a visible key for this row
+        const float keep = exp2f(m - mb);             // m = -inf gives 0
+        l *= keep; o *= keep; m = mb;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (ms[u] == -INFINITY) continue;         // that split's sums may be uninitialised
+            const float w = exp2f(ms[u] - m);
+            l += ls[u] * w;
+            o += os[u] * w;
+        }
     }
     const float inv = 1.0f / l;
     bf16x4 ob = {(bf16_t)(o[0] * inv), (bf16_t)(o[1] * inv), (bf16_t)(o[2] * inv), (bf16_t)(o[3] * inv)};
@@ -459,9 +481,12 @@ static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
     launch_traced(MASSV_K_ATTENTION, attention_mfma_kernel<D, MT>, dim3(p.n_split, a.n_kv_heads, a.batch),
                   dim3(kAttnThreads), lds, st, p);
     if (p.n_split > 1)
-        launch_traced(MASSV_K_ATTN_COMBINE, attention_combine_kernel<D>, dim3(a.n_q_heads, a.n_query, a.batch),
-                      dim3(D / 4), 0, st, (const float*)p.part_o, (const float*)p.part_ml, p.out, a.n_query,
-                      a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16, p.out_mt);
+    {
+        const int total_rows = a.batch * a.n_query * a.n_q_heads, rows_per_wg = 256 / (D / 4);
+        launch_traced(MASSV_K_ATTN_COMBINE, attention_combine_kernel<D>, dim3((total_rows + rows_per_wg - 1) / rows_per_wg),
+                      dim3(256), 0, st, (const float*)p.part_o, (const float*)p.part_ml, p.out, a.n_query,
+                      a.n_q_heads, a.n_kv_heads, p.n_split, MT * 16, p.out_mt, total_rows);
+    }
     return launch_status();
 }
 
