@@ -217,12 +217,16 @@ int massv_lm_head_logits(const void* x, const void* final_norm, const void* w_lm
 /*   T = 0: x_i accepted iff x_i == argmax target_logits[b,i] (lowest index on */
 /*          ties); final token = argmax target_logits[b,n].                    */
 /* After the call the caller keeps kv_len[b] + n_accepted[b] + 1 cache rows.   */
+/* gamma = 0 is the plain sampling step of the drafting loop (Section 2.1: the */
+/* drafter draws x_i from q_i): there is nothing to verify, n_accepted = 0 and */
+/* out_tokens[b,0] is drawn from softmax(target_logits[b,0]/T) with            */
+/* uniforms[b,0] (argmax at T = 0); draft_logits and draft_tokens are unused.  */
 /* ------------------------------------------------------------------------- */
 size_t massv_spec_accept_workspace(int32_t B, int32_t gamma, int32_t V);
 
 /* target_logits [B][gamma+1][V] float32 in
- * draft_logits  [B][gamma][V]   float32 in; may be NULL iff temperature == 0
- * draft_tokens  [B][gamma]      int32   in; values outside [0,V) are rejected
+ * draft_logits  [B][gamma][V]   float32 in; may be NULL iff temperature == 0 or gamma == 0
+ * draft_tokens  [B][gamma]      int32   in; values outside [0,V) are rejected; may be NULL iff gamma == 0
  * uniforms      [B][gamma+1]    float32 in, in [0,1); may be NULL iff temperature == 0
  * n_accepted    [B]             int32   out, 0..gamma
  * out_tokens    [B][gamma+1]    int32   out: the accepted drafts, the final
@@ -233,6 +237,31 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
                       float temperature, int32_t B, int32_t gamma, int32_t V,
                       int32_t* n_accepted, int32_t* out_tokens,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* spec_tvd: total variation distance of Section 6 between the target and the */
+/* draft distribution of every row, TVD = 1/2 sum_x |p(x) - q(x)| with         */
+/* p = softmax(target_logits[r]/T), q = softmax(draft_logits[r]/T); 1 - TVD is */
+/* the expected acceptance probability of a token drawn from q at that row.   */
+/* ------------------------------------------------------------------------- */
+size_t massv_spec_tvd_workspace(int32_t rows, int32_t V);
+
+/* target_logits, draft_logits [rows][V] float32 in (device); temperature > 0, finite;
+ * tvd [rows] float64 out (device), absolute error below 1e-6 (exponentials in float, sums in double).
+ * rows <= 32767.  Logits as for massv_spec_accept. */
+int massv_spec_tvd(const float* target_logits, const float* draft_logits, float temperature,
+                   int32_t rows, int32_t V, double* tvd,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* embed_tokens: x[m, :] = table[tokens[m], :], the input of the first layer   */
+/* for the tokens a drafting or verify step feeds back (Section 2.1's loop).   */
+/* table [V][H] and x [M][H] of `dtype`, row-major, device; tokens [M] int32   */
+/* device.  A token outside [0,V) gives a row of zeros.  H * elem size must be */
+/* a multiple of 4 bytes.                                                      */
+/* ------------------------------------------------------------------------- */
+int massv_embed_tokens(const void* table, const int32_t* tokens, void* x,
+                       int32_t M, int32_t H, int32_t V, int32_t dtype, void* stream);
 
 /* ------------------------------------------------------------------------- */
 /* Timing hook (diagnostic; for callers that want one kernel's duration        */

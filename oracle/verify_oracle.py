@@ -226,6 +226,24 @@ def tvd(p, q):
     return 0.5 * float(np.sum(np.abs(np.asarray(p, dtype=np.float64) - np.asarray(q, dtype=np.float64))))
 
 
+def tvd_rows(target_logits, draft_logits, temperature):
+    """Eq. (TVD) for every row: the distance between softmax(target/T) and softmax(draft/T) (Section 6)."""
+    t = np.asarray(target_logits, dtype=np.float64)
+    d = np.asarray(draft_logits, dtype=np.float64)
+    return np.array([tvd(softmax(t[r] / temperature), softmax(d[r] / temperature)) for r in range(t.shape[0])])
+
+
+def embed_tokens(table, tokens):
+    """Input rows of the first layer for fed-back tokens (Section 2.1's loop): row m is table[tokens[m]];
+    a token outside the vocabulary gives a zero row."""
+    table = np.asarray(table)
+    out = np.zeros((len(tokens), table.shape[1]), dtype=table.dtype)
+    for m, tok in enumerate(np.asarray(tokens).tolist()):
+        if 0 <= tok < table.shape[0]:
+            out[m] = table[tok]
+    return out
+
+
 def residual(p, q):
     """max(p - q, 0) without normalisation; p itself when that is identically 0 (R7)."""
     r = np.maximum(np.asarray(p, dtype=np.float64) - np.asarray(q, dtype=np.float64), 0.0)
@@ -237,7 +255,9 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
     """Sequential accept / reject / resample for every sequence of the batch.
 
     target_logits [B, gamma+1, V], draft_logits [B, gamma, V] (ignored at T=0),
-    draft_tokens [B, gamma], uniforms [B, gamma+1] (ignored at T=0).
+    draft_tokens [B, gamma], uniforms [B, gamma+1] (ignored at T=0).  gamma = 0
+    is the drafting loop's own sampling step: one token drawn from the single
+    row's distribution, nothing to verify.
     Returns n_accepted [B] int32, out_tokens [B, gamma+1] int32 (accepted
     drafts, the final token, then -1), and margin [B, 2]: the smallest relative
     distance from flipping of (0) any evaluated accept comparison with p < q,
@@ -255,7 +275,7 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
     masses = []
     greedy = (temperature == 0)
     if not greedy:
-        dl = np.asarray(draft_logits, dtype=np.float64)
+        dl = np.asarray(draft_logits, dtype=np.float64) if gamma > 0 else None
         u = np.asarray(uniforms, dtype=np.float64).reshape(B, Q)
     for b in range(B):
         n = 0

@@ -28,6 +28,7 @@ EXPORTS = [
     "massv_verify_layer_workspace", "massv_verify_layer", "massv_verify_layers",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
     "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
+    "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS = range(9)
 
@@ -98,6 +99,12 @@ def load():
     lib.massv_weight_pack.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.massv_trace_kernel.restype = C.c_int
     lib.massv_trace_kernel.argtypes = [C.c_int, vp, vp]
+    lib.massv_spec_tvd_workspace.restype = sz
+    lib.massv_spec_tvd_workspace.argtypes = [i32, i32]
+    lib.massv_spec_tvd.restype = C.c_int
+    lib.massv_spec_tvd.argtypes = [vp, vp, f32, i32, i32, vp, vp, sz, vp]
+    lib.massv_embed_tokens.restype = C.c_int
+    lib.massv_embed_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -321,10 +328,12 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
                 n_accepted=None, out_tokens=None, ws=None):
     """target_logits [B,gamma+1,V] f32, draft_logits [B,gamma,V] f32 (None at T=0),
     draft_tokens [B,gamma] i32, uniforms [B,gamma+1] f32 (None at T=0).
+    gamma = 0 (draft_logits, draft_tokens None) draws one token per sequence.
     Returns (n_accepted [B] i32, out_tokens [B,gamma+1] i32)."""
     lib = load()
     _need(target_logits, "target_logits", torch.float32)
-    _need(draft_tokens, "draft_tokens", torch.int32)
+    if draft_tokens is not None:
+        _need(draft_tokens, "draft_tokens", torch.int32)
     if draft_logits is not None:
         _need(draft_logits, "draft_logits", torch.float32)
     if uniforms is not None:
@@ -343,6 +352,42 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
                                  float(temperature), B, gamma, V, _ptr(n_accepted), _ptr(out_tokens),
                                  _ptr(ws), ws.numel(), _stream()), "massv_spec_accept")
     return n_accepted, out_tokens
+
+
+def spec_tvd(target_logits, draft_logits, temperature, tvd=None, ws=None):
+    """target_logits, draft_logits [rows,V] f32 -> tvd [rows] f64."""
+    lib = load()
+    _need(target_logits, "target_logits", torch.float32)
+    _need(draft_logits, "draft_logits", torch.float32)
+    if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape:
+        raise ValueError("spec_tvd: both logit arrays must be [rows, V]")
+    rows, V = target_logits.shape
+    dev = target_logits.device
+    if tvd is None:
+        tvd = torch.empty((rows,), dtype=torch.float64, device=dev)
+    else:
+        _need(tvd, "tvd", torch.float64)
+    if ws is None:
+        ws = workspace(lib.massv_spec_tvd_workspace(rows, V), dev)
+    _check(lib.massv_spec_tvd(_ptr(target_logits), _ptr(draft_logits), float(temperature), rows, V,
+                              _ptr(tvd), _ptr(ws), ws.numel(), _stream()), "massv_spec_tvd")
+    return tvd
+
+
+def embed_tokens(table, tokens, x=None):
+    """table [V,H], tokens [M] i32 -> x [M,H] of the table's dtype."""
+    lib = load()
+    _need(table, "table", table.dtype)
+    _need(tokens, "tokens", torch.int32)
+    V, H = table.shape
+    M = tokens.numel()
+    if x is None:
+        x = torch.empty((M, H), dtype=table.dtype, device=table.device)
+    else:
+        _need(x, "x", table.dtype)
+    _check(lib.massv_embed_tokens(_ptr(table), _ptr(tokens), _ptr(x), M, H, V, dtype_code(table), _stream()),
+           "massv_embed_tokens")
+    return x
 
 
 # ---------------------------------------------------------------------------

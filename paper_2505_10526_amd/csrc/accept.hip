@@ -180,9 +180,13 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
     }
 }
 
-// Unnormalised-to-normalised probability of one logit in double.
+// Unnormalised-to-normalised probability of one logit in double.  The product is rounded on its own
+// (never fused into a following subtraction), so that equal logits under equal statistics give
+// exactly equal probabilities and p - q is exactly zero there.
 __device__ inline double prob_of(float logit, double m, double inv_s, TempScale ts) {
-    return (double)exp2f(scaled(logit - (float)m, ts)) * inv_s;
+#pragma clang fp contract(off)
+    const double p = (double)exp2f(scaled(logit - (float)m, ts)) * inv_s;
+    return p;
 }
 
 __global__ __launch_bounds__(kAccThreads)
@@ -283,7 +287,7 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
     // ---- which token inside the chunk: every thread owns 4 consecutive tokens ----
     const int base = chunk * kAccChunk + tid * kPickPerThread;
     const float* trow = target + ((size_t)b * Q + s.n) * V;
-    const float* drow = draft + ((size_t)b * gamma + (s.bonus ? 0 : s.n)) * V;
+    const float* drow = s.bonus ? trow : draft + ((size_t)b * gamma + s.n) * V;      // never read when bonus
     const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
     double r[kPickPerThread];
     double tot = 0.0;
@@ -325,12 +329,88 @@ static AcceptLayout accept_layout(int B, int gamma, int V) {
     return l;
 }
 
+
+// ---- total variation distance between the two distributions of a row (paper Section 6) ----
+struct RowStat { double m, s; };
+
+// One wave per row: the chunk partials of pass 1 merged into the row's maximum and sum of exponentials.
+__global__ __launch_bounds__(kAccThreads)
+void tvd_rowstat_kernel(const RowPartial* __restrict__ part, int n_rows, int C, float scale2,
+                        RowStat* __restrict__ stat) {
+    const int lane = threadIdx.x % kWave;
+    const int r = blockIdx.x * (kAccThreads / kWave) + threadIdx.x / kWave;
+    if (r >= n_rows) return;
+    const RowPartial* p = part + (size_t)r * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += kWave) m = fmaxf(m, p[c].m);
+    m = wave_max(m);
+    double s = 0.0;
+    for (int c = lane; c < C; c += kWave)
+        if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
+    s = wave_sum(s);
+    if (lane == 0) { RowStat o; o.m = (double)m; o.s = s; stat[r] = o; }
+}
+
+// One wave per (row, chunk): sum of |p - q| over the chunk's 1024 tokens, in double.
+__global__ __launch_bounds__(kAccThreads)
+void tvd_chunk_kernel(const float* __restrict__ target, const float* __restrict__ draft,
+                      int rows, int V, int C, TempScale ts, int vec,
+                      const RowStat* __restrict__ stat, double* __restrict__ chunk_abs) {
+    const int lane = threadIdx.x % kWave;
+    const int c = blockIdx.x * (kAccThreads / kWave) + threadIdx.x / kWave, r = blockIdx.y;
+    if (c >= C) return;
+    const RowStat st = stat[r], sd = stat[rows + r];
+    const int base = c * kAccChunk;
+    float xt[kAccPerLane], xd[kAccPerLane];
+    load_chunk(target + (size_t)r * V, V, base, lane, vec, xt);
+    load_chunk(draft + (size_t)r * V, V, base, lane, vec, xd);
+    const double inv_st = 1.0 / st.s, inv_sd = 1.0 / sd.s;
+    double a = 0.0;
+#pragma unroll
+    for (int k = 0; k < kAccPerLane; ++k)
+        a += fabs(prob_of(xt[k], st.m, inv_st, ts) - prob_of(xd[k], sd.m, inv_sd, ts));
+    a = wave_sum(a);
+    if (lane == 0) chunk_abs[(size_t)r * C + c] = a;
+}
+
+// One wave per row: chunk sums added in a fixed order, halved.
+__global__ __launch_bounds__(kAccThreads)
+void tvd_final_kernel(const double* __restrict__ chunk_abs, int rows, int C, double* __restrict__ tvd) {
+    const int lane = threadIdx.x % kWave;
+    const int r = blockIdx.x * (kAccThreads / kWave) + threadIdx.x / kWave;
+    if (r >= rows) return;
+    double a = 0.0;
+    for (int c = lane; c < C; c += kWave) a += chunk_abs[(size_t)r * C + c];
+    a = wave_sum(a);
+    if (lane == 0) tvd[r] = 0.5 * a;
+}
+
+struct TvdLayout { size_t part, stat, chunk, total; };
+static TvdLayout tvd_layout(int rows, int V) {
+    TvdLayout l;
+    const size_t C = n_chunks(V);
+    l.part = 0;
+    l.stat = align_up(l.part + 2 * (size_t)rows * C * sizeof(RowPartial), 256);
+    l.chunk = align_up(l.stat + 2 * (size_t)rows * sizeof(RowStat), 256);
+    l.total = align_up(l.chunk + (size_t)rows * C * sizeof(double), 256);
+    return l;
+}
+
+static TempScale temp_scale(float temperature) {
+    TempScale ts;
+    ts.inv = 1.0 / (double)temperature;
+    const double k2 = ts.inv * 1.4426950408889634074;      // log2(e) / T
+    ts.hi = (float)k2;
+    ts.lo = (float)(k2 - (double)ts.hi);
+    return ts;
+}
+
 }  // namespace massv
 
 using namespace massv;
 
 extern "C" size_t massv_spec_accept_workspace(int32_t B, int32_t gamma, int32_t V) {
-    if (B < 1 || gamma < 1 || gamma > kMaxGamma || V < 1) return 0;
+    if (B < 1 || gamma < 0 || gamma > kMaxGamma || V < 1) return 0;
     return accept_layout(B, gamma, V).total;
 }
 
@@ -339,11 +419,12 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
                                  float temperature, int32_t B, int32_t gamma, int32_t V,
                                  int32_t* n_accepted, int32_t* out_tokens,
                                  void* workspace, size_t workspace_bytes, void* stream) {
-    if (B < 1 || gamma < 1 || V < 1) return MASSV_EINVAL;
+    if (B < 1 || gamma < 0 || V < 1) return MASSV_EINVAL;
     if (!(temperature >= 0.f) || isinf(temperature)) return MASSV_EINVAL;     // also catches NaN
-    if (!target_logits || !draft_tokens || !n_accepted || !out_tokens) return MASSV_EINVAL;
+    if (!target_logits || !n_accepted || !out_tokens) return MASSV_EINVAL;
+    if (gamma > 0 && !draft_tokens) return MASSV_EINVAL;
     const int greedy = (temperature == 0.f);
-    if (!greedy && (!draft_logits || !uniforms)) return MASSV_EINVAL;
+    if (!greedy && (!uniforms || (gamma > 0 && !draft_logits))) return MASSV_EINVAL;
     if (gamma > kMaxGamma) return MASSV_EUNSUPPORTED;
     if ((size_t)B * (gamma + 1) > 65535 || (size_t)B > 65535) return MASSV_EUNSUPPORTED;   // grid.y limit
     const AcceptLayout lay = accept_layout(B, gamma, V);
@@ -357,12 +438,7 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     ChunkMass* mass = (ChunkMass*)(ws + lay.mass);
     const int C = n_chunks(V), Q = gamma + 1;
     TempScale ts; ts.hi = 1.f; ts.lo = 0.f; ts.inv = 1.0;
-    if (!greedy) {
-        ts.inv = 1.0 / (double)temperature;
-        const double k2 = ts.inv * 1.4426950408889634074;      // log2(e) / T
-        ts.hi = (float)k2;
-        ts.lo = (float)(k2 - (double)ts.hi);
-    }
+    if (!greedy) ts = temp_scale(temperature);
     const int vec = (V % 4 == 0) && ((uintptr_t)target_logits % 16 == 0) &&
                     (greedy || (uintptr_t)draft_logits % 16 == 0);
     const int rows = greedy ? B * Q : B * (Q + gamma);
@@ -378,5 +454,41 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
         hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,
                            target_logits, draft_logits, uniforms, gamma, V, C, ts, sel, mass, out_tokens);
     }
+    return launch_status();
+}
+
+extern "C" size_t massv_spec_tvd_workspace(int32_t rows, int32_t V) {
+    if (rows < 1 || rows > 32767 || V < 1) return 0;
+    return tvd_layout(rows, V).total;
+}
+
+extern "C" int massv_spec_tvd(const float* target_logits, const float* draft_logits, float temperature,
+                              int32_t rows, int32_t V, double* tvd,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (rows < 1 || V < 1) return MASSV_EINVAL;
+    if (!(temperature > 0.f) || isinf(temperature)) return MASSV_EINVAL;      // also catches NaN
+    if (!target_logits || !draft_logits || !tvd) return MASSV_EINVAL;
+    if (rows > 32767) return MASSV_EUNSUPPORTED;                              // grid.y limit of pass 1
+    const TvdLayout lay = tvd_layout(rows, V);
+    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    RowPartial* part = (RowPartial*)(ws + lay.part);
+    RowStat* stat = (RowStat*)(ws + lay.stat);
+    double* chunk_abs = (double*)(ws + lay.chunk);
+    const int C = n_chunks(V);
+    const TempScale ts = temp_scale(temperature);
+    const int vec = (V % 4 == 0) && ((uintptr_t)target_logits % 16 == 0) && ((uintptr_t)draft_logits % 16 == 0);
+    const int wpb = kAccThreads / kWave;
+
+    hipLaunchKernelGGL(accept_stats_kernel, dim3((C + wpb - 1) / wpb, 2 * rows), dim3(kAccThreads), 0, st,
+                       target_logits, draft_logits, rows, V, C, ts, 0, vec, part);
+    hipLaunchKernelGGL(tvd_rowstat_kernel, dim3((2 * rows + wpb - 1) / wpb), dim3(kAccThreads), 0, st,
+                       (const RowPartial*)part, 2 * rows, C, ts.hi, stat);
+    hipLaunchKernelGGL(tvd_chunk_kernel, dim3((C + wpb - 1) / wpb, rows), dim3(kAccThreads), 0, st,
+                       target_logits, draft_logits, rows, V, C, ts, vec, (const RowStat*)stat, chunk_abs);
+    hipLaunchKernelGGL(tvd_final_kernel, dim3((rows + wpb - 1) / wpb), dim3(kAccThreads), 0, st,
+                       (const double*)chunk_abs, rows, C, tvd);
     return launch_status();
 }

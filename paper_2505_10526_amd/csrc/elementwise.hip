@@ -317,9 +317,31 @@ __global__ void weight_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __res
     *reinterpret_cast<bf16x8*>(dst + o * 8) = *reinterpret_cast<const bf16x8*>(src + n * K + k);
 }
 
+// Embedding rows gathered as 4-byte words: one workgroup per output row.
+__global__ __launch_bounds__(256)
+void embed_tokens_kernel(const uint32_t* __restrict__ table, const int* __restrict__ tokens,
+                         uint32_t* __restrict__ x, int words, int V) {
+    const int m = blockIdx.x, tok = tokens[m];
+    const bool ok = tok >= 0 && tok < V;
+    const uint32_t* src = table + (size_t)(ok ? tok : 0) * words;
+    uint32_t* dst = x + (size_t)m * words;
+    for (int i = threadIdx.x; i < words; i += blockDim.x) dst[i] = ok ? src[i] : 0u;
+}
+
 }  // namespace massv
 
 using namespace massv;
+
+extern "C" int massv_embed_tokens(const void* table, const int32_t* tokens, void* x,
+                                  int32_t M, int32_t H, int32_t V, int32_t dtype, void* stream) {
+    if (!table || !tokens || !x || M < 1 || H < 1 || V < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    const size_t row_bytes = (size_t)H * (dtype == MASSV_F32 ? 4 : 2);
+    if (row_bytes % 4) return MASSV_EUNSUPPORTED;
+    hipLaunchKernelGGL(embed_tokens_kernel, dim3(M), dim3(256), 0, (hipStream_t)stream,
+                       (const uint32_t*)table, tokens, (uint32_t*)x, (int)(row_bytes / 4), V);
+    return launch_status();
+}
 
 extern "C" int massv_weight_pack(const void* src, void* dst, int32_t N, int32_t K, int32_t dtype, void* stream) {
     if (!src || !dst || N < 1 || K < 1) return MASSV_EINVAL;

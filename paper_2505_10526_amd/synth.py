@@ -59,6 +59,10 @@ TINY = LayerShape(256, 4, 2, 64, 688, 4096, ACT_SILU, True, dtype="f32")
 TINY_BF16 = LayerShape(256, 4, 2, 64, 704, 4096, ACT_SILU, True, dtype="bf16")
 QWEN7B = LayerShape(3584, 28, 4, 128, 18944, 152064, ACT_SILU, True)
 GEMMA12B = LayerShape(3840, 16, 8, 256, 15360, 262144, ACT_GELU_TANH, False)
+# Drafter-sized shapes (Section 5, "Models": a small language model of the target's family drafts for it).
+# The drafter's vocabulary is taken equal to the target's so that both logit rows index the same tokens.
+TINY_DRAFT_BF16 = LayerShape(128, 2, 1, 64, 352, 4096, ACT_SILU, True, dtype="bf16")
+QWEN1P5B = LayerShape(1536, 12, 2, 128, 8960, 152064, ACT_SILU, True)
 
 
 def _rng(seed, *stream):
@@ -114,6 +118,11 @@ def lm_head_weights(shape: LayerShape, seed: int, std: float = 0.02):
         "final_norm": normal((shape.hidden,), 0.1, seed, 1000, 0, dtype=dt, mean=1.0),
         "w_lm": normal((shape.vocab, shape.hidden), std, seed, 1000, 1, dtype=dt),
     }
+
+
+def embedding_table(shape: LayerShape, seed: int, std: float = 1.0):
+    """Input embedding rows, one per vocabulary entry: N(0, std)."""
+    return normal((shape.vocab, shape.hidden), std, seed, 1000, 2, dtype=shape.dtype)
 
 
 @dataclass

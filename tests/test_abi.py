@@ -62,10 +62,34 @@ def test_spec_accept_argument_checks(lib):
     assert f(*ok_args(T=-0.5)) == binding.EINVAL
     assert f(*ok_args(T=float("nan"))) == binding.EINVAL
     assert f(*ok_args(B=0)) == binding.EINVAL
-    assert f(*ok_args(g=0)) == binding.EINVAL
+    assert f(*ok_args(g=-1)) == binding.EINVAL
+    assert f(*ok_args(x=None)) == binding.EINVAL            # gamma > 0 needs draft tokens
+    assert f(*ok_args(g=0, d=None, x=None, u=None)) == binding.EINVAL     # sampling at T > 0 needs a uniform
+    assert lib.massv_spec_accept_workspace(2, 0, 1000) > 0
     assert f(*ok_args(g=99)) == binding.EUNSUPPORTED
     assert f(*ok_args(wsb=ws - 1)) == binding.EWORKSPACE
     assert f(*ok_args(ws=None)) == binding.EWORKSPACE
+
+
+def test_spec_tvd_and_embed_argument_checks(lib):
+    f = lib.massv_spec_tvd
+    ws = lib.massv_spec_tvd_workspace(6, 1000)
+    assert ws > 0 and lib.massv_spec_tvd_workspace(0, 1000) == 0
+    assert f(None, FAKE, 1.0, 6, 1000, FAKE, FAKE, ws, None) == binding.EINVAL
+    assert f(FAKE, None, 1.0, 6, 1000, FAKE, FAKE, ws, None) == binding.EINVAL
+    assert f(FAKE, FAKE, 1.0, 6, 1000, None, FAKE, ws, None) == binding.EINVAL
+    assert f(FAKE, FAKE, 0.0, 6, 1000, FAKE, FAKE, ws, None) == binding.EINVAL      # undefined at T = 0
+    assert f(FAKE, FAKE, float("inf"), 6, 1000, FAKE, FAKE, ws, None) == binding.EINVAL
+    assert f(FAKE, FAKE, 1.0, 0, 1000, FAKE, FAKE, ws, None) == binding.EINVAL
+    assert f(FAKE, FAKE, 1.0, 40000, 1000, FAKE, FAKE, 1 << 40, None) == binding.EUNSUPPORTED
+    assert f(FAKE, FAKE, 1.0, 6, 1000, FAKE, FAKE, ws - 1, None) == binding.EWORKSPACE
+    g = lib.massv_embed_tokens
+    assert g(None, FAKE, FAKE, 4, 64, 100, binding.BF16, None) == binding.EINVAL
+    assert g(FAKE, None, FAKE, 4, 64, 100, binding.BF16, None) == binding.EINVAL
+    assert g(FAKE, FAKE, None, 4, 64, 100, binding.BF16, None) == binding.EINVAL
+    assert g(FAKE, FAKE, FAKE, 0, 64, 100, binding.BF16, None) == binding.EINVAL
+    assert g(FAKE, FAKE, FAKE, 4, 64, 100, 7, None) == binding.EINVAL
+    assert g(FAKE, FAKE, FAKE, 4, 63, 100, binding.BF16, None) == binding.EUNSUPPORTED
 
 
 def test_attention_argument_checks(lib):

@@ -19,9 +19,10 @@ TOL = 1e-4          # relative decision margin above which results must be ident
 
 def run_gpu(a, temperature):
     dev = "cuda:0"
+    gamma = a.target_logits.shape[1] - 1
     t = torch.from_numpy(a.target_logits).to(dev)
-    d = torch.from_numpy(a.draft_logits).to(dev) if temperature > 0 else None
-    x = torch.from_numpy(a.draft_tokens).to(dev)
+    d = torch.from_numpy(a.draft_logits).to(dev) if temperature > 0 and gamma > 0 else None
+    x = torch.from_numpy(a.draft_tokens).to(dev) if gamma > 0 else None
     u = torch.from_numpy(a.uniforms).to(dev) if temperature > 0 else None
     n, out = binding.spec_accept(t, d, x, u, temperature)
     torch.cuda.synchronize()
@@ -140,3 +141,41 @@ def test_repeatable_bits():
     r1 = run_gpu(a, 1.0)
     r2 = run_gpu(a, 1.0)
     assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1])
+
+
+@pytest.mark.parametrize("temperature", [0.0, 1.0, 0.7])
+@pytest.mark.parametrize("B,V", [(8, 151936), (3, 1000), (1, 5)])
+def test_sampling_step_without_drafts(B, V, temperature):
+    """gamma = 0: one token per sequence drawn from the single row (the drafting loop's own draw)."""
+    a = synth.accept_inputs(B, 0, V, temperature, seed=31, target_std=2.0)
+    assert a.target_logits.shape == (B, 1, V)
+    n = check(a, temperature, min_exact=0.0)
+    assert np.all(n == 0)
+
+
+@pytest.mark.parametrize("temperature", [1.0, 0.7, 0.25])
+@pytest.mark.parametrize("rows,V", [(12, 152064), (5, 4096 + 5), (3, 700), (1, 3)])
+def test_tvd_rows(rows, V, temperature):
+    """Eq. (TVD) of Section 6 per row; sums are carried in double on both sides, the exponentials in
+    float on the GPU: absolute error far below 1e-5."""
+    a = synth.accept_inputs(rows, 1, V, 1.0, seed=41, target_std=2.0, noise_std=1.5)
+    t, d = a.target_logits[:, 0].copy(), a.draft_logits[:, 0].copy()
+    if V > 64:
+        t[0, 5:40] = -np.inf                                      # zero-probability tokens on one side
+    got = binding.spec_tvd(torch.from_numpy(t).cuda(), torch.from_numpy(d).cuda(), temperature).cpu().numpy()
+    want = O.tvd_rows(t, d, float(np.float32(temperature)))
+    assert got.shape == (rows,)
+    assert np.max(np.abs(got - want)) < 1e-5, (got, want)
+    assert np.any(want > 1e-3)                                    # the case is not trivially zero
+
+
+def test_tvd_identical_and_disjoint_rows():
+    V = 9000
+    a = synth.accept_inputs(4, 1, V, 1.0, seed=42)
+    t = a.target_logits[:, 0].copy()
+    d = t.copy()
+    t[2:, V // 2:] = -np.inf
+    d[2:, : V // 2] = -np.inf
+    got = binding.spec_tvd(torch.from_numpy(t).cuda(), torch.from_numpy(d).cuda(), 1.0).cpu().numpy()
+    assert np.all(got[:2] == 0.0)
+    assert np.all(np.abs(got[2:] - 1.0) < 1e-6)                  # float exponentials: sum p is 1 to ~1e-7

@@ -179,3 +179,12 @@ def test_layer_repeatable_bits():
         outs.append((x.clone(), kd.clone(), vd.clone()))
     for a, b in zip(*outs):
         assert torch.equal(torch.nan_to_num(a.float()), torch.nan_to_num(b.float()))
+
+
+@pytest.mark.parametrize("s", [synth.TINY, synth.TINY_BF16], ids=["f32", "bf16"])
+def test_embed_tokens_gathers_rows(s):
+    table = synth.embedding_table(s, 5)
+    tokens = np.array([0, s.vocab - 1, 17, 17, -3, s.vocab, 1234], dtype=np.int32)
+    ref = O.embed_tokens(table, tokens)
+    got = binding.embed_tokens(to_dev(table, s.dtype), i32(tokens))
+    assert np.array_equal(got.float().cpu().numpy(), ref)

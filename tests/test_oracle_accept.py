@@ -283,3 +283,53 @@ def test_synthetic_accept_inputs_exercise_every_accept_length():
     n, out, _ = O.spec_accept(a.target_logits, a.draft_logits, a.draft_tokens, a.uniforms, 1.0)
     assert set(np.unique(n)) == set(range(6))
     assert np.all((out >= 0).sum(1) == n + 1)
+
+
+def test_sampling_step_draws_from_the_single_row():
+    """gamma = 0 (the drafting loop's own draw, Section 2.1): with V = 4 and weights 1:2:3:4 the token
+    is the quartile-like bucket of the uniform, n_accepted is 0; greedy gives the lowest arg-max."""
+    logits = np.log(np.array([[[1.0, 2.0, 3.0, 4.0]]]))            # p = .1 .2 .3 .4
+    for u, want in ((0.0, 0), (0.05, 0), (0.15, 1), (0.29, 1), (0.31, 2), (0.59, 2), (0.61, 3), (0.999, 3)):
+        n, out, _ = O.spec_accept(logits, None, np.zeros((1, 0), np.int32), np.array([[u]]), 1.0)
+        assert n[0] == 0 and out[0, 0] == want, (u, out)
+    # temperature 0.5 squares the weights: p = 1/30, 4/30, 9/30, 16/30
+    for u, want in ((0.03, 0), (0.04, 1), (0.16, 1), (0.17, 2), (0.46, 2), (0.47, 3)):
+        _, out, _ = O.spec_accept(logits, None, np.zeros((1, 0), np.int32), np.array([[u]]), 0.5)
+        assert out[0, 0] == want, (u, out)
+    n, out, _ = O.spec_accept(np.array([[[0.0, 7.0, 7.0, 1.0]]]), None, np.zeros((1, 0), np.int32), None, 0.0)
+    assert n[0] == 0 and out[0, 0] == 1
+
+
+def test_sampling_step_frequencies_follow_softmax():
+    rng = np.random.default_rng(3)
+    logits = rng.normal(size=(1, 1, 6)) * 1.5
+    p = np.exp(logits[0, 0] / 0.8); p /= p.sum()
+    draws = 20000
+    u = rng.random(draws)
+    counts = np.zeros(6)
+    big = np.repeat(logits, draws, axis=0)
+    _, out, _ = O.spec_accept(big, None, np.zeros((draws, 0), np.int32), u[:, None], 0.8)
+    for k in out[:, 0]:
+        counts[k] += 1
+    chi2 = float(np.sum((counts - draws * p) ** 2 / (draws * p)))
+    assert chi2 < 25.7                                            # chi-square, 5 dof, p = 1e-4
+
+
+def test_tvd_rows_closed_forms():
+    """Eq. (TVD) on logits: identical rows give 0, disjoint supports give 1, two-token rows give
+    |sigmoid(a/T) - sigmoid(b/T)|, and a shift of either row by a constant changes nothing."""
+    t = np.array([[0.0, 1.0, 2.0], [0.0, -np.inf, -np.inf], [3.0, 0.0, -np.inf]])
+    d = np.array([[5.0, 6.0, 7.0], [-np.inf, 0.0, 1.0], [-1.0, 0.0, -np.inf]])
+    T = 0.7
+    got = O.tvd_rows(t, d, T)
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    assert abs(got[0]) < 1e-15
+    assert abs(got[1] - 1.0) < 1e-15
+    assert abs(got[2] - abs(sig(3.0 / T) - sig(-1.0 / T))) < 1e-14
+
+
+def test_embed_tokens_gathers_rows():
+    table = np.arange(20, dtype=np.float32).reshape(5, 4)
+    out = O.embed_tokens(table, [3, 0, 4, 7, -1])
+    assert np.array_equal(out[0], table[3]) and np.array_equal(out[1], table[0]) and np.array_equal(out[2], table[4])
+    assert not out[3].any() and not out[4].any()
