@@ -58,8 +58,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen7b_full",
-                    choices=["qwen7b_full", "qwen7b_layer", "gemma12b_layer"])
+                    choices=["qwen7b_full", "qwen7b_layer", "gemma12b_layer", "sd_iteration"])
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (debugging)")
+    ap.add_argument("--temperature", type=float, default=None, help="override the workload's sampling temperature")
     ap.add_argument("--no-extra", action="store_true", help="skip the attention/accept bandwidth section")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU checker timing")
     ap.add_argument("--seed", type=int, default=0)
@@ -103,9 +104,14 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload == "sd_iteration":
+        print(json.dumps(iteration_bench(torch, binding, synth, dev, args)))
+        return
     wl = dict(WORKLOADS[args.workload])
     if args.layers:
         wl["layers"] = args.layers
+    if args.temperature is not None:
+        wl["temperature"] = float(args.temperature)
     shape = getattr(synth, wl["shape"])
     B, gamma, N = wl["batch"], wl["gamma"], wl["layers"]
     Q, M = gamma + 1, wl["batch"] * (gamma + 1)
@@ -240,6 +246,121 @@ def main():
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, args.seed)
     print(json.dumps(result))
+
+
+class DeviceModel:
+    """A random-weight decoder stack with embedding table, vocabulary projection and a KV cache, on the device."""
+
+    def __init__(self, torch, binding, shape, n_layers, B, l_max, gen, dev):
+        bf = torch.bfloat16
+        H, F, d = shape.hidden, shape.mlp, shape.head_dim
+        nq, nkv = shape.n_q_heads * d, shape.n_kv_heads * d
+
+        def randn(*s, std=1.0, mean=0.0):
+            return (torch.randn(*s, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(bf)
+
+        ws, ks, vs = [], [], []
+        for _ in range(n_layers):
+            w = {"ln1": randn(H, std=0.1, mean=1.0), "wq": randn(nq, H, std=0.02), "wk": randn(nkv, H, std=0.02),
+                 "wv": randn(nkv, H, std=0.02), "wo": randn(H, nq, std=0.02), "ln2": randn(H, std=0.1, mean=1.0),
+                 "wg": randn(F, H, std=0.02), "wu": randn(F, H, std=0.02), "wd": randn(H, F, std=0.02),
+                 "bq": None, "bk": None, "bv": None}
+            if shape.qkv_bias:
+                w.update(bq=randn(nq, std=0.02), bk=randn(nkv, std=0.02), bv=randn(nkv, std=0.02))
+            ws.append(binding.pack_layer_weights(w))
+            ks.append(randn(B, shape.n_kv_heads, l_max, d))
+            vs.append(binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d)))
+        self.shape, self.l_max = shape, l_max
+        self.stack = binding.LayerStack(ws, ks, vs)
+        self.final_norm = randn(H, std=0.1, mean=1.0)
+        self.w_lm = binding.weight_pack(randn(shape.vocab, H, std=0.02))
+        self.table = randn(shape.vocab, H)
+        self.cfg = binding.LayerConfig(H, shape.n_q_heads, shape.n_kv_heads, d, F, shape.act, shape.qkv_bias,
+                                       shape.norm_eps, shape.rope_theta)
+        self.weight_bytes = n_layers * (nq * H + 2 * nkv * H + H * nq + 3 * F * H) * 2 + shape.vocab * H * 2
+
+
+def iteration_bench(torch, binding, synth, dev, args):
+    """One whole speculative-decoding iteration (paper Section 2.1) at the 7B-target / 1.5B-drafter shapes:
+    gamma drafter decode steps (embedding, 28 layers at one query position, vocabulary projection, draw),
+    then the target's verify pass over gamma+1 positions and the accept rule.  Random weights: acceptance
+    is near zero, so tokens/s here is a floor; the per-part times and their ratio are the result."""
+    B, gamma, T = 8, 5, float(args.temperature or 0.0)
+    Q = gamma + 1
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    rng = np.random.default_rng(args.seed)
+    kv_len_h = rng.integers(1024, 2049, B).astype(np.int32)
+    n_img_h = rng.integers(256, 1025, B).astype(np.int32)
+    l_max = (2048 + Q + 31) // 32 * 32
+    n_layers = args.layers or 28
+    tgt = DeviceModel(torch, binding, synth.QWEN7B, n_layers, B, l_max, gen, dev)
+    drf = DeviceModel(torch, binding, synth.QWEN1P5B, n_layers, B, l_max, gen, dev)
+    V = tgt.shape.vocab
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    kv_t, pos_t = i32(kv_len_h), i32(synth.positions(kv_len_h, n_img_h, Q))
+    kv_d = [i32(kv_len_h + i) for i in range(gamma)]
+    pos_d = [i32(synth.positions(kv_len_h + i, n_img_h, 1)) for i in range(gamma)]
+    last = torch.randint(0, V, (B,), generator=gen, device=dev, dtype=torch.int32)
+    uni_d = torch.rand(gamma, B, 1, generator=gen, device=dev).clamp_(max=1 - 2 ** -24)
+    uni_t = torch.rand(B, Q, generator=gen, device=dev).clamp_(max=1 - 2 ** -24)
+    seq = torch.empty((B, Q), dtype=torch.int32, device=dev)
+    step_logits = torch.empty((B, V), dtype=torch.float32, device=dev)
+    draft_logits = torch.empty((B, gamma, V), dtype=torch.float32, device=dev)
+    logits = torch.empty((B * Q, V), dtype=torch.float32, device=dev)
+    xd = torch.empty((B, 1, drf.shape.hidden), dtype=torch.bfloat16, device=dev)
+    xt = torch.empty((B, Q, tgt.shape.hidden), dtype=torch.bfloat16, device=dev)
+    n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    out_tok = torch.empty((B, Q), dtype=torch.int32, device=dev)
+    n0 = torch.empty((B,), dtype=torch.int32, device=dev)
+    tok = torch.empty((B, 1), dtype=torch.int32, device=dev)
+    ws = binding.workspace(1 << 28, dev)
+
+    def draft_steps():
+        seq[:, 0] = last
+        for i in range(gamma):
+            binding.embed_tokens(drf.table, seq[:, i].contiguous(), x=xd.view(B, -1))
+            binding.verify_layers(drf.cfg, drf.stack, xd, pos_d[i], kv_d[i], l_max, ws=ws)
+            binding.lm_head_logits(xd.view(B, -1), drf.final_norm, drf.w_lm, drf.shape.norm_eps, out=step_logits, ws=ws)
+            binding.spec_accept(step_logits.view(B, 1, V), None, None, uni_d[i] if T > 0 else None, T,
+                                n_accepted=n0, out_tokens=tok, ws=ws)
+            seq[:, i + 1] = tok[:, 0]
+            if T > 0:
+                draft_logits[:, i].copy_(step_logits)
+
+    def verify():
+        binding.embed_tokens(tgt.table, seq.view(-1), x=xt.view(B * Q, -1))
+        binding.verify_layers(tgt.cfg, tgt.stack, xt, pos_t, kv_t, l_max, ws=ws)
+        binding.lm_head_logits(xt.view(B * Q, -1), tgt.final_norm, tgt.w_lm, tgt.shape.norm_eps, out=logits, ws=ws)
+        binding.spec_accept(logits.view(B, Q, V), draft_logits if T > 0 else None, seq[:, 1:].contiguous(),
+                            uni_t if T > 0 else None, T, n_accepted=n_acc, out_tokens=out_tok, ws=ws)
+
+    def timed(fn, iters):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters
+
+    for _ in range(args.warmup):
+        draft_steps(); verify()
+    it_ms = timed(lambda: (draft_steps(), verify()), args.steps)
+    d_ms = timed(draft_steps, args.steps)
+    v_ms = timed(verify, args.steps)
+    emitted = int((n_acc + 1).sum().item())
+    return {
+        "metric": "whole speculative-decoding iteration (drafting loop + verify step)", "unit": "tokens/s",
+        "value": round(emitted / (it_ms * 1e-3), 1), "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(it_ms, 4), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "7B-shaped target + 1.5B-shaped drafter, %d layers each, B=8, gamma=5, "
+                               "kv_len U[1024,2048], T=%g" % (n_layers, T)},
+        "draft_loop_ms": round(d_ms, 4), "draft_step_ms": round(d_ms / gamma, 4), "verify_ms": round(v_ms, 4),
+        "cost_ratio_draft_step_over_verify": round(d_ms / gamma / v_ms, 4),
+        "draft_step_weight_stream_GBps": round(drf.weight_bytes / (d_ms / gamma * 1e-3) / 1e9, 1),
+        "verify_weight_stream_GBps": round(tgt.weight_bytes / (v_ms * 1e-3) / 1e9, 1),
+        "mean_emitted_per_sequence": round(emitted / B, 3),
+    }
 
 
 def time_calls(torch, fn, iters, warm=3):

@@ -7,9 +7,9 @@
 //                          chunk) produces {max, first arg-max, sum exp} with
 //                          shuffles only -- no LDS, no barriers, waves retire
 //                          independently.
-//           accept_decide  one wave per sequence merges the chunk partials in
-//                          chunk order, gathers the logits of the drafted
-//                          tokens and walks the accept chain.
+//           accept_decide  one workgroup per sequence merges the chunk partials
+//                          (a wave per row); lane i of its first wave tests
+//                          draft i, the first failure ends the chain.
 //   pass 2  residual_mass  (T > 0) re-reads the ONE target/draft row pair per
 //                          sequence the final token is drawn from and sums
 //                          max(p - q, 0) and p per chunk,
@@ -34,6 +34,10 @@ struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d;
 struct ChunkMass { double r, p; };
 
 struct TempScale { float hi, lo; double inv; };   // log2(e)/T split in two floats: d*hi + d*lo is d*log2(e)/T to ~1 ulp; inv = 1/T
+
+// 2^x by the hardware instruction alone: x <= 0 here, results below the smallest normal number flush to
+// zero (a probability under 2^-126 of the row's largest), no range handling needed.
+__device__ inline float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // d is a logit minus the row maximum (<= 0, possibly -inf for padding or a
 // zero-probability token); clamping to the largest finite value keeps
@@ -98,7 +102,7 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
         float acc = 0.f;
         if (m > -INFINITY) {
 #pragma unroll
-            for (int k = 0; k < kAccPerLane; ++k) acc += exp2f(scaled(x[k] - m, ts));
+            for (int k = 0; k < kAccPerLane; ++k) acc += exp2_raw(scaled(x[k] - m, ts));
         }
         s = wave_sum((double)acc);
     }
@@ -121,6 +125,20 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
     __shared__ double row_m[2 * kMaxGamma + 1], row_s[2 * kMaxGamma + 1];
     __shared__ int row_arg[2 * kMaxGamma + 1];
     const int nrows = greedy ? Q : Q + gamma;
+    // wave 0, lane i examines draft i: its token and the two logits at that token do not depend on the
+    // statistics, so their loads are issued before the merge below and are back when it is done
+    int tok = 0;
+    bool in_range = false;
+    float lt_f = 0.f, ld_f = 0.f, u_f = 0.f;
+    if (wave == 0 && lane < gamma) {
+        tok = tokens[b * gamma + lane];
+        in_range = (tok >= 0 && tok < V);
+        if (in_range && !greedy) {
+            lt_f = target[((size_t)b * Q + lane) * V + tok];
+            ld_f = draft[((size_t)b * gamma + lane) * V + tok];
+            u_f = uniforms[b * Q + lane];
+        }
+    }
     // one wave per row: lanes take the chunk partials, merged by a fixed shuffle tree
     for (int t = wave; t < nrows; t += kDecideThreads / kWave) {
         const int r = (t < Q) ? b * Q + t : B * Q + b * gamma + (t - Q);
@@ -144,22 +162,17 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
     __syncthreads();
     if (wave != 0) return;
 
-    // lane i examines draft i: all gathers and comparisons in parallel, then the first failure ends the chain
+    // all comparisons in parallel, then the first failure ends the chain
     bool ok = true;
-    int tok = 0;
     if (lane < gamma) {
-        tok = tokens[b * gamma + lane];
-        if (tok < 0 || tok >= V) {
+        if (!in_range) {
             ok = false;
         } else if (greedy) {
             ok = (tok == row_arg[lane]);
         } else {
-            const double lt = (double)target[((size_t)b * Q + lane) * V + tok];
-            const double ld = (double)draft[((size_t)b * gamma + lane) * V + tok];
-            const double p = exp((lt - row_m[lane]) * inv_t) / row_s[lane];
-            const double q = exp((ld - row_m[Q + lane]) * inv_t) / row_s[Q + lane];
-            const double u = (double)uniforms[b * Q + lane];
-            ok = (p >= q) || (u * q < p);
+            const double p = exp(((double)lt_f - row_m[lane]) * inv_t) / row_s[lane];
+            const double q = exp(((double)ld_f - row_m[Q + lane]) * inv_t) / row_s[Q + lane];
+            ok = (p >= q) || ((double)u_f * q < p);
         }
     }
     const unsigned long long fail = __ballot(!ok);
@@ -185,7 +198,7 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
 // exactly equal probabilities and p - q is exactly zero there.
 __device__ inline double prob_of(float logit, double m, double inv_s, TempScale ts) {
 #pragma clang fp contract(off)
-    const double p = (double)exp2f(scaled(logit - (float)m, ts)) * inv_s;
+    const double p = (double)exp2_raw(scaled(logit - (float)m, ts)) * inv_s;
     return p;
 }
 
