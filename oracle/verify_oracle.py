@@ -42,6 +42,15 @@ What it leaves open, and the reading taken here:
       half-split pairing (j, j + d/2) with angle pos * theta^(-2j/d), gated MLP
       down(act(gate(x)) * up(x)) with act = SiLU or tanh-GELU.
 
+  R13 Variants of the layer used by the Gemma 3 targets of Section 5 ("Models"),
+      which the paper names but does not describe; taken from that model
+      family's public description: (a) sliding-window layers, where a query at
+      cache row r sees rows max(0, r-W+1) .. r only; (b) RMSNorm over head_dim
+      of every query and key head (own gain vectors) after the projection and
+      before the rotary embedding; (c) an RMSNorm of the attention block's and
+      of the MLP block's output before each is added to the residual stream.
+      All are optional and off for the Qwen-shaped configurations.
+
 Pins (tests/test_oracle_*.py): brute-force attention loops, closed forms for
 constant keys / values, causality and grouped-head invariants, equivalence of
 the parallel pass with one-query-at-a-time decoding, library special cases for
@@ -134,12 +143,13 @@ def softmax(z, axis=-1):
     return e / np.sum(e, axis=axis, keepdims=True)
 
 
-def attention(q, k_cache, v_cache, kv_len, scale=None):
+def attention(q, k_cache, v_cache, kv_len, scale=None, window=0):
     """Grouped-query causal attention of the Q new positions (reading R1).
 
     q: [B, Q, n_q, d]; k_cache, v_cache: [B, n_kv, L_max, d] whose rows
     [0, kv_len[b] + Q) are valid (the new positions are already appended);
-    kv_len: [B] lengths before the step.  Returns [B, Q, n_q, d] float64.
+    kv_len: [B] lengths before the step.  window W > 0: the query at cache row r
+    sees rows max(0, r - W + 1) .. r only (R13a).  Returns [B, Q, n_q, d] float64.
     """
     q = np.asarray(q, dtype=np.float64)
     k_cache = np.asarray(k_cache, dtype=np.float64)
@@ -156,8 +166,9 @@ def attention(q, k_cache, v_cache, kv_len, scale=None):
             g = h // G
             for i in range(Q):
                 n_vis = L + i + 1
-                s = scale * (k_cache[b, g, :n_vis] @ q[b, i, h])
-                out[b, i, h] = softmax(s) @ v_cache[b, g, :n_vis]
+                lo = max(0, n_vis - int(window)) if window else 0
+                s = scale * (k_cache[b, g, lo:n_vis] @ q[b, i, h])
+                out[b, i, h] = softmax(s) @ v_cache[b, g, lo:n_vis]
     return out
 
 
@@ -165,9 +176,11 @@ def verify_layer(shape, w, x, pos, k_cache, v_cache, kv_len):
     """One decoder layer over the Q new positions of every sequence.
 
     shape: object with hidden, n_q_heads, n_kv_heads, head_dim, mlp, act,
-    norm_eps, rope_theta, dtype.  w: dict of ln1, wq, wk, wv, bq, bk, bv, wo,
-    ln2, wg, wu, wd.  x: [B, Q, H].  Returns (x_out, k_cache, v_cache) with the
-    new rows written at [kv_len[b], kv_len[b] + Q) on the storage grid."""
+    norm_eps, rope_theta, dtype and optionally window.  w: dict of ln1, wq, wk,
+    wv, bq, bk, bv, wo, ln2, wg, wu, wd and optionally q_norm, k_norm [d],
+    post_attn_norm, post_mlp_norm [H] (R13).  x: [B, Q, H].  Returns (x_out,
+    k_cache, v_cache) with the new rows written at [kv_len[b], kv_len[b] + Q) on
+    the storage grid."""
     x = np.asarray(x, dtype=np.float64)
     B, Q, H = x.shape
     nq, nkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
@@ -178,16 +191,26 @@ def verify_layer(shape, w, x, pos, k_cache, v_cache, kv_len):
     q = linear(xn, w["wq"], w.get("bq")).reshape(B, Q, nq, d)
     k = linear(xn, w["wk"], w.get("bk")).reshape(B, Q, nkv, d)
     v = linear(xn, w["wv"], w.get("bv")).reshape(B, Q, nkv, d)
+    if w.get("q_norm") is not None:
+        q = rmsnorm(q, w["q_norm"], shape.norm_eps)
+    if w.get("k_norm") is not None:
+        k = rmsnorm(k, w["k_norm"], shape.norm_eps)
     q = rope(q, pos, shape.rope_theta)
     k = rope(k, pos, shape.rope_theta)
     for b in range(B):
         L = int(kv_len[b])
         k_cache[b, :, L:L + Q] = _store(k[b].transpose(1, 0, 2), shape.dtype)
         v_cache[b, :, L:L + Q] = _store(v[b].transpose(1, 0, 2), shape.dtype)
-    o = attention(q, k_cache, v_cache, kv_len)
-    h = x + linear(o.reshape(B, Q, nq * d), w["wo"])
+    o = attention(q, k_cache, v_cache, kv_len, window=getattr(shape, "window", 0))
+    a = linear(o.reshape(B, Q, nq * d), w["wo"])
+    if w.get("post_attn_norm") is not None:
+        a = rmsnorm(a, w["post_attn_norm"], shape.norm_eps)
+    h = x + a
     hn = rmsnorm(h, w["ln2"], shape.norm_eps)
-    y = h + gated_mlp(hn, w["wg"], w["wu"], w["wd"], shape.act)
+    f = gated_mlp(hn, w["wg"], w["wu"], w["wd"], shape.act)
+    if w.get("post_mlp_norm") is not None:
+        f = rmsnorm(f, w["post_mlp_norm"], shape.norm_eps)
+    y = h + f
     return _store(y, shape.dtype), k_cache, v_cache
 
 

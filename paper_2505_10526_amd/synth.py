@@ -48,6 +48,11 @@ class LayerShape:
     norm_eps: float = 1e-6
     rope_theta: float = 1e6
     dtype: str = "bf16"          # "bf16" or "f32"
+    # Variants of the Gemma 3 family (the 12B / 27B targets of Section 5): sliding-window attention over the
+    # last `window` cache rows (0 = all), RMSNorm of every query / key head, RMSNorm of each block's output.
+    window: int = 0
+    qk_norm: bool = False
+    post_norms: bool = False
 
     @property
     def group(self) -> int:
@@ -63,6 +68,13 @@ GEMMA12B = LayerShape(3840, 16, 8, 256, 15360, 262144, ACT_GELU_TANH, False)
 # The drafter's vocabulary is taken equal to the target's so that both logit rows index the same tokens.
 TINY_DRAFT_BF16 = LayerShape(128, 2, 1, 64, 352, 4096, ACT_SILU, True, dtype="bf16")
 QWEN1P5B = LayerShape(1536, 12, 2, 128, 8960, 152064, ACT_SILU, True)
+# A local (sliding-window) layer of the Gemma3-12B-shaped target with that family's extra norms.
+GEMMA12B_LOCAL = LayerShape(3840, 16, 8, 256, 15360, 262144, ACT_GELU_TANH, False, rope_theta=1e4,
+                            window=1024, qk_norm=True, post_norms=True)
+TINY_GEMMA = LayerShape(256, 4, 2, 64, 688, 4096, ACT_GELU_TANH, False, rope_theta=1e4, dtype="f32",
+                        window=48, qk_norm=True, post_norms=True)
+TINY_GEMMA_BF16 = LayerShape(256, 4, 2, 64, 704, 4096, ACT_GELU_TANH, False, rope_theta=1e4, dtype="bf16",
+                             window=48, qk_norm=True, post_norms=True)
 
 
 def _rng(seed, *stream):
@@ -109,6 +121,12 @@ def layer_weights(shape: LayerShape, seed: int, layer: int = 0, std: float = 0.0
         w["bq"] = normal((nq,), std, seed, layer, 9, dtype=dt)
         w["bk"] = normal((nkv,), std, seed, layer, 10, dtype=dt)
         w["bv"] = normal((nkv,), std, seed, layer, 11, dtype=dt)
+    if s.qk_norm:
+        w["q_norm"] = normal((d,), 0.1, seed, layer, 12, dtype=dt, mean=1.0)
+        w["k_norm"] = normal((d,), 0.1, seed, layer, 13, dtype=dt, mean=1.0)
+    if s.post_norms:
+        w["post_attn_norm"] = normal((H,), 0.1, seed, layer, 14, dtype=dt, mean=1.0)
+        w["post_mlp_norm"] = normal((H,), 0.1, seed, layer, 15, dtype=dt, mean=1.0)
     return w
 
 
