@@ -91,6 +91,10 @@ int massv_abi_version(void);
 /* new positions' own keys included (they must already be in the cache at     */
 /* rows L_b .. L_b+Q-1).  Query head h reads KV head h / G.                   */
 /*   out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:].k[b,h/G,j,:]) v[b,h/G,j,:] */
+/* window = W > 0 restricts query i to the last W of those rows,               */
+/* [max(0, L_b+i-W+1), L_b+i]: the sliding-window layers of the Gemma 3        */
+/* targets named in Section 5 ("Models"); rows before the window of the first  */
+/* query are not read at all.                                                  */
 /* ------------------------------------------------------------------------- */
 typedef struct {
     int32_t batch;            /* B >= 1 */
@@ -101,6 +105,7 @@ typedef struct {
     int32_t l_max;            /* rows allocated per (b, kv head); multiple of 32 */
     float   scale;            /* 0 => 1/sqrt(head_dim) */
     int32_t dtype;            /* massv_dtype of q, caches and out */
+    int32_t window;           /* 0: every cached row; W > 0: the last W rows only */
 } massv_attn_desc;
 
 /* Bytes of workspace massv_verify_attention needs for this descriptor (0 if the
@@ -137,6 +142,12 @@ int massv_weight_pack(const void* src_row_major, void* dst, int32_t N, int32_t K
 /*   x <- h + (act(hn Wg^T) * (hn Wu^T)) Wd^T                                  */
 /* rmsnorm(x,g) = x * g / sqrt(mean(x^2) + eps).  rope rotates the pairs       */
 /* (j, j + d/2) of every head by angle pos * theta^(-2j/d).                    */
+/* Optional steps of the Gemma 3 family (Section 5's 12B / 27B targets), each  */
+/* switched on by a non-NULL gain vector in massv_layer_weights:               */
+/*   q_norm, k_norm [d]:  every query / key head is replaced by its rmsnorm    */
+/*                        over head_dim (after the bias, before rope);        */
+/*   post_attn_norm [H]:  h = x + rmsnorm(a Wo^T, post_attn_norm);             */
+/*   post_mlp_norm [H]:   x <- h + rmsnorm(mlp output, post_mlp_norm).         */
 /* ------------------------------------------------------------------------- */
 typedef struct {
     massv_attn_desc attn;     /* batch, n_query, heads, head_dim, l_max, scale, dtype */
@@ -163,6 +174,10 @@ typedef struct {
     const void* wg;           /* [F][H] */
     const void* wu;           /* [F][H] */
     const void* wd;           /* [H][F] */
+    const void* q_norm;       /* [d] or NULL */
+    const void* k_norm;       /* [d] or NULL */
+    const void* post_attn_norm; /* [H] or NULL */
+    const void* post_mlp_norm;  /* [H] or NULL */
 } massv_layer_weights;
 
 size_t massv_verify_layer_workspace(const massv_layer_desc* desc);
@@ -185,10 +200,14 @@ int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* 
  * slice of it): weights[l], k_caches[l], v_caches[l] belong to layer l; `weights`, `k_caches`,
  * `v_caches` are HOST arrays (of structs / of device pointers) read before the call returns.  Equal to
  * n_layers calls of massv_verify_layer, except that the norm opening layer l+1 is computed by the kernel
- * that closes layer l from its un-rounded sum (one launch fewer per layer).  Workspace as for one layer. */
+ * that closes layer l from its un-rounded sum (one launch fewer per layer).  Workspace as for one layer.
+ * windows, rope_thetas: HOST arrays [n_layers] that replace desc->attn.window / desc->rope_theta for
+ * layer l (stacks that interleave sliding-window and global layers), or NULL to use the descriptor's
+ * values for every layer. */
 int massv_verify_layers(const massv_layer_desc* desc, const massv_layer_weights* weights, int32_t n_layers,
                         void* x, const int32_t* pos, void* const* k_caches, void* const* v_caches,
-                        const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream);
+                        const int32_t* kv_len, const int32_t* windows, const float* rope_thetas,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- */
 /* lm_head_logits: logits[m, v] = sum_k rmsnorm(x, final_norm)[m, k] * w_lm[v, k] */

@@ -36,7 +36,7 @@ K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEP
 class AttnDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_query", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("l_max", C.c_int32),
-                ("scale", C.c_float), ("dtype", C.c_int32)]
+                ("scale", C.c_float), ("dtype", C.c_int32), ("window", C.c_int32)]
 
 
 class LayerDesc(C.Structure):
@@ -44,7 +44,8 @@ class LayerDesc(C.Structure):
                 ("qkv_bias", C.c_int32), ("norm_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
-WEIGHT_FIELDS = ["ln1", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ln2", "wg", "wu", "wd"]
+WEIGHT_FIELDS = ["ln1", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ln2", "wg", "wu", "wd",
+                 "q_norm", "k_norm", "post_attn_norm", "post_mlp_norm"]
 
 
 class LayerWeights(C.Structure):
@@ -86,7 +87,8 @@ def load():
                                        vp, sz, vp]
     lib.massv_verify_layers.restype = C.c_int
     lib.massv_verify_layers.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), i32, vp, vp,
-                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, vp, sz, vp]
+                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp,
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_float), vp, sz, vp]
     lib.massv_lm_head_logits_workspace.restype = sz
     lib.massv_lm_head_logits_workspace.argtypes = [i32, i32, i32, i32]
     lib.massv_lm_head_logits.restype = C.c_int
@@ -157,8 +159,8 @@ def _need(t, name, dtype=None):
 # ---------------------------------------------------------------------------
 # verify_attention
 # ---------------------------------------------------------------------------
-def attn_desc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, dtype, scale=0.0) -> AttnDesc:
-    return AttnDesc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, scale, dtype)
+def attn_desc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, dtype, scale=0.0, window=0) -> AttnDesc:
+    return AttnDesc(batch, n_query, n_q_heads, n_kv_heads, head_dim, l_max, scale, dtype, window)
 
 
 def v_cache_pack(v_row_major: torch.Tensor) -> torch.Tensor:
@@ -172,16 +174,17 @@ def v_cache_pack(v_row_major: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def verify_attention(q, k_cache, v_cache, kv_len, scale=0.0, out=None, ws=None):
+def verify_attention(q, k_cache, v_cache, kv_len, scale=0.0, out=None, ws=None, window=0):
     """q [B,Q,n_q,d]; k_cache [B,n_kv,L_max,d]; v_cache blocked [B,n_kv,L_max/32,d,32];
-    kv_len int32 [B].  Returns out [B,Q,n_q,d]."""
+    kv_len int32 [B]; window > 0: sliding-window attention over the last `window` rows.
+    Returns out [B,Q,n_q,d]."""
     lib = load()
     for t, n in ((q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache")):
         _need(t, n, q.dtype)
     _need(kv_len, "kv_len", torch.int32)
     B, Q, n_q, d = q.shape
     n_kv, l_max = k_cache.shape[1], k_cache.shape[2]
-    desc = attn_desc(B, Q, n_q, n_kv, d, l_max, dtype_code(q), scale)
+    desc = attn_desc(B, Q, n_q, n_kv, d, l_max, dtype_code(q), scale, window)
     if out is None:
         out = torch.empty_like(q)
     need = lib.massv_verify_attention_workspace(C.byref(desc))
@@ -207,10 +210,11 @@ class LayerConfig:
     norm_eps: float = 1e-6
     rope_theta: float = 1e6
     scale: float = 0.0
+    window: int = 0
 
 
 def layer_desc(cfg: LayerConfig, batch, n_query, l_max, dtype) -> LayerDesc:
-    a = attn_desc(batch, n_query, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, l_max, dtype, cfg.scale)
+    a = attn_desc(batch, n_query, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, l_max, dtype, cfg.scale, cfg.window)
     return LayerDesc(a, cfg.hidden, cfg.mlp, cfg.act, int(bool(cfg.qkv_bias)), cfg.norm_eps, cfg.rope_theta)
 
 
@@ -275,9 +279,15 @@ class LayerStack:
     """Marshalled arguments of massv_verify_layers for a fixed stack of layers: arrays of weight
     structs and cache pointers built once.  Keeps the tensors alive."""
 
-    def __init__(self, weights: list, k_caches: list, v_caches: list):
+    def __init__(self, weights: list, k_caches: list, v_caches: list, windows=None, rope_thetas=None):
+        """windows / rope_thetas: optional per-layer sliding-window sizes and rotary bases (stacks that
+        interleave local and global layers); None = the descriptor's values for every layer."""
         n = len(weights)
         assert n == len(k_caches) == len(v_caches) and n >= 1
+        assert windows is None or len(windows) == n
+        assert rope_thetas is None or len(rope_thetas) == n
+        self.windows = None if windows is None else (C.c_int32 * n)(*[int(v) for v in windows])
+        self.rope_thetas = None if rope_thetas is None else (C.c_float * n)(*[float(v) for v in rope_thetas])
         self.n = n
         self._keep = (weights, k_caches, v_caches)
         lws = [w if isinstance(w, LayerWeights) else layer_weights(w) for w in weights]
@@ -298,7 +308,8 @@ def verify_layers(cfg: LayerConfig, stack: LayerStack, x, pos, kv_len, l_max, ws
     if ws is None:
         ws = workspace(lib.massv_verify_layer_workspace(C.byref(desc)), x.device)
     _check(lib.massv_verify_layers(C.byref(desc), stack.weights, stack.n, _ptr(x), _ptr(pos), stack.k, stack.v,
-                                   _ptr(kv_len), _ptr(ws), ws.numel(), _stream()), "massv_verify_layers")
+                                   _ptr(kv_len), stack.windows, stack.rope_thetas, _ptr(ws), ws.numel(), _stream()),
+           "massv_verify_layers")
     return x
 
 

@@ -54,13 +54,14 @@ template <typename T>
 __global__ __launch_bounds__(256)
 void attention_generic_kernel(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc,
                               const int32_t* __restrict__ kv_len, T* __restrict__ out,
-                              int Q, int n_q, int n_kv, int d, int l_max, float scale) {
+                              int Q, int n_q, int n_kv, int d, int l_max, float scale, int window) {
     const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int G = n_q / n_kv, g = h / G;
     const size_t bg = (size_t)b * n_kv + g;
     int L = kv_len[b]; L = L < 0 ? 0 : L;
     int n_vis = L + i + 1;
     if (n_vis > l_max) n_vis = l_max;
+    const int lo = (window > 0 && n_vis > window) ? n_vis - window : 0;      // first row of the sliding window
     __shared__ float qs[256];
     __shared__ float w[256];
     __shared__ float red[4];
@@ -68,7 +69,7 @@ void attention_generic_kernel(const T* __restrict__ q, const T* __restrict__ kc,
     if (tid < d) qs[tid] = ldf(qr + tid);
     __syncthreads();
     float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-    for (int j0 = 0; j0 < n_vis; j0 += 256) {
+    for (int j0 = lo; j0 < n_vis; j0 += 256) {
         const int j = j0 + tid;
         float s = -INFINITY;
         if (j < n_vis) {
@@ -119,6 +120,7 @@ struct AttnParams {
     bf16_t* out;                 // used when n_split == 1
     float* part_o; float* part_ml;   // [B][n_kv][S][rows_pad][D], [B][n_kv][S][rows_pad][2]
     int Q, n_q, n_kv, l_max, n_split;
+    int window;                  // 0: all rows; W > 0: a query at row r sees rows r-W+1 .. r
     int out_mt;                  // > 0: out is written in operand order with this many row tiles
     float scale_log2;            // scale * log2(e)
 };
@@ -144,8 +146,14 @@ void attention_mfma_kernel(AttnParams p) {
     int L = p.kv_len[b]; L = L < 0 ? 0 : L;
     const int n_total = clamp_total(L, p.Q, p.l_max);
     const int n_blocks = (n_total + kBlk - 1) / kBlk;
-    const int per = (n_blocks + p.n_split - 1) / p.n_split;
-    const int blk_begin = split * per;
+    // sliding window: the first query (row L) sees rows from L-W+1 on and later queries start higher, so
+    // blocks below that row are skipped altogether; blocks that hold a row below the LAST query's window
+    // start (row L+Q-W) need the lower mask
+    const int W = p.window;
+    const int blk_lo = (W > 0 && L + 1 > W) ? (L + 1 - W) / kBlk : 0;
+    const int low_mask_end = (W > 0) ? L + p.Q - W : 0;         // rows below it are outside some query's window
+    const int per = (n_blocks - blk_lo + p.n_split - 1) / p.n_split;
+    const int blk_begin = blk_lo + split * per;
     const int blk_end = (blk_begin + per < n_blocks) ? blk_begin + per : n_blocks;
     const int first_masked_blk = L / kBlk;      // blocks before it hold cached positions only
 
@@ -226,7 +234,7 @@ void attention_mfma_kernel(AttnParams p) {
                 for (int e = 0; e < 8; ++e)
                     if (blk * kBlk + lc * 8 + e >= n_total) vreg[nt][e] = (bf16_t)0.f;
         }
-        const bool masked = blk >= first_masked_blk;
+        const bool masked = blk >= first_masked_blk || blk * kBlk < low_mask_end;
 
         // ---- S^T tile pairs: lane holds keys 8 lc + (0..7) of query row 16 mt + lr ----
         floatx4 s0[MT], s1[MT];
@@ -247,9 +255,12 @@ void attention_mfma_kernel(AttnParams p) {
             float sv[8] = {s0[mt][0], s0[mt][1], s0[mt][2], s0[mt][3], s1[mt][0], s1[mt][1], s1[mt][2], s1[mt][3]};
             if (masked) {
                 const int last_visible = L + qi[mt];
+                const int first_visible = W > 0 ? last_visible - W + 1 : 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (blk * kBlk + lc * 8 + e > last_visible) sv[e] = -INFINITY;
+                for (int e = 0; e < 8; ++e) {
+                    const int key = blk * kBlk + lc * 8 + e;
+                    if (key > last_visible || key < first_visible) sv[e] = -INFINITY;
+                }
             }
             float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
             mx *= p.scale_log2;                                // scale > 0: the maximum commutes with it
@@ -456,6 +467,7 @@ int check_attn_desc(const massv_attn_desc* a) {
     if (a->l_max < kBlk || a->l_max % kBlk) return MASSV_EINVAL;
     if (a->n_query > a->l_max) return MASSV_EINVAL;
     if (!(a->scale >= 0.f) || isinf(a->scale)) return MASSV_EINVAL;
+    if (a->window < 0) return MASSV_EINVAL;
     if (a->dtype != MASSV_F32 && a->dtype != MASSV_BF16) return MASSV_EINVAL;
     if (a->head_dim % 2) return MASSV_EINVAL;
     if (a->batch > 65535 || a->n_q_heads > 65535) return MASSV_EUNSUPPORTED;
@@ -507,7 +519,7 @@ int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cach
     if (a.dtype == MASSV_F32) {
         hipLaunchKernelGGL(attention_generic_kernel<float>, dim3(a.n_query, a.n_q_heads, a.batch), dim3(256), 0, st,
                            (const float*)q, (const float*)k_cache, (const float*)v_cache, kv_len, (float*)out,
-                           a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, scale);
+                           a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, scale, a.window);
         return launch_status();
     }
     AttnParams p;
@@ -515,6 +527,7 @@ int launch_attention(const massv_attn_desc& a, const void* q, const void* k_cach
     p.out = (bf16_t*)out;
     p.Q = a.n_query; p.n_q = a.n_q_heads; p.n_kv = a.n_kv_heads; p.l_max = a.l_max;
     p.n_split = n_split_of(a);
+    p.window = a.window;
     p.out_mt = out_packed ? (a.batch * a.n_query + 15) / 16 : 0;
     p.scale_log2 = scale * 1.4426950408889634f;
     const int rp = rows_pad_of(a);

@@ -76,6 +76,17 @@ int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float ep
     return launch_status();
 }
 
+// Sum of one float per thread over a workgroup of at most 256 threads (every thread must call it).
+__device__ inline float block_sum_256(float v, float* red /* [4] shared */) {
+    v = wave_sum(v);
+    __syncthreads();                                  // red may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int w = 0; w < (int)(blockDim.x + 63) / 64; ++w) t += red[w];
+    return t;
+}
+
 // ---------------------------------------------------------------------------
 // Rotary embedding + KV append.  grid = (M, n_q + 2 n_kv); thread j < d/2 owns
 // the pair (j, j + d/2) of one head of one token.
@@ -88,14 +99,23 @@ template <typename T>
 __global__ void rope_append_kernel(const T* __restrict__ qkv, const int32_t* __restrict__ pos,
                                    const int32_t* __restrict__ kv_len, T* __restrict__ q_out,
                                    T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                   const T* __restrict__ q_norm, const T* __restrict__ k_norm, float eps,
                                    int Q, int n_q, int n_kv, int d, int l_max, double log2_theta) {
     const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
     const int half = d / 2;
-    if (j >= half) return;
+    const bool live = j < half;
     const int b = m / Q, i = m % Q;
     const int width = (n_q + 2 * n_kv) * d;
     const T* src = qkv + (size_t)m * width + (size_t)head * d;
-    const float x1 = ldf(src + j), x2 = ldf(src + j + half);
+    float x1 = live ? ldf(src + j) : 0.f, x2 = live ? ldf(src + j + half) : 0.f;
+    const T* hn = head < n_q ? q_norm : head < n_q + n_kv ? k_norm : nullptr;
+    if (hn) {                                            // uniform over the workgroup: RMSNorm of the head
+        __shared__ float red[4];
+        const float ss = block_sum_256(x1 * x1 + x2 * x2, red);
+        const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+        if (live) { x1 *= rstd * ldf(hn + j); x2 *= rstd * ldf(hn + j + half); }
+    }
+    if (!live) return;
     int row = kv_len[b];
     row = (row < 0 ? 0 : row) + i;
     if (head < n_q + n_kv) {
@@ -121,33 +141,40 @@ __global__ void rope_append_kernel(const T* __restrict__ qkv, const int32_t* __r
 }
 
 int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
-                       void* k_cache, void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st) {
+                       void* k_cache, void* v_cache, const void* q_norm, const void* k_norm, float eps,
+                       const massv_attn_desc& a, float theta, hipStream_t st) {
     const int M = a.batch * a.n_query;
     dim3 grid(M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
     const double l2t = log2((double)theta);
     if (a.dtype == MASSV_F32)
         hipLaunchKernelGGL(rope_append_kernel<float>, grid, block, 0, st, (const float*)qkv, pos, kv_len, (float*)q_out,
-                           (float*)k_cache, (float*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+                           (float*)k_cache, (float*)v_cache, (const float*)q_norm, (const float*)k_norm, eps,
+                           a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
     else
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)qkv, pos, kv_len, (bf16_t*)q_out,
-                           (bf16_t*)k_cache, (bf16_t*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+                           (bf16_t*)k_cache, (bf16_t*)v_cache, (const bf16_t*)q_norm, (const bf16_t*)k_norm, eps,
+                           a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
     return launch_status();
 }
 
 // bf16 path: the q/k/v projection leaves fp32 partial sums per K slab; this kernel sums them, adds the
-// bias, applies the rotary embedding and scatters q / k / v.  Same grid as rope_append_kernel.
+// bias, optionally normalises the query / key head, applies the rotary embedding and scatters q / k / v.
+// Same grid as rope_append_kernel.
 __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
                                   const bf16_t* __restrict__ bq, const bf16_t* __restrict__ bk,
                                   const bf16_t* __restrict__ bv, const int32_t* __restrict__ pos,
                                   const int32_t* __restrict__ kv_len, bf16_t* __restrict__ q_out,
                                   bf16_t* __restrict__ k_cache, bf16_t* __restrict__ v_cache,
+                                  const bf16_t* __restrict__ q_norm, const bf16_t* __restrict__ k_norm, float eps,
                                   int Q, int n_q, int n_kv, int d, int l_max, double log2_theta) {
     const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
     const int half = d / 2;
-    if (j >= half) return;
+    const bf16_t* hn = head < n_q ? q_norm : head < n_q + n_kv ? k_norm : nullptr;
+    if (j >= half && !hn) return;                        // with a head norm every thread reaches the block sum
+    const bool live = j < half;
     const int b = m / Q, i = m % Q;
     const int width = (n_q + 2 * n_kv) * d;
-    const size_t col = (size_t)head * d + j;
+    const size_t col = (size_t)head * d + (live ? j : 0);
     float x1 = 0.f, x2 = 0.f;
     for (int s0 = 0; s0 < n_slabs; s0 += 8) {           // 8 slabs' loads in flight at once; summed in slab order
         float t1[8], t2[8];
@@ -161,9 +188,17 @@ __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs
         for (int u = 0; u < 8; ++u) { x1 += t1[u]; x2 += t2[u]; }
     }
     const bf16_t* bias = head < n_q ? bq : head < n_q + n_kv ? bk : bv;
-    if (bias) {
+    if (bias && live) {
         const int hb = head < n_q ? head : head < n_q + n_kv ? head - n_q : head - n_q - n_kv;
         x1 += (float)bias[hb * d + j]; x2 += (float)bias[hb * d + j + half];
+    }
+    if (hn) {                                            // uniform over the workgroup: RMSNorm of the head
+        __shared__ float red[4];
+        if (!live) { x1 = 0.f; x2 = 0.f; }
+        const float ss = block_sum_256(x1 * x1 + x2 * x2, red);
+        const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+        if (!live) return;
+        x1 *= rstd * (float)hn[j]; x2 *= rstd * (float)hn[j + half];
     }
     int row = kv_len[b];
     row = (row < 0 ? 0 : row) + i;
@@ -189,12 +224,14 @@ __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs
 
 int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, const void* bq, const void* bk,
                       const void* bv, const int32_t* pos, const int32_t* kv_len, void* q_out, void* k_cache,
-                      void* v_cache, const massv_attn_desc& a, float theta, hipStream_t st) {
+                      void* v_cache, const void* q_norm, const void* k_norm, float eps,
+                      const massv_attn_desc& a, float theta, hipStream_t st) {
     const int M = a.batch * a.n_query;
     dim3 grid(M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
     hipLaunchKernelGGL(qkv_finish_kernel, grid, block, 0, st, partial, n_slabs, slab_stride, (const bf16_t*)bq,
                        (const bf16_t*)bk, (const bf16_t*)bv, pos, kv_len, (bf16_t*)q_out, (bf16_t*)k_cache,
-                       (bf16_t*)v_cache, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, log2((double)theta));
+                       (bf16_t*)v_cache, (const bf16_t*)q_norm, (const bf16_t*)k_norm, eps,
+                       a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, log2((double)theta));
     return launch_status();
 }
 
@@ -203,18 +240,33 @@ int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, con
 // (H <= 8192), so a row's loads are all in flight at once.
 constexpr int kFinishThreads = 1024;
 
+// Sum of one float per thread over the kFinishThreads threads of a workgroup (every thread calls it).
+__device__ inline float finish_block_sum(float v, float* part /* [kFinishThreads / kWave] shared */) {
+    v = wave_sum(v);
+    __syncthreads();                                  // part may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFinishThreads / kWave; ++w) tot += part[w];
+    return tot;
+}
+
+// post != nullptr: the projection's output row is RMS-normalised with these gains before it is added.
 __global__ __launch_bounds__(kFinishThreads)
 void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
-                            bf16_t* __restrict__ x, const bf16_t* __restrict__ ln, bf16_t* __restrict__ xn,
-                            int H, float eps, int mt_count) {
+                            bf16_t* __restrict__ x, const bf16_t* __restrict__ post, const bf16_t* __restrict__ ln,
+                            bf16_t* __restrict__ xn, int H, float eps, int mt_count) {
     const int m = blockIdx.x, tid = threadIdx.x;
     const int k8 = tid;
     const bool live = k8 < H / 8;
+    __shared__ float part[kFinishThreads / kWave];
     float v[8];
+    float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float ss = 0.f;
+    bf16x8 xv = {0, 0, 0, 0, 0, 0, 0, 0};
     if (live) {
-        const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
-        float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
         for (int s0 = 0; s0 < n_slabs; s0 += 4) {              // 4 slabs' loads in flight at once; summed in slab order
             floatx4 p0[4], p1[4];
 #pragma unroll
@@ -230,20 +282,26 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { add[e] += p0[u][e]; add[4 + e] += p1[u][e]; }
         }
+    }
+    if (post) {                                                // uniform over the grid
+        float sy = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sy += add[e] * add[e];
+        const float rstd_y = 1.0f / sqrtf(finish_block_sum(sy, part) / (float)H + eps);
+        if (live) {
+            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(post + k8 * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) add[e] *= rstd_y * (float)gv[e];
+        }
+    }
+    if (live) {
         bf16x8 o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) { v[e] = (float)xv[e] + add[e]; o[e] = (bf16_t)v[e]; ss += v[e] * v[e]; }
         *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
     }
     if (!ln) return;
-    ss = wave_sum(ss);
-    __shared__ float part[kFinishThreads / kWave];
-    if ((tid & 63) == 0) part[tid >> 6] = ss;
-    __syncthreads();
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < kFinishThreads / kWave; ++w) tot += part[w];
-    const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+    const float rstd = 1.0f / sqrtf(finish_block_sum(ss, part) / (float)H + eps);
     if (live) {
         const bf16x8 gv = *reinterpret_cast<const bf16x8*>(ln + k8 * 8);
         bf16x8 o;
@@ -253,11 +311,29 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
     }
 }
 
-int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* ln,
-                           void* xn_packed, int M, int H, float eps, hipStream_t st) {
+int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* post,
+                           const void* ln, void* xn_packed, int M, int H, float eps, hipStream_t st) {
     if (H % 8 || H > 8 * kFinishThreads) return MASSV_EUNSUPPORTED;
     hipLaunchKernelGGL(residual_finish_kernel, dim3(M), dim3(kFinishThreads), 0, st, partial, n_slabs, slab_stride,
-                       (bf16_t*)x, (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
+                       (bf16_t*)x, (const bf16_t*)post, (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
+    return launch_status();
+}
+
+// fp32 path: x += rmsnorm(y, g) row by row (the block-output norm); one workgroup per row.
+__global__ __launch_bounds__(256)
+void postnorm_residual_kernel(float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+                              int H, float eps) {
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const float* yr = y + (size_t)m * H;
+    float ss = 0.f;
+    for (int k = tid; k < H; k += 256) ss += yr[k] * yr[k];
+    __shared__ float red[4];
+    const float rstd = 1.0f / sqrtf(block_sum_256(ss, red) / (float)H + eps);
+    for (int k = tid; k < H; k += 256) x[(size_t)m * H + k] += yr[k] * rstd * g[k];
+}
+
+int launch_postnorm_residual(void* x, const void* y, const void* g, int M, int H, float eps, hipStream_t st) {
+    hipLaunchKernelGGL(postnorm_residual_kernel, dim3(M), dim3(256), 0, st, (float*)x, (const float*)y, (const float*)g, H, eps);
     return launch_status();
 }
 

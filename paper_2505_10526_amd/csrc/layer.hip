@@ -5,7 +5,7 @@
 
 namespace massv {
 
-struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, partial, attn_ws, total; };
+struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, proj, partial, attn_ws, total; };
 
 // The four projections of a layer as launch_gemm sees them (pointers filled in by the caller).
 struct LayerGemms { GemmArgs qkv, op, gu, dn; };
@@ -45,6 +45,7 @@ static LayerLayout layer_layout(const massv_layer_desc& d) {
     l.attn = o; o = align_up(o + Mp * nq * es, 256);
     l.h = o;    o = align_up(o + Mp * d.mlp * es, 256);
     l.gu = o;   o = align_up(o + (bf ? 0 : M * 2 * d.mlp * 4), 256);
+    l.proj = o; o = align_up(o + (bf ? 0 : M * d.hidden * 4), 256);   // fp32: a block's output ahead of its output norm
     l.partial = o; o = align_up(o + part, 256);
     l.attn_ws = o; o = align_up(o + attention_workspace(a), 256);
     l.total = o;
@@ -104,8 +105,10 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
     if (!bf) { g.qkv.bias[0] = bias ? w->bq : nullptr; g.qkv.bias[1] = bias ? w->bk : nullptr; g.qkv.bias[2] = bias ? w->bv : nullptr; }
     g.qkv.y = bf ? (void*)partial : (void*)(ws + lay.qkv);
     g.op.x = ws + lay.attn; g.op.w[0] = w->wo; g.op.residual = x; g.op.y = bf ? (void*)partial : x;
+    if (!bf && w->post_attn_norm) { g.op.epilogue = EPI_STORE; g.op.residual = nullptr; g.op.y = ws + lay.proj; }
     g.gu.x = ws + lay.xn; g.gu.w[0] = w->wg; g.gu.w[1] = w->wu; g.gu.y = ws + lay.h; g.gu.scratch = ws + lay.gu;
     g.dn.x = ws + lay.h; g.dn.w[0] = w->wd; g.dn.residual = x; g.dn.y = bf ? (void*)partial : x;
+    if (!bf && w->post_mlp_norm) { g.dn.epilogue = EPI_STORE; g.dn.residual = nullptr; g.dn.y = ws + lay.proj; }
 
     // shape checks for every projection before the first launch
     if ((rc = gemm_supported(g.qkv)) != MASSV_OK) return rc;
@@ -116,12 +119,17 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
     if (!bf) {
         if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
-        if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a, desc->rope_theta, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, w->q_norm, w->k_norm,
+                                     desc->norm_eps, a, desc->rope_theta, st)) != MASSV_OK) return rc;
         if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, false, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
+        if (w->post_attn_norm &&
+            (rc = launch_postnorm_residual(x, ws + lay.proj, w->post_attn_norm, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
         if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
-        return launch_gemm(g.dn, st);
+        if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
+        if (w->post_mlp_norm) return launch_postnorm_residual(x, ws + lay.proj, w->post_mlp_norm, M, H, desc->norm_eps, st);
+        return MASSV_OK;
     }
     // bf16: the narrow projections leave fp32 partial sums per K slab; the row-wise kernel that has to
     // run next anyway (rotary + append, residual + norm) sums them.
@@ -129,16 +137,16 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
     if (!xn_ready && (rc = launch_rmsnorm_packed(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
     if ((rc = launch_qkv_finish(partial, gemm_plan(g.qkv).slabs, Mp * wq, bias ? w->bq : nullptr, bias ? w->bk : nullptr,
-                                bias ? w->bv : nullptr, pos, kv_len, ws + lay.qrot, k_cache, v_cache, a,
-                                desc->rope_theta, st)) != MASSV_OK) return rc;
+                                bias ? w->bv : nullptr, pos, kv_len, ws + lay.qrot, k_cache, v_cache, w->q_norm, w->k_norm,
+                                desc->norm_eps, a, desc->rope_theta, st)) != MASSV_OK) return rc;
     if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, true, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
-    if ((rc = launch_residual_finish(partial, gemm_plan(g.op).slabs, Mp * H, x, w->ln2, ws + lay.xn, M, H,
-                                     desc->norm_eps, st)) != MASSV_OK) return rc;
+    if ((rc = launch_residual_finish(partial, gemm_plan(g.op).slabs, Mp * H, x, w->post_attn_norm, w->ln2, ws + lay.xn,
+                                     M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
-    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, next_ln, next_ln ? ws + lay.xn : nullptr,
-                                  M, H, desc->norm_eps, st);
+    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, w->post_mlp_norm, next_ln,
+                                  next_ln ? ws + lay.xn : nullptr, M, H, desc->norm_eps, st);
 }
 
 extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
@@ -155,13 +163,16 @@ extern "C" int massv_verify_layer(const massv_layer_desc* desc, const massv_laye
 
 extern "C" int massv_verify_layers(const massv_layer_desc* desc, const massv_layer_weights* weights, int32_t n_layers,
                                    void* x, const int32_t* pos, void* const* k_caches, void* const* v_caches,
-                                   const int32_t* kv_len, void* workspace, size_t workspace_bytes, void* stream) {
+                                   const int32_t* kv_len, const int32_t* windows, const float* rope_thetas,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_layer_desc(desc);
     if (rc != MASSV_OK) return rc;
     if (n_layers < 1 || !weights || !x || !pos || !k_caches || !v_caches || !kv_len) return MASSV_EINVAL;
     for (int l = 0; l < n_layers; ++l) {
         if ((rc = check_layer_weights(desc, weights + l)) != MASSV_OK) return rc;
         if (!k_caches[l] || !v_caches[l]) return MASSV_EINVAL;
+        if (windows && windows[l] < 0) return MASSV_EINVAL;
+        if (rope_thetas && !(rope_thetas[l] > 0.f)) return MASSV_EINVAL;
     }
     const LayerLayout lay = layer_layout(*desc);
     if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
@@ -169,7 +180,10 @@ extern "C" int massv_verify_layers(const massv_layer_desc* desc, const massv_lay
     for (int l = 0; l < n_layers; ++l) {
         // bf16: the norm that opens layer l+1 is computed by the kernel that closes layer l
         const void* next_ln = (bf && l + 1 < n_layers) ? weights[l + 1].ln1 : nullptr;
-        rc = run_layer(desc, weights + l, x, pos, k_caches[l], v_caches[l], kv_len, workspace, lay,
+        massv_layer_desc dl = *desc;                    // this layer's window and rotary base
+        if (windows) dl.attn.window = windows[l];
+        if (rope_thetas) dl.rope_theta = rope_thetas[l];
+        rc = run_layer(&dl, weights + l, x, pos, k_caches[l], v_caches[l], kv_len, workspace, lay,
                        bf && l > 0, next_ln, (hipStream_t)stream);
         if (rc != MASSV_OK) return rc;
     }

@@ -40,9 +40,9 @@ def test_status_strings(lib):
 
 
 def test_struct_sizes_match_header():
-    assert C.sizeof(binding.AttnDesc) == 32
-    assert C.sizeof(binding.LayerDesc) == 32 + 24
-    assert C.sizeof(binding.LayerWeights) == 12 * C.sizeof(C.c_void_p)
+    assert C.sizeof(binding.AttnDesc) == 36
+    assert C.sizeof(binding.LayerDesc) == 36 + 24
+    assert C.sizeof(binding.LayerWeights) == 16 * C.sizeof(C.c_void_p)
 
 
 FAKE = C.c_void_p(0x1000)      # never dereferenced: every call below must fail validation first
@@ -107,6 +107,12 @@ def test_attention_argument_checks(lib):
     assert call(binding.attn_desc(2, 12, 28, 4, 128, 2080, binding.BF16)) == binding.EUNSUPPORTED  # 84 stacked rows
     assert call(binding.attn_desc(2, 6, 28, 4, 128, 2080, 7)) == binding.EINVAL
     assert call(binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16, scale=-1.0)) == binding.EINVAL
+
+
+def test_negative_window_is_rejected(lib):
+    d = binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16, window=-1)
+    assert lib.massv_verify_attention_workspace(C.byref(d)) == 0
+    assert lib.massv_verify_attention(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == binding.EINVAL
 
 
 def test_layer_and_lm_head_argument_checks(lib):

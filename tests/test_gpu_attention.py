@@ -15,7 +15,7 @@ TOL_BF16 = 2e-2      # max |err| / max |ref|, the bound set for bf16 activations
 TOL_F32 = 2e-5       # fp32 path: fp32 accumulation over <= 300 keys of O(1) values
 
 
-def run_case(shape, B, Q, kv_len, n_img, seed, std=1.0, hot_keys=0, l_max=None, q_std=1.0, nan_tail=False):
+def run_case(shape, B, Q, kv_len, n_img, seed, std=1.0, hot_keys=0, l_max=None, q_std=1.0, nan_tail=False, window=0):
     kv = synth.kv_cache(shape, B, Q, kv_len, n_img, seed, std=std, hot_keys=hot_keys)
     # the step's own rows: new keys / values at [kv_len, kv_len+Q)
     newk = synth.normal((B, shape.n_kv_heads, Q, shape.head_dim), std, seed, 77, dtype=shape.dtype)
@@ -28,11 +28,11 @@ def run_case(shape, B, Q, kv_len, n_img, seed, std=1.0, hot_keys=0, l_max=None, 
             kv.k[b, :, L + Q:] = np.nan
             kv.v[b, :, L + Q:] = np.nan
     q = synth.queries(shape, B, Q, seed, std=q_std)
-    ref = O.attention(q, kv.k, kv.v, kv.kv_len)
+    ref = O.attention(q, kv.k, kv.v, kv.kv_len, window=window)
     lm = round_up(l_max or kv.l_max, 32)
     kd = to_dev(pad_rows(kv.k, lm), shape.dtype)
     vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), shape.dtype))
-    out = binding.verify_attention(to_dev(q, shape.dtype), kd, vd, i32(kv.kv_len))
+    out = binding.verify_attention(to_dev(q, shape.dtype), kd, vd, i32(kv.kv_len), window=window)
     torch.cuda.synchronize()
     return out.float().cpu().numpy(), ref
 
@@ -115,3 +115,48 @@ def test_repeatable_bits_and_pack_roundtrip():
     a = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
     b = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
     assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------
+# sliding-window layers of the Gemma 3 targets (Section 5, "Models")
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("window", [1, 2, 6, 31, 32, 33, 64, 100, 300, 5000])
+def test_window_bf16_d128_ragged(window):
+    """Windows smaller than the query count, at and around block boundaries, larger than the cache;
+    ragged lengths including an empty cache."""
+    got, ref = run_case(synth.QWEN7B, 4, 6, [0, 37, 250, 1000], [0, 10, 64, 300], seed=21, hot_keys=2, nan_tail=True,
+                        window=window)
+    assert_close(got, ref, TOL_BF16, f"window {window}")
+
+
+@pytest.mark.parametrize("window", [5, 48, 200])
+def test_window_fp32_and_d64(window):
+    got, ref = run_case(synth.TINY, 2, 6, [256, 30], [64, 10], seed=22, hot_keys=2, window=window)
+    assert_close(got, ref, TOL_F32, f"fp32 window {window}")
+    s = synth.LayerShape(256, 4, 2, 64, 704, 4096, dtype="bf16")
+    got, ref = run_case(s, 3, 4, [300, 2, 95], [64, 0, 64], seed=23, hot_keys=2, nan_tail=True, window=window)
+    assert_close(got, ref, TOL_BF16, f"bf16 d64 window {window}")
+
+
+def test_window_gemma12b_local_layer_shape():
+    """16 q / 8 kv heads, d=256, KV 4096, window 1024: three quarters of the cache are never read."""
+    got, ref = run_case(synth.GEMMA12B_LOCAL, 2, 6, [4096, 3000], [256, 256], seed=24, hot_keys=2, window=1024)
+    assert_close(got, ref, TOL_BF16, "gemma local")
+
+
+def test_window_rows_outside_are_not_read():
+    """Rows below every query's window hold NaN: the output must not see them."""
+    s, B, Q, W = synth.QWEN7B, 2, 6, 40
+    kv = synth.kv_cache(s, B, Q, [500, 90], [100, 20], seed=25, junk_tail=False)
+    q = synth.queries(s, B, Q, 25)
+    ref = O.attention(q, kv.k, kv.v, kv.kv_len, window=W)
+    k, v = kv.k.copy(), kv.v.copy()
+    for b in range(B):
+        lo = int(kv.kv_len[b]) - W + 1          # the first query's window starts here
+        k[b, :, :lo] = np.nan
+        v[b, :, : lo // 32 * 32] = np.nan       # values are read in blocks of 32 rows and masked by weight 0
+    lm = round_up(kv.l_max, 32)
+    out = binding.verify_attention(to_dev(q, s.dtype), to_dev(pad_rows(k, lm), s.dtype),
+                                   binding.v_cache_pack(to_dev(pad_rows(v, lm), s.dtype)), i32(kv.kv_len), window=W)
+    torch.cuda.synchronize()
+    assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "window with NaN outside")

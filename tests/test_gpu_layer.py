@@ -15,7 +15,7 @@ TOL_F32 = 5e-5      # fp32 path; sums of up to 688 products, fp32 accumulation i
 
 def cfg_of(s):
     return binding.LayerConfig(s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.mlp, s.act, s.qkv_bias,
-                               s.norm_eps, s.rope_theta)
+                               s.norm_eps, s.rope_theta, window=s.window)
 
 
 def run_layer(s, B, Q, kv_len, n_img, seed, kv_std=1.0, compress=True, w_std=0.02):
@@ -188,3 +188,51 @@ def test_embed_tokens_gathers_rows(s):
     ref = O.embed_tokens(table, tokens)
     got = binding.embed_tokens(to_dev(table, s.dtype), i32(tokens))
     assert np.array_equal(got.float().cpu().numpy(), ref)
+
+
+# ---------------------------------------------------------------------------
+# layer variants of the Gemma 3 targets: sliding window, query/key head norms, block-output norms
+# ---------------------------------------------------------------------------
+def test_gemma_style_tiny_layers():
+    run_layer(synth.TINY_GEMMA, 2, 6, [256, 100], [64, 30], seed=31, w_std=0.05)
+    run_layer(synth.TINY_GEMMA_BF16, 3, 4, [140, 0, 95], [8, 0, 64], seed=32, w_std=0.05)
+
+
+def test_gemma12b_local_layer():
+    """One Gemma3-12B-shaped sliding-window layer: d=256 heads with query/key norms, window 1024 over KV 4096,
+    block-output norms, tanh-GELU MLP."""
+    run_layer(synth.GEMMA12B_LOCAL, 4, 6, [4096, 3000, 1024, 500], [256, 256, 256, 100], seed=33)
+
+
+def test_each_gemma_variant_alone():
+    """Each optional step switched on by itself (a step wired to the wrong switch fails here)."""
+    import dataclasses
+    base = synth.TINY_BF16
+    for kw in (dict(window=20), dict(qk_norm=True), dict(post_norms=True)):
+        run_layer(dataclasses.replace(base, **kw), 2, 6, [100, 37], [30, 5], seed=34, w_std=0.05)
+
+
+def test_layer_stack_interleaves_local_and_global_layers():
+    """Four layers in one call, windows (24, 24, 0, 24) and rotary bases (1e4, 1e4, 1e6, 1e4) given per layer."""
+    import dataclasses
+    for base in (synth.TINY_GEMMA, synth.TINY_GEMMA_BF16):
+        windows, thetas = [24, 24, 0, 24], [1e4, 1e4, 1e6, 1e4]
+        shapes = [dataclasses.replace(base, window=w, rope_theta=t) for w, t in zip(windows, thetas)]
+        B, Q, seed = 2, 6, 35
+        ws_h = [synth.layer_weights(s, seed, layer=l, std=0.05) for l, s in enumerate(shapes)]
+        kvs = [synth.kv_cache(base, B, Q, [200, 61], [64, 30], seed, layer=l, hot_keys=1) for l in range(4)]
+        x = synth.hidden_states(base, B, Q, seed)
+        pos = synth.positions(kvs[0].kv_len, kvs[0].n_img, Q, compress_image=True)
+        y_ref = x
+        for l in range(4):
+            y_ref, _, _ = O.verify_layer(shapes[l], ws_h[l], y_ref, pos, kvs[l].k, kvs[l].v, kvs[l].kv_len)
+        lm = round_up(kvs[0].l_max, 32)
+        kds = [to_dev(pad_rows(kv.k, lm), base.dtype) for kv in kvs]
+        vds = [binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), base.dtype)) for kv in kvs]
+        wds = [binding.pack_layer_weights({k: (None if v is None else to_dev(v, base.dtype)) for k, v in w.items()}) for w in ws_h]
+        stack = binding.LayerStack(wds, kds, vds, windows=windows, rope_thetas=thetas)
+        xd = to_dev(x, base.dtype)
+        binding.verify_layers(cfg_of(base), stack, xd, i32(pos), i32(kvs[0].kv_len), lm)
+        torch.cuda.synchronize()
+        tol = TOL_BF16 if base.dtype == "bf16" else TOL_F32 * 4
+        assert_close(xd.float().cpu().numpy(), y_ref, tol, "interleaved stack output")
