@@ -429,6 +429,24 @@ def extra_bandwidth(torch, binding, synth, dev, gen):
     acc_bytes = B * Q * V * 4 + B * gamma * V * 4 + B * 2 * V * 4
     acc0_bytes = B * Q * V * 4
     gb = lambda nbytes, ms: round(nbytes / (ms * 1e-3) / 1e9, 1)
+    del tls, dls
+
+    # compute-bound counterpart: a prefill-sized projection (4096 rows through the 3584 -> 18944 gate projection)
+    Ml, Nl, Kl = 4096, s.mlp, s.hidden
+    xl = torch.randn(Ml, Kl, generator=gen, device=dev).to(bf)
+    wl = binding.weight_pack((torch.randn(Nl, Kl, generator=gen, device=dev) * 0.02).to(bf))
+    yl = torch.empty((Ml, Nl), dtype=bf, device=dev)
+    lin_ms = time_calls(torch, lambda: binding.linear(xl, wl, out=yl), 20)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for a, b in evs:
+        a.record(); b.record()
+    torch.cuda.synchronize()
+    for a, b in evs:
+        binding.trace_kernel(binding.K_LINEAR, a, b)
+        binding.linear(xl, wl, out=yl)
+    torch.cuda.synchronize()
+    tile_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    lin_flops = 2.0 * Ml * Nl * Kl
     return {
         "workload": "long-context batched: B=32, gamma=7, KV 8192 bf16, 28/4 heads, d=128, V=152064",
         "verify_attention": {"us": round(attn_ms * 1e3, 1), "GBps": gb(attn_bytes, attn_ms),
@@ -437,6 +455,10 @@ def extra_bandwidth(torch, binding, synth, dev, gen):
                              "frac_of_8TBps": round(gb(acc_bytes, acc_ms) / HBM_PEAK_GBS, 4), "bytes": acc_bytes},
         "spec_accept_T0": {"us": round(acc0_ms * 1e3, 1), "GBps": gb(acc0_bytes, acc0_ms),
                            "frac_of_8TBps": round(gb(acc0_bytes, acc0_ms) / HBM_PEAK_GBS, 4), "bytes": acc0_bytes},
+        "linear_prefill": {"shape": "M=4096, K=3584, N=18944 bf16", "bound": "mfma", "flops": lin_flops,
+                           "call_us": round(lin_ms * 1e3, 1), "tile_kernel_us": round(tile_ms * 1e3, 1),
+                           "TFLOPs": round(lin_flops / (tile_ms * 1e-3) / 1e12, 1), "peak_TFLOPs": 2500.0,
+                           "frac_of_bf16_peak": round(lin_flops / (tile_ms * 1e-3) / 2.5e15, 4)},
     }
 
 

@@ -258,6 +258,20 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- */
+/* commit_tokens: bookkeeping after spec_accept, on the device so that the     */
+/* decoding loop of Section 2.1 needs no host round trip: sequence b keeps its */
+/* n_b accepted drafts and the final token, so                                 */
+/*   last_token[b] = out_tokens[b][n_accepted[b]]   (input of the next step)   */
+/*   kv_len[b]    += n_accepted[b] + 1              (cache rows now valid)     */
+/* Rows written for rejected drafts stay in the caches beyond the new kv_len   */
+/* and are overwritten by the next step: nothing is moved.                     */
+/* n_accepted [B], out_tokens [B][gamma+1] int32 in; kv_len [B] int32 in/out;  */
+/* last_token [B] int32 out (may be NULL); all device pointers.                */
+/* ------------------------------------------------------------------------- */
+int massv_commit_tokens(const int32_t* n_accepted, const int32_t* out_tokens, int32_t* kv_len,
+                        int32_t* last_token, int32_t B, int32_t gamma, void* stream);
+
+/* ------------------------------------------------------------------------- */
 /* spec_tvd: total variation distance of Section 6 between the target and the */
 /* draft distribution of every row, TVD = 1/2 sum_x |p(x) - q(x)| with         */
 /* p = softmax(target_logits[r]/T), q = softmax(draft_logits[r]/T); 1 - TVD is */
@@ -283,6 +297,26 @@ int massv_embed_tokens(const void* table, const int32_t* tokens, void* x,
                        int32_t M, int32_t H, int32_t V, int32_t dtype, void* stream);
 
 /* ------------------------------------------------------------------------- */
+/* linear: Y = act(X W^T + bias) for prefill-sized inputs, the compute-bound   */
+/* counterpart of the verify projections.  Section 3.1: the drafter's          */
+/* multimodal projector g_psi maps each of the m vision features (dimension    */
+/* d_vis) to the language model's embedding dimension; it has the target       */
+/* projector's architecture, a small MLP, i.e. a few calls of this entry point */
+/* over M = (images x m) rows.  The same call serves the projections of an     */
+/* image-token prefill.                                                        */
+/* ------------------------------------------------------------------------- */
+typedef enum { MASSV_LIN_NONE = 0, MASSV_LIN_SILU = 1, MASSV_LIN_GELU_TANH = 2, MASSV_LIN_GELU_ERF = 3 } massv_linear_act;
+
+size_t massv_linear_workspace(int32_t M, int32_t N, int32_t K, int32_t dtype);
+
+/* x [M][K] row-major (dtype) in; w [N][K] (dtype) in the streaming layout of massv_weight_pack;
+ * bias [N] (dtype) or NULL; y [M][N] row-major (dtype) out; all device pointers.  fp32 accumulation, one
+ * rounding to dtype after the activation.  bf16 only; K % 64 == 0 and N % 16 == 0, any M >= 1, else
+ * MASSV_EUNSUPPORTED.  The workspace receives X in operand order. */
+int massv_linear(const void* x, const void* w, const void* bias, void* y, int32_t M, int32_t N, int32_t K,
+                 int32_t act, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
 /* Timing hook (diagnostic; for callers that want one kernel's duration        */
 /* without a profiler).  Arms a one-shot request on the CALLING THREAD: the    */
 /* next launch of kernel `kernel_id` made by a library call from this thread   */
@@ -302,7 +336,8 @@ typedef enum {
     MASSV_K_DOWN = 5,         /* down projection + residual */
     MASSV_K_LMHEAD = 6,       /* vocabulary projection of lm_head_logits */
     MASSV_K_ACCEPT_STATS = 7, /* pass 1 of spec_accept over all logit rows */
-    MASSV_K_RESIDUAL_MASS = 8 /* pass 2 of spec_accept over the resampled rows */
+    MASSV_K_RESIDUAL_MASS = 8,/* pass 2 of spec_accept over the resampled rows */
+    MASSV_K_LINEAR = 9        /* the tile kernel of massv_linear */
 } massv_kernel_id;
 
 int massv_trace_kernel(int kernel_id, void* start_event, void* stop_event);

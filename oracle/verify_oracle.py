@@ -131,6 +131,18 @@ def gelu_tanh(x):
     return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
 
 
+def gelu_erf(x):
+    x = np.asarray(x, dtype=np.float64)
+    return 0.5 * x * (1.0 + np.vectorize(math.erf)(x / math.sqrt(2.0)))
+
+
+def projector_mlp(h, w1, b1, w2, b2, dtype="bf16"):
+    """Multimodal projector of Section 3.1 in its usual two-layer form: vision features [m, d_vis] ->
+    Linear, GELU, Linear -> [m, d_emb].  The hidden activation is stored in `dtype` between the two maps."""
+    mid = _store(gelu_erf(linear(h, w1, b1)), dtype)
+    return linear(mid, w2, b2)
+
+
 def gated_mlp(x, wg, wu, wd, act):
     a = silu if act == ACT_SILU else gelu_tanh
     return linear(a(linear(x, wg)) * linear(x, wu), wd)
@@ -265,6 +277,15 @@ def embed_tokens(table, tokens):
         if 0 <= tok < table.shape[0]:
             out[m] = table[tok]
     return out
+
+
+def commit_tokens(n_accepted, out_tokens, kv_len):
+    """Bookkeeping between two iterations of Section 2.1's loop: sequence b keeps n_b drafts and the final
+    token.  Returns (last_token, new kv_len)."""
+    n = np.asarray(n_accepted)
+    out = np.asarray(out_tokens)
+    last = np.array([out[b, n[b]] for b in range(len(n))], dtype=np.int32)
+    return last, (np.asarray(kv_len) + n + 1).astype(np.int32)
 
 
 def residual(p, q):

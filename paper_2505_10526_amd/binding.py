@@ -28,9 +28,11 @@ EXPORTS = [
     "massv_verify_layer_workspace", "massv_verify_layer", "massv_verify_layers",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
     "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
-    "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens",
+    "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
+    "massv_linear_workspace", "massv_linear",
 ]
-K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS = range(9)
+K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR = range(10)
+LIN_NONE, LIN_SILU, LIN_GELU_TANH, LIN_GELU_ERF = range(4)
 
 
 class AttnDesc(C.Structure):
@@ -105,6 +107,12 @@ def load():
     lib.massv_spec_tvd_workspace.argtypes = [i32, i32]
     lib.massv_spec_tvd.restype = C.c_int
     lib.massv_spec_tvd.argtypes = [vp, vp, f32, i32, i32, vp, vp, sz, vp]
+    lib.massv_linear_workspace.restype = sz
+    lib.massv_linear_workspace.argtypes = [i32, i32, i32, i32]
+    lib.massv_linear.restype = C.c_int
+    lib.massv_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.massv_commit_tokens.restype = C.c_int
+    lib.massv_commit_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.massv_embed_tokens.restype = C.c_int
     lib.massv_embed_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     _lib = lib
@@ -383,6 +391,40 @@ def spec_tvd(target_logits, draft_logits, temperature, tvd=None, ws=None):
     _check(lib.massv_spec_tvd(_ptr(target_logits), _ptr(draft_logits), float(temperature), rows, V,
                               _ptr(tvd), _ptr(ws), ws.numel(), _stream()), "massv_spec_tvd")
     return tvd
+
+
+def linear(x, w_packed, bias=None, act=LIN_NONE, out=None, ws=None):
+    """x [M,K] row-major; w_packed [N,K] in streaming layout (weight_pack); bias [N] or None -> y [M,N]."""
+    lib = load()
+    _need(x, "x")
+    _need(w_packed, "w", x.dtype)
+    if bias is not None:
+        _need(bias, "bias", x.dtype)
+    M, K = x.shape
+    N = w_packed.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    else:
+        _need(out, "out", x.dtype)
+    if ws is None:
+        ws = workspace(lib.massv_linear_workspace(M, N, K, dtype_code(x)), x.device)
+    _check(lib.massv_linear(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(out), M, N, K, int(act), dtype_code(x),
+                            _ptr(ws), ws.numel(), _stream()), "massv_linear")
+    return out
+
+
+def commit_tokens(n_accepted, out_tokens, kv_len, last_token=None):
+    """kv_len [B] += n_accepted + 1 (in place); returns last_token [B] = out_tokens[b, n_accepted[b]]."""
+    for t, n in ((n_accepted, "n_accepted"), (out_tokens, "out_tokens"), (kv_len, "kv_len")):
+        _need(t, n, torch.int32)
+    B, Q = out_tokens.shape
+    if last_token is None:
+        last_token = torch.empty((B,), dtype=torch.int32, device=kv_len.device)
+    else:
+        _need(last_token, "last_token", torch.int32)
+    _check(load().massv_commit_tokens(_ptr(n_accepted), _ptr(out_tokens), _ptr(kv_len), _ptr(last_token), B, Q - 1,
+                                      _stream()), "massv_commit_tokens")
+    return last_token
 
 
 def embed_tokens(table, tokens, x=None):

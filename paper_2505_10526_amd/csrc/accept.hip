@@ -470,6 +470,26 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     return launch_status();
 }
 
+namespace massv {
+__global__ void commit_tokens_kernel(const int* __restrict__ n_accepted, const int* __restrict__ out_tokens,
+                                     int* __restrict__ kv_len, int* __restrict__ last_token, int B, int gamma) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int n = n_accepted[b];
+    n = n < 0 ? 0 : (n > gamma ? gamma : n);
+    if (last_token) last_token[b] = out_tokens[b * (gamma + 1) + n];
+    kv_len[b] += n + 1;
+}
+}  // namespace massv
+
+extern "C" int massv_commit_tokens(const int32_t* n_accepted, const int32_t* out_tokens, int32_t* kv_len,
+                                   int32_t* last_token, int32_t B, int32_t gamma, void* stream) {
+    if (!n_accepted || !out_tokens || !kv_len || B < 1 || gamma < 0) return MASSV_EINVAL;
+    hipLaunchKernelGGL(commit_tokens_kernel, dim3((B + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                       n_accepted, out_tokens, kv_len, last_token, B, gamma);
+    return launch_status();
+}
+
 extern "C" size_t massv_spec_tvd_workspace(int32_t rows, int32_t V) {
     if (rows < 1 || rows > 32767 || V < 1) return 0;
     return tvd_layout(rows, V).total;

@@ -24,7 +24,7 @@ TraceRequest& trace_request() {
 extern "C" int massv_trace_kernel(int kernel_id, void* start_event, void* stop_event) {
     massv::TraceRequest& t = massv::trace_request();
     if (kernel_id < 0) { t.kid = -1; return MASSV_OK; }
-    if (kernel_id > MASSV_K_RESIDUAL_MASS || !start_event || !stop_event) return MASSV_EINVAL;
+    if (kernel_id > MASSV_K_LINEAR || !start_event || !stop_event) return MASSV_EINVAL;
     t.kid = kernel_id; t.start = (hipEvent_t)start_event; t.stop = (hipEvent_t)stop_event;
     return MASSV_OK;
 }

@@ -141,6 +141,26 @@ def test_layer_and_lm_head_argument_checks(lib):
     assert g(FAKE, FAKE, FAKE, FAKE, 0, 3584, 152064, 1e-6, binding.BF16, FAKE, need, None) == binding.EINVAL
 
 
+def test_linear_argument_checks(lib):
+    f = lib.massv_linear
+    ws = lib.massv_linear_workspace(300, 272, 128, binding.BF16)
+    assert ws >= 304 * 128 * 2
+    assert lib.massv_linear_workspace(300, 272, 100, binding.BF16) == 0
+    ok = lambda **kw: [kw.get("x", FAKE), kw.get("w", FAKE), kw.get("b", None), kw.get("y", FAKE), kw.get("M", 300),
+                       kw.get("N", 272), kw.get("K", 128), kw.get("act", 0), kw.get("dt", binding.BF16), kw.get("ws", FAKE),
+                       kw.get("wsb", ws), None]
+    assert f(*ok(x=None)) == binding.EINVAL
+    assert f(*ok(w=None)) == binding.EINVAL
+    assert f(*ok(y=None)) == binding.EINVAL
+    assert f(*ok(M=0)) == binding.EINVAL
+    assert f(*ok(act=9)) == binding.EINVAL
+    assert f(*ok(K=96)) == binding.EUNSUPPORTED          # k-steps of 64
+    assert f(*ok(N=270)) == binding.EUNSUPPORTED
+    assert f(*ok(dt=binding.F32)) == binding.EUNSUPPORTED
+    assert f(*ok(wsb=ws - 1)) == binding.EWORKSPACE
+    assert f(*ok(ws=None)) == binding.EWORKSPACE
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))

@@ -179,3 +179,14 @@ def test_tvd_identical_and_disjoint_rows():
     got = binding.spec_tvd(torch.from_numpy(t).cuda(), torch.from_numpy(d).cuda(), 1.0).cpu().numpy()
     assert np.all(got[:2] == 0.0)
     assert np.all(np.abs(got[2:] - 1.0) < 1e-6)                  # float exponentials: sum p is 1 to ~1e-7
+
+
+def test_commit_tokens():
+    a = synth.accept_inputs(40, 5, 4096, 0.0, seed=51, noise_std=1.0, peak=6.0)
+    n, out, _ = O.spec_accept(a.target_logits, None, a.draft_tokens, None, 0.0)
+    kv = np.arange(40, dtype=np.int32) * 7
+    last_ref, kv_ref = O.commit_tokens(n, out, kv)
+    kv_d = torch.from_numpy(kv).cuda()
+    last = binding.commit_tokens(torch.from_numpy(n).cuda(), torch.from_numpy(out).cuda(), kv_d)
+    assert np.array_equal(last.cpu().numpy(), last_ref) and np.array_equal(kv_d.cpu().numpy(), kv_ref)
+    assert len(set(n.tolist())) > 2

@@ -333,3 +333,10 @@ def test_embed_tokens_gathers_rows():
     out = O.embed_tokens(table, [3, 0, 4, 7, -1])
     assert np.array_equal(out[0], table[3]) and np.array_equal(out[1], table[0]) and np.array_equal(out[2], table[4])
     assert not out[3].any() and not out[4].any()
+
+
+def test_commit_tokens_worked_example():
+    """gamma = 3: a sequence that kept 2 drafts emits 3 tokens and its next input is the third."""
+    out = np.array([[11, 12, 99, -1], [7, -1, -1, -1], [1, 2, 3, 4]])
+    last, kv = O.commit_tokens([2, 0, 3], out, [100, 50, 0])
+    assert last.tolist() == [99, 7, 4] and kv.tolist() == [103, 51, 4]

@@ -412,3 +412,18 @@ def test_query_key_norm_removes_projection_scale():
     y3, _, _ = O.verify_layer(s, w3, x, pos, kv.k, kv.v, kv.kv_len)
     y4, _, _ = O.verify_layer(s, w4, x, pos, kv.k, kv.v, kv.kv_len)
     assert np.max(np.abs(y3 - y4)) > 1e-3
+
+
+def test_gelu_erf_and_projector_against_torch():
+    """Exact GELU against the library routine; the two-layer projector (Section 3.1) rebuilt from torch float64
+    matmuls, with the hidden activation stored in bf16 in between."""
+    x = np.linspace(-6, 6, 101)
+    np.testing.assert_allclose(O.gelu_erf(x), torch.nn.functional.gelu(torch.from_numpy(x)).numpy(), rtol=1e-12, atol=1e-15)
+    rng = np.random.default_rng(5)
+    h = synth.bf16_representable(rng.standard_normal((7, 12)).astype(np.float32))
+    w1 = synth.bf16_representable((rng.standard_normal((20, 12)) * 0.3).astype(np.float32)); b1 = synth.bf16_representable(rng.standard_normal(20).astype(np.float32))
+    w2 = synth.bf16_representable((rng.standard_normal((5, 20)) * 0.3).astype(np.float32)); b2 = synth.bf16_representable(rng.standard_normal(5).astype(np.float32))
+    T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    mid = torch.nn.functional.gelu(T(h) @ T(w1).T + T(b1)).to(torch.bfloat16).double()
+    want = (mid @ T(w2).T + T(b2)).numpy()
+    np.testing.assert_allclose(O.projector_mlp(h, w1, b1, w2, b2, "bf16"), want, rtol=1e-12, atol=1e-12)
