@@ -25,13 +25,12 @@ constexpr int kLinTile = 256;            // rows / features per workgroup
 constexpr int kLinGroupM = 8;            // row tiles per scheduling group
 constexpr size_t kLinLds = 2 * 2 * 2 * 16 * 64 * sizeof(bf16x8);      // [buf][k32 sub-step][W|X][tile16 * 64 + lane] = 128 KB
 
-__device__ inline float linear_act(float v, int act) {
-    switch (act) {
-        case MASSV_LIN_SILU: return v / (1.0f + expf(-v));
-        case MASSV_LIN_GELU_TANH: return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
-        case MASSV_LIN_GELU_ERF: return 0.5f * v * (1.0f + erff(v * 0.7071067811865476f));
-        default: return v;
-    }
+template <int ACT>
+__device__ inline float linear_act(float v) {
+    if constexpr (ACT == MASSV_LIN_SILU) return v / (1.0f + expf(-v));
+    else if constexpr (ACT == MASSV_LIN_GELU_TANH) return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+    else if constexpr (ACT == MASSV_LIN_GELU_ERF) return 0.5f * v * (1.0f + erff(v * 0.7071067811865476f));
+    else return v;
 }
 
 // Row-major X[M][K] -> operand order [ceil(M/16)][K/32][64][8]; rows beyond M are zero.  One thread per 16-byte chunk.
@@ -49,9 +48,10 @@ __global__ void linear_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __res
     *reinterpret_cast<bf16x8*>(dst + o * 8) = v;
 }
 
+template <int ACT>
 __global__ __launch_bounds__(256)
 void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict__ wpk, const bf16_t* __restrict__ bias,
-                        bf16_t* __restrict__ y, int M, int N, int K, int tiles_m, int tiles_n, int act) {
+                        bf16_t* __restrict__ y, int M, int N, int K, int tiles_m, int tiles_n) {
     extern __shared__ bf16x8 lds_raw[];
     bf16x8 (*lds)[2][2][16 * 64] = reinterpret_cast<bf16x8 (*)[2][2][16 * 64]>(lds_raw);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -186,7 +186,7 @@ void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict
                 }
                 bf16x4 o;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (bf16_t)linear_act(v[r], act);
+                for (int r = 0; r < 4; ++r) o[r] = (bf16_t)linear_act<ACT>(v[r]);
                 *reinterpret_cast<bf16x4*>(y + (size_t)m * N + n) = o;
             }
     }
@@ -222,8 +222,10 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
     if (!lds_ready[dev]) {
-        if (hipFuncSetAttribute((const void*)linear_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLds) != hipSuccess)
-            return MASSV_ELAUNCH;
+        const void* kernels[4] = {(const void*)linear_tile_kernel<MASSV_LIN_NONE>, (const void*)linear_tile_kernel<MASSV_LIN_SILU>,
+                                  (const void*)linear_tile_kernel<MASSV_LIN_GELU_TANH>, (const void*)linear_tile_kernel<MASSV_LIN_GELU_ERF>};
+        for (const void* k : kernels)
+            if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLds) != hipSuccess) return MASSV_ELAUNCH;
         lds_ready[dev] = true;
     }
     hipStream_t st = (hipStream_t)stream;
@@ -231,7 +233,24 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     hipLaunchKernelGGL(linear_pack_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const bf16_t*)x,
                        (bf16_t*)workspace, chunks, M, K);
     const int tiles_m = (M + kLinTile - 1) / kLinTile, tiles_n = (N + kLinTile - 1) / kLinTile;
-    launch_traced(MASSV_K_LINEAR, linear_tile_kernel, dim3(tiles_m * tiles_n), dim3(256), kLinLds, st,
-                  (const bf16_t*)workspace, (const bf16_t*)w, (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n, act);
+    const dim3 grid(tiles_m * tiles_n), block(256);
+    const bf16_t* xp = (const bf16_t*)workspace;
+    switch (act) {
+        case MASSV_LIN_SILU:
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_SILU>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+            break;
+        case MASSV_LIN_GELU_TANH:
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_TANH>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+            break;
+        case MASSV_LIN_GELU_ERF:
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_ERF>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+            break;
+        default:
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_NONE>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+    }
     return launch_status();
 }
