@@ -143,3 +143,95 @@ def test_greedy_iteration_matches_checker(kind, seed):
     assert np.array_equal(out_g, out_o)
     if kind == "self":
         assert np.all(n_o == gamma)
+
+
+# ---------------------------------------------------------------------------
+# several iterations in a row with the bookkeeping on the device (massv_commit_tokens)
+# ---------------------------------------------------------------------------
+def oracle_generation(draft, target, last_tokens, gamma, iterations):
+    """Greedy decoding loop of Section 2.1.  Per iteration: gamma drafter steps, one more drafter forward on the
+    last draft (so that the drafter's cache covers every token that can be kept), the target's verify pass, the
+    accept rule, then kv_len += n + 1 and the final token becomes the next input."""
+    B = len(last_tokens)
+    kd = [kv.k.copy() for kv in draft.kv]; vd = [kv.v.copy() for kv in draft.kv]
+    kt = [kv.k.copy() for kv in target.kv]; vt = [kv.v.copy() for kv in target.kv]
+    kv_len = target.kv_len.copy()
+    last = np.asarray(last_tokens, dtype=np.int32)
+    emitted, clear = [[] for _ in range(B)], True
+    for _ in range(iterations):
+        tok, drafts = last.copy(), np.zeros((B, gamma), dtype=np.int32)
+        for i in range(gamma + 1):
+            pos = synth.positions(kv_len + i, draft.n_img, 1, compress_image=True)
+            logits = oracle_forward(draft, kd, vd, tok[:, None], kv_len + i, pos)
+            if i == gamma:
+                break                                   # the extra forward only appends the last draft's cache row
+            clear &= clear_decisions(logits)
+            _, out, _ = O.spec_accept(logits, None, np.zeros((B, 0), np.int32), None, 0.0)
+            tok = out[:, 0].astype(np.int32)
+            drafts[:, i] = tok
+        seq = np.concatenate([last[:, None], drafts], axis=1)
+        pos = synth.positions(kv_len, target.n_img, gamma + 1, compress_image=True)
+        logits = oracle_forward(target, kt, vt, seq, kv_len, pos)
+        clear &= clear_decisions(logits)
+        n, out, _ = O.spec_accept(logits, None, drafts, None, 0.0)
+        for b in range(B):
+            emitted[b].extend(out[b, : n[b] + 1].tolist())
+        last, kv_len = O.commit_tokens(n, out, kv_len)
+    return emitted, kv_len, clear
+
+
+def gpu_generation(draft, target, last_tokens, gamma, iterations):
+    B = len(last_tokens)
+    d, t = DeviceModel(draft), DeviceModel(target)
+    kv_len = i32(target.kv_len)
+    img_half = i32(target.n_img // 2)                   # rotary ids count the image prefix as half its length
+    last = i32(last_tokens)
+    steps = torch.arange(gamma + 1, dtype=torch.int32, device=last.device)
+    records = []
+    for _ in range(iterations):
+        tok = last.clone()
+        drafts = torch.empty((B, gamma), dtype=torch.int32, device=last.device)
+        for i in range(gamma + 1):
+            kv_i = (kv_len + i).contiguous()
+            pos_i = (kv_i - img_half).reshape(B, 1).contiguous()
+            logits = d.forward(tok.reshape(B, 1), kv_i, pos_i)
+            if i == gamma:
+                break
+            _, out = binding.spec_accept(logits, None, None, None, 0.0)
+            tok = out.reshape(B).clone()
+            drafts[:, i] = tok
+        seq = torch.cat([last.reshape(B, 1), drafts], dim=1).contiguous()
+        pos = ((kv_len - img_half).reshape(B, 1) + steps.reshape(1, -1)).contiguous()
+        logits = t.forward(seq, kv_len, pos)
+        n, out = binding.spec_accept(logits, None, drafts.contiguous(), None, 0.0)
+        records.append((n.clone(), out.clone()))
+        last = binding.commit_tokens(n, out, kv_len)    # kv_len advances in place, no host round trip
+    torch.cuda.synchronize()
+    emitted = [[] for _ in range(B)]
+    for n, out in records:
+        n, out = n.cpu().numpy(), out.cpu().numpy()
+        for b in range(B):
+            emitted[b].extend(out[b, : n[b] + 1].tolist())
+    return emitted, kv_len.cpu().numpy()
+
+
+def build_generation_case(seed, iterations=3, gamma=3, B=2):
+    kv_len, n_img = [70, 33][:B], [40, 16][:B]
+    room = iterations * (gamma + 1) + 1
+    target = HostModel(synth.TINY_BF16, 2, B, kv_len, n_img, room, seed)
+    draft = HostModel(synth.TINY_BF16, 2, B, kv_len, n_img, room, seed)
+    noise = synth.normal(draft.head["w_lm"].shape, 0.015, seed, 77, dtype="bf16")
+    draft.head = dict(draft.head, w_lm=synth.bf16_representable(draft.head["w_lm"] + noise))
+    last = np.random.default_rng(seed).integers(0, target.s.vocab, B).astype(np.int32)
+    return draft, target, last, gamma, iterations
+
+
+@pytest.mark.parametrize("seed", [4, 34])
+def test_greedy_generation_over_three_iterations(seed):
+    draft, target, last, gamma, iterations = build_generation_case(seed)
+    em_o, kv_o, clear = oracle_generation(draft, target, last, gamma, iterations)
+    assert clear, "pick another seed: an arg-max of the checker's chain is too close to call"
+    em_g, kv_g = gpu_generation(draft, target, last, gamma, iterations)
+    assert em_g == em_o
+    assert np.array_equal(kv_g, kv_o)
+    assert any(len(e) > iterations for e in em_o)       # some drafts were accepted along the way
