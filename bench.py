@@ -70,16 +70,16 @@ def parse():
 
 
 WORKLOADS = {
-    # BASELINE config 3: full 28-layer Qwen2.5-VL-7B-shaped verify step
+    # full 28-layer Qwen2.5-VL-7B-shaped verify step (the headline workload)
     "qwen7b_full": dict(shape="QWEN7B", layers=28, batch=8, gamma=5, kv_lo=1024, kv_hi=2048,
                         img_lo=256, img_hi=1024, noise=1.5, temperature=0.0,
                         label="Qwen2.5-VL-7B-shaped full verify step: 28 layers + lm_head + accept, "
                               "B=8, gamma=5, kv_len U[1024,2048], 256-1024 image rows, T=0"),
-    # BASELINE config 2: one layer + lm_head + accept, B=1
+    # one layer + lm_head + accept at batch 1
     "qwen7b_layer": dict(shape="QWEN7B", layers=1, batch=1, gamma=5, kv_lo=1024, kv_hi=1024,
                          img_lo=700, img_hi=700, noise=1.5, temperature=0.0,
                          label="one Qwen2.5-VL-7B-shaped layer + lm_head + accept, B=1, gamma=5, KV 1024, T=0"),
-    # BASELINE config 4
+    # Gemma3-12B-shaped layer
     "gemma12b_layer": dict(shape="GEMMA12B", layers=1, batch=4, gamma=5, kv_lo=4096, kv_hi=4096,
                            img_lo=256, img_hi=256, noise=2.0, temperature=0.0,
                            label="one Gemma3-12B-shaped layer + lm_head + accept, B=4, gamma=5, KV 4096, T=0"),
