@@ -160,6 +160,7 @@ def main():
     desc = binding.layer_desc(cfg, B, Q, l_max, binding.BF16)
     ws_bytes = max(binding.verify_layer_workspace(desc),
                    binding.load().massv_lm_head_logits_workspace(M, H, V, binding.BF16),
+                   binding.load().massv_lm_head_greedy_accept_workspace(B, gamma, H, V, binding.BF16),
                    binding.load().massv_spec_accept_workspace(B, gamma, V))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     T = wl["temperature"]
@@ -210,6 +211,26 @@ def main():
     tokens_per_s = emitted / (ms_per_step * 1e-3)
     k_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
+    # the same step with the vocabulary projection and the T = 0 accept rule fused (no logits written)
+    fused_ms = None
+    if T == 0:
+        n_f, out_f = torch.empty_like(n_acc), torch.empty_like(out_tok)
+        def fused_step():
+            x.copy_(x0)
+            binding.verify_layers(cfg, stack, x, pos, kv_len, l_max, ws=ws, desc=desc)
+            binding.lm_head_greedy_accept(x, final_norm, w_lm, draft_tokens, shape.norm_eps, n_accepted=n_f, out_tokens=out_f, ws=ws)
+        for _ in range(args.warmup):
+            fused_step()
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for _ in range(args.steps):
+            fused_step()
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - tf0) * 1e3 / args.steps
+        if not (torch.equal(n_f, n_acc) and torch.equal(out_f, out_tok)):
+            print("bench.py: fused greedy step disagrees with the separate calls", file=sys.stderr)
+            sys.exit(1)
+
     # ---------------- roofline of the dominant kernel: gate/up projection ----------------
     gateup_bytes = 2 * F * H * 2 + M * H * 2 + M * F * 2          # Wg, Wu (bf16) + X read + H written
     weight_bytes_step = N * (nq * H + 2 * nkv * H + H * nq + 3 * F * H) * 2 + V * H * 2
@@ -245,6 +266,7 @@ def main():
                    "draft_noise_std": wl["noise"], "launch": "eager, one stream"},
         "positions_per_s": round(M / (ms_per_step * 1e-3), 1),
         "mean_emitted_per_sequence": round(emitted / B, 3),
+        "fused_greedy_ms_per_step": None if fused_ms is None else round(fused_ms, 4),
         "peaked_variant": {"what": "target logits x 8, same draft noise (synthetic)", "mean_emitted_per_sequence": round(emitted8 / B, 3),
                            "tokens_per_s": round(emitted8 / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,

@@ -258,6 +258,22 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- */
+/* lm_head_greedy_accept: massv_lm_head_logits followed by massv_spec_accept   */
+/* at temperature 0 (Section 2.1: a draft is kept iff it is the arg-max of the */
+/* target's distribution at its position), without writing the logits: the     */
+/* projection keeps per row only the largest logit and its lowest column.      */
+/* Results are identical to the two calls.                                     */
+/* x [B][gamma+1][H] (dtype); final_norm [H] or NULL; w_lm [V][H] in streaming */
+/* layout; draft_tokens [B][gamma] int32 (NULL iff gamma == 0); n_accepted [B],*/
+/* out_tokens [B][gamma+1] int32 out.  bf16 only, limits as for the two calls. */
+/* ------------------------------------------------------------------------- */
+size_t massv_lm_head_greedy_accept_workspace(int32_t B, int32_t gamma, int32_t H, int32_t V, int32_t dtype);
+int massv_lm_head_greedy_accept(const void* x, const void* final_norm, const void* w_lm,
+                                const int32_t* draft_tokens, int32_t B, int32_t gamma, int32_t H, int32_t V,
+                                float norm_eps, int32_t dtype, int32_t* n_accepted, int32_t* out_tokens,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
 /* commit_tokens: bookkeeping after spec_accept, on the device so that the     */
 /* decoding loop of Section 2.1 needs no host round trip: sequence b keeps its */
 /* n_b accepted drafts and the final token, so                                 */

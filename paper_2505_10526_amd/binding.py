@@ -30,6 +30,7 @@ EXPORTS = [
     "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
     "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
     "massv_linear_workspace", "massv_linear",
+    "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR = range(10)
 LIN_NONE, LIN_SILU, LIN_GELU_TANH, LIN_GELU_ERF = range(4)
@@ -111,6 +112,10 @@ def load():
     lib.massv_linear_workspace.argtypes = [i32, i32, i32, i32]
     lib.massv_linear.restype = C.c_int
     lib.massv_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.massv_lm_head_greedy_accept_workspace.restype = sz
+    lib.massv_lm_head_greedy_accept_workspace.argtypes = [i32, i32, i32, i32, i32]
+    lib.massv_lm_head_greedy_accept.restype = C.c_int
+    lib.massv_lm_head_greedy_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, vp, vp, sz, vp]
     lib.massv_commit_tokens.restype = C.c_int
     lib.massv_commit_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.massv_embed_tokens.restype = C.c_int
@@ -370,6 +375,29 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
     _check(lib.massv_spec_accept(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(uniforms),
                                  float(temperature), B, gamma, V, _ptr(n_accepted), _ptr(out_tokens),
                                  _ptr(ws), ws.numel(), _stream()), "massv_spec_accept")
+    return n_accepted, out_tokens
+
+
+def lm_head_greedy_accept(x, final_norm, w_lm, draft_tokens, norm_eps=1e-6, n_accepted=None, out_tokens=None, ws=None):
+    """x [B,Q,H]; w_lm [V,H] in streaming layout; draft_tokens [B,Q-1] i32 (None when Q == 1).
+    Temperature-0 verification without materialising the logits.  Returns (n_accepted, out_tokens)."""
+    lib = load()
+    _need(x, "x")
+    _need(w_lm, "w_lm", x.dtype)
+    if draft_tokens is not None:
+        _need(draft_tokens, "draft_tokens", torch.int32)
+    B, Q, H = x.shape
+    V = w_lm.shape[0]
+    dev = x.device
+    if n_accepted is None:
+        n_accepted = torch.empty((B,), dtype=torch.int32, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, Q), dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = workspace(lib.massv_lm_head_greedy_accept_workspace(B, Q - 1, H, V, dtype_code(x)), dev)
+    _check(lib.massv_lm_head_greedy_accept(_ptr(x), _ptr(final_norm), _ptr(w_lm), _ptr(draft_tokens), B, Q - 1, H, V,
+                                           float(norm_eps), dtype_code(x), _ptr(n_accepted), _ptr(out_tokens),
+                                           _ptr(ws), ws.numel(), _stream()), "massv_lm_head_greedy_accept")
     return n_accepted, out_tokens
 
 

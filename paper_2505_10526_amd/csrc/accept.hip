@@ -29,7 +29,6 @@ constexpr int kAccChunk = kWave * kAccPerLane;            // 1024 logits per wav
 constexpr int kPickPerThread = kAccChunk / kAccThreads;   // 4 consecutive logits per thread when locating the token
 constexpr int kMaxGamma = 15;
 
-struct RowPartial { float m; int arg; double s; };
 struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d; };
 struct ChunkMass { double r, p; };
 
@@ -471,6 +470,14 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
 }
 
 namespace massv {
+int launch_accept_decide_greedy(const RowPartial* part, int C, const int32_t* draft_tokens, int B, int gamma, int V,
+                                int32_t* n_accepted, int32_t* out_tokens, hipStream_t st) {
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st, (const float*)nullptr, (const float*)nullptr,
+                       draft_tokens, (const float*)nullptr, B, gamma, V, C, 1.0, 1.f, 1, part, (SeqSel*)nullptr, n_accepted,
+                       out_tokens);
+    return launch_status();
+}
+
 __global__ void commit_tokens_kernel(const int* __restrict__ n_accepted, const int* __restrict__ out_tokens,
                                      int* __restrict__ kv_len, int* __restrict__ last_token, int B, int gamma) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;

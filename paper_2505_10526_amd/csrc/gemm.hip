@@ -39,6 +39,8 @@
 // configuration.
 #include "kernels.h"
 
+#include <limits.h>
+
 namespace massv {
 
 constexpr int kGemmWaves = 4;            // waves per workgroup (K split)
@@ -168,6 +170,12 @@ void gemm_stream_kernel(GemmDev g) {
         }
     }
 
+    // EPI_ARGMAX: largest summed output (and its lowest column) seen by this lane for row 16 mt + lr
+    float best_v[MT];
+    int best_i[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { best_v[mt] = -INFINITY; best_i[mt] = INT_MAX; }
+
     // ---- sum the waves through LDS in wave order, GRP tiles per round ----
     constexpr int GRP = ReduceGroup<MT, NT>::value;
     for (int g0 = 0; g0 < NT; g0 += GRP) {
@@ -202,12 +210,43 @@ void gemm_stream_kernel(GemmDev g) {
                         for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(gemm_act(s[i], g.act) * u[i]);
                         *reinterpret_cast<bf16x4*>((bf16_t*)g.y + packed_index(m, col, MT)) = o;
                     }
+                } else if (EPI == EPI_ARGMAX) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)                   // ascending columns: a tie keeps the lower one
+                        if (s[i] > best_v[mt] || (s[i] == best_v[mt] && col + i < best_i[mt])) { best_v[mt] = s[i]; best_i[mt] = col + i; }
                 } else if (m < g.M) {
                     float* dst = (float*)g.y + (EPI == EPI_PARTIAL ? (size_t)blockIdx.y * g.slab_stride : 0) +
                                  (size_t)m * g.ldy + col;
                     *reinterpret_cast<floatx4*>(dst) = s;
                 }
             }
+        }
+    }
+    if constexpr (EPI == EPI_ARGMAX) {
+        // lanes of the four column groups of a row, then the four waves, then one record per row and workgroup
+        __syncthreads();                                         // the reduction buffer is free
+        float* bv = reinterpret_cast<float*>(red);               // [WK][MT*16]
+        int* bi = reinterpret_cast<int*>(bv + WK * MT * 16);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float v = best_v[mt]; int i = best_i[mt];
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(v, o, kWave);
+                const int oi = __shfl_xor(i, o, kWave);
+                if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+            }
+            if (lc == 0) { bv[wave * MT * 16 + mt * 16 + lr] = v; bi[wave * MT * 16 + mt * 16 + lr] = i; }
+        }
+        __syncthreads();
+        if (tid < MT * 16 && tid < g.M) {
+            float v = bv[tid]; int i = bi[tid];
+            for (int w = 1; w < WK; ++w) {
+                const float ov = bv[w * MT * 16 + tid]; const int oi = bi[w * MT * 16 + tid];
+                if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+            }
+            RowPartial r; r.m = v; r.arg = i; r.s = 0.0;
+            reinterpret_cast<RowPartial*>(g.y)[(size_t)tid * gridDim.x + blockIdx.x] = r;
         }
     }
 }
@@ -258,7 +297,7 @@ static int n_total(const GemmArgs& g) { return g.n[0] + g.n[1] + g.n[2]; }
 int gemm_supported(const GemmArgs& g) {
     if (g.M < 1 || g.K < 1 || g.n[0] < 1) return MASSV_EINVAL;
     if (g.epilogue == EPI_GATED && (g.n[1] != g.n[0] || g.n[2] != 0)) return MASSV_EINVAL;
-    if (g.dtype == MASSV_F32) return (g.epilogue == EPI_PARTIAL) ? MASSV_EINVAL : MASSV_OK;
+    if (g.dtype == MASSV_F32) return (g.epilogue == EPI_PARTIAL || g.epilogue == EPI_ARGMAX) ? MASSV_EINVAL : MASSV_OK;
     if (g.epilogue == EPI_STORE || g.epilogue == EPI_RESIDUAL) return MASSV_EINVAL;   // bf16 goes through partial sums
     if (g.M > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
     if (g.K % 32) return MASSV_EUNSUPPORTED;
@@ -277,7 +316,7 @@ GemmPlan gemm_plan(const GemmArgs& g) {
     const int T = (g.epilogue == EPI_GATED) ? 2 * (g.n[0] / 16) : n_total(g) / 16;
     const int n_chunks = (g.K + 127) / 128;
     static const int cand_partial[] = {8, 7, 4}, cand_gated[] = {10, 8, 4}, cand_logits[] = {10, 8, 4};
-    const int* cand = g.epilogue == EPI_GATED ? cand_gated : g.epilogue == EPI_LOGITS ? cand_logits : cand_partial;
+    const int* cand = g.epilogue == EPI_GATED ? cand_gated : (g.epilogue == EPI_LOGITS || g.epilogue == EPI_ARGMAX) ? cand_logits : cand_partial;
     double best_score = -1.0;
     for (int i = 0; i < 3; ++i) {
         int nt = cand[i];
@@ -387,6 +426,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
         case EPI_PARTIAL: rc2 = launch_stream_epi<EPI_PARTIAL>(d, g.M, p, g.kid, st); break;
         case EPI_GATED: rc2 = launch_stream_epi<EPI_GATED>(d, g.M, p, g.kid, st); break;
         case EPI_LOGITS: rc2 = launch_stream_epi<EPI_LOGITS>(d, g.M, p, g.kid, st); break;
+        case EPI_ARGMAX: rc2 = launch_stream_epi<EPI_ARGMAX>(d, g.M, p, g.kid, st); break;
     }
     if (rc2 != MASSV_OK) return rc2;
     return launch_status();

@@ -60,10 +60,17 @@ enum Epilogue {
     EPI_RESIDUAL = 1,   // f32 only: y = acc + residual (residual may alias y)
     EPI_GATED = 2,      // two matrices (gate, up) of equal size: y = act(gate) * up (bf16: y in operand order)
     EPI_LOGITS = 3,     // y = acc stored as float32 [M][N]
-    EPI_PARTIAL = 4     // bf16 only: fp32 partial sums y[slab][16*ceil(M/16)][N], one slab per K range;
+    EPI_PARTIAL = 4,    // bf16 only: fp32 partial sums y[slab][16*ceil(M/16)][N], one slab per K range;
                         // bias / residual are applied by the kernel that sums the slabs
+    EPI_ARGMAX = 5      // bf16 only: nothing is stored but, per row and workgroup, the largest output and its
+                        // (lowest) column: y is RowPartial[M][groups]
 };
+// Maximum, first arg-max and sum of exponentials of one piece of a logit row (pieces are merged by accept_decide_kernel).
+struct RowPartial { float m; int arg; double s; };
 struct GemmPlan { int nt, slabs, chunks_per_slab, groups; };
+// Greedy accept chain from per-piece row partials: part[row][C] for the B*(gamma+1) target rows (accept.hip).
+int launch_accept_decide_greedy(const RowPartial* part, int C, const int32_t* draft_tokens, int B, int gamma, int V,
+                                int32_t* n_accepted, int32_t* out_tokens, hipStream_t st);
 struct GemmArgs {
     const void* x;            // f32: [M][K] row-major; bf16: operand order (packed_index), packed_elems(M,K) elements
     const void* w[3];         // [n_i][K]

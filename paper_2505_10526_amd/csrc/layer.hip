@@ -224,3 +224,45 @@ extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const
     g.epilogue = EPI_LOGITS; g.dtype = dtype; g.kid = MASSV_K_LMHEAD;
     return launch_gemm(g, st);
 }
+
+// lm_head and the temperature-0 accept rule in one pass over the vocabulary projection: the projection's epilogue
+// keeps, per row and workgroup, only the largest logit and its column, so the M x V logits are never written.
+static GemmArgs greedy_gemm(int32_t M, int32_t H, int32_t V) {
+    GemmArgs g = {};
+    g.n[0] = V; g.M = M; g.K = H; g.epilogue = EPI_ARGMAX; g.dtype = MASSV_BF16; g.kid = MASSV_K_LMHEAD;
+    return g;
+}
+
+static int check_greedy(int32_t B, int32_t gamma, int32_t H, int32_t V, int32_t dtype) {
+    if (B < 1 || gamma < 0 || H < 1 || V < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    if (dtype != MASSV_BF16) return MASSV_EUNSUPPORTED;
+    if (gamma > 15 || (int64_t)B * (gamma + 1) > MASSV_MAX_ROWS || H % 32 || V % 16) return MASSV_EUNSUPPORTED;
+    return MASSV_OK;
+}
+
+extern "C" size_t massv_lm_head_greedy_accept_workspace(int32_t B, int32_t gamma, int32_t H, int32_t V, int32_t dtype) {
+    if (check_greedy(B, gamma, H, V, dtype) != MASSV_OK) return 0;
+    const int M = B * (gamma + 1);
+    const GemmPlan p = gemm_plan(greedy_gemm(M, H, V));
+    return align_up(packed_elems(M, H) * 2, 256) + align_up((size_t)M * p.groups * sizeof(RowPartial), 256);
+}
+
+extern "C" int massv_lm_head_greedy_accept(const void* x, const void* final_norm, const void* w_lm,
+                                           const int32_t* draft_tokens, int32_t B, int32_t gamma, int32_t H, int32_t V,
+                                           float norm_eps, int32_t dtype, int32_t* n_accepted, int32_t* out_tokens,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_greedy(B, gamma, H, V, dtype);
+    if (rc != MASSV_OK) return rc;
+    if (!x || !w_lm || !n_accepted || !out_tokens || (gamma > 0 && !draft_tokens)) return MASSV_EINVAL;
+    if (!(norm_eps >= 0.f)) return MASSV_EINVAL;
+    if (!workspace || workspace_bytes < massv_lm_head_greedy_accept_workspace(B, gamma, H, V, dtype)) return MASSV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int M = B * (gamma + 1);
+    if ((rc = launch_rmsnorm_packed(x, final_norm, workspace, M, H, norm_eps, st)) != MASSV_OK) return rc;
+    GemmArgs g = greedy_gemm(M, H, V);
+    RowPartial* part = (RowPartial*)((char*)workspace + align_up(packed_elems(M, H) * 2, 256));
+    g.x = workspace; g.w[0] = w_lm; g.y = part;
+    if ((rc = launch_gemm(g, st)) != MASSV_OK) return rc;
+    return launch_accept_decide_greedy(part, gemm_plan(g).groups, draft_tokens, B, gamma, V, n_accepted, out_tokens, st);
+}

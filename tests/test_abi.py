@@ -161,6 +161,26 @@ def test_linear_argument_checks(lib):
     assert f(*ok(ws=None)) == binding.EWORKSPACE
 
 
+def test_lm_head_greedy_accept_argument_checks(lib):
+    f = lib.massv_lm_head_greedy_accept
+    ws = lib.massv_lm_head_greedy_accept_workspace(8, 5, 3584, 152064, binding.BF16)
+    assert ws > 0
+    assert lib.massv_lm_head_greedy_accept_workspace(8, 5, 3584, 152064, binding.F32) == 0
+    ok = lambda **kw: [kw.get("x", FAKE), FAKE, kw.get("w", FAKE), kw.get("d", FAKE), kw.get("B", 8), kw.get("g", 5), kw.get("H", 3584),
+                       kw.get("V", 152064), 1e-6, kw.get("dt", binding.BF16), kw.get("n", FAKE), kw.get("o", FAKE), kw.get("ws", FAKE),
+                       kw.get("wsb", ws), None]
+    assert f(*ok(x=None)) == binding.EINVAL
+    assert f(*ok(w=None)) == binding.EINVAL
+    assert f(*ok(d=None)) == binding.EINVAL
+    assert f(*ok(n=None)) == binding.EINVAL
+    assert f(*ok(B=0)) == binding.EINVAL
+    assert f(*ok(dt=binding.F32)) == binding.EUNSUPPORTED
+    assert f(*ok(B=11)) == binding.EUNSUPPORTED            # 66 rows
+    assert f(*ok(g=16, B=1)) == binding.EUNSUPPORTED
+    assert f(*ok(V=152065)) == binding.EUNSUPPORTED
+    assert f(*ok(wsb=ws - 1)) == binding.EWORKSPACE
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))

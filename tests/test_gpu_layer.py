@@ -236,3 +236,52 @@ def test_layer_stack_interleaves_local_and_global_layers():
         torch.cuda.synchronize()
         tol = TOL_BF16 if base.dtype == "bf16" else TOL_F32 * 4
         assert_close(xd.float().cpu().numpy(), y_ref, tol, "interleaved stack output")
+
+
+# ---------------------------------------------------------------------------
+# vocabulary projection fused with the temperature-0 accept rule (no logits written)
+# ---------------------------------------------------------------------------
+def greedy_case(s, B, gamma, seed, head_std=0.05, duplicate_rows=False):
+    Q = gamma + 1
+    head = synth.lm_head_weights(s, seed, std=head_std)
+    if duplicate_rows:                                   # every logit appears twice: ties must go to the lower token id
+        head["w_lm"][s.vocab // 2:] = head["w_lm"][: s.vocab // 2]
+    x = synth.hidden_states(s, B, Q, seed)
+    logits = O.lm_head_logits(x.reshape(B * Q, -1), head["final_norm"], head["w_lm"], s.norm_eps).reshape(B, Q, -1)
+    # drafts: the checker's arg-max for a random-length prefix of every sequence, something else after it
+    rng = np.random.default_rng(seed)
+    drafts = np.argmax(logits[:, :gamma], axis=-1).astype(np.int32)
+    for b in range(B):
+        keep = int(rng.integers(0, gamma + 1))
+        if keep < gamma:
+            drafts[b, keep] = (drafts[b, keep] + 1 + int(rng.integers(0, s.vocab - 1))) % s.vocab
+    xd = to_dev(x, s.dtype)
+    norm, w = to_dev(head["final_norm"], s.dtype), binding.weight_pack(to_dev(head["w_lm"], s.dtype))
+    return xd, norm, w, i32(drafts), logits, drafts
+
+
+@pytest.mark.parametrize("s,B,gamma,dup", [(synth.TINY_BF16, 3, 5, False), (synth.TINY_BF16, 8, 5, True), (synth.TINY_BF16, 1, 0, False),
+                                           (synth.TINY_BF16, 4, 15, False), (synth.QWEN7B, 8, 5, False), (synth.QWEN7B, 2, 3, True)],
+                         ids=["tiny", "tiny-ties", "tiny-gamma0", "tiny-gamma15", "qwen7b", "qwen7b-ties"])
+def test_lm_head_greedy_accept(s, B, gamma, dup):
+    xd, norm, w, dtok, logits_ref, drafts = greedy_case(s, B, gamma, seed=41 + B + gamma, duplicate_rows=dup)
+    n_f, out_f = binding.lm_head_greedy_accept(xd, norm, w, dtok if gamma else None, s.norm_eps)
+    # the two separate calls on the same inputs: identical integers, ties included
+    lg = binding.lm_head_logits(xd, norm, w, s.norm_eps).reshape(B, gamma + 1, -1)
+    n_2, out_2 = binding.spec_accept(lg, None, dtok if gamma else None, None, 0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(n_f, n_2) and torch.equal(out_f, out_2)
+    if dup:
+        assert int(out_f.max()) < s.vocab // 2
+        return
+    # the checker, wherever its arg-max is clear of the bf16 path's error
+    top = np.sort(logits_ref, axis=-1)[..., -2:]
+    clear = (top[..., 1] - top[..., 0]) > 5e-3 * np.max(np.abs(logits_ref))
+    n_o, out_o, _ = O.spec_accept(logits_ref, None, drafts, None, 0.0)
+    for b in range(B):
+        if clear[b].all():
+            assert int(n_f[b]) == n_o[b] and np.array_equal(out_f[b].cpu().numpy(), out_o[b])
+    if gamma <= 5:
+        assert clear.all(axis=1).sum() >= 1                 # the comparison with the checker is not vacuous
+    if gamma >= 5 and B >= 3:
+        assert len(set(n_o.tolist())) > 1
