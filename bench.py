@@ -359,19 +359,25 @@ def iteration_bench(torch, binding, synth, dev, args):
         for i in range(gamma):
             binding.embed_tokens(drf.table, seq[:, i].contiguous(), x=xd.view(B, -1))
             binding.verify_layers(drf.cfg, drf.stack, xd, pos_d[i], kv_d[i], l_max, ws=ws)
-            binding.lm_head_logits(xd.view(B, -1), drf.final_norm, drf.w_lm, drf.shape.norm_eps, out=step_logits, ws=ws)
-            binding.spec_accept(step_logits.view(B, 1, V), None, None, uni_d[i] if T > 0 else None, T,
-                                n_accepted=n0, out_tokens=tok, ws=ws)
-            seq[:, i + 1] = tok[:, 0]
-            if T > 0:
+            if T == 0:      # arg-max straight out of the vocabulary projection, no logits written
+                binding.lm_head_greedy_accept(xd, drf.final_norm, drf.w_lm, None, drf.shape.norm_eps, n_accepted=n0,
+                                              out_tokens=tok, ws=ws)
+            else:
+                binding.lm_head_logits(xd.view(B, -1), drf.final_norm, drf.w_lm, drf.shape.norm_eps, out=step_logits, ws=ws)
+                binding.spec_accept(step_logits.view(B, 1, V), None, None, uni_d[i], T, n_accepted=n0, out_tokens=tok, ws=ws)
                 draft_logits[:, i].copy_(step_logits)
+            seq[:, i + 1] = tok[:, 0]
 
     def verify():
         binding.embed_tokens(tgt.table, seq.view(-1), x=xt.view(B * Q, -1))
         binding.verify_layers(tgt.cfg, tgt.stack, xt, pos_t, kv_t, l_max, ws=ws)
-        binding.lm_head_logits(xt.view(B * Q, -1), tgt.final_norm, tgt.w_lm, tgt.shape.norm_eps, out=logits, ws=ws)
-        binding.spec_accept(logits.view(B, Q, V), draft_logits if T > 0 else None, seq[:, 1:].contiguous(),
-                            uni_t if T > 0 else None, T, n_accepted=n_acc, out_tokens=out_tok, ws=ws)
+        if T == 0:
+            binding.lm_head_greedy_accept(xt, tgt.final_norm, tgt.w_lm, seq[:, 1:].contiguous(), tgt.shape.norm_eps,
+                                          n_accepted=n_acc, out_tokens=out_tok, ws=ws)
+        else:
+            binding.lm_head_logits(xt.view(B * Q, -1), tgt.final_norm, tgt.w_lm, tgt.shape.norm_eps, out=logits, ws=ws)
+            binding.spec_accept(logits.view(B, Q, V), draft_logits, seq[:, 1:].contiguous(), uni_t, T,
+                                n_accepted=n_acc, out_tokens=out_tok, ws=ws)
 
     def timed(fn, iters):
         torch.cuda.synchronize()

@@ -160,3 +160,12 @@ def test_window_rows_outside_are_not_read():
                                    binding.v_cache_pack(to_dev(pad_rows(v, lm), s.dtype)), i32(kv.kv_len), window=W)
     torch.cuda.synchronize()
     assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "window with NaN outside")
+
+
+@pytest.mark.parametrize("window", [3, 40, 700])
+def test_window_four_row_tiles_and_wide_heads(window):
+    """gamma = 7 on the 28/4-head shape stacks 56 rows (four row tiles); d = 256 with gamma = 15 stacks 32."""
+    got, ref = run_case(synth.QWEN7B, 2, 8, [900, 65], [300, 10], seed=26, hot_keys=2, nan_tail=True, window=window)
+    assert_close(got, ref, TOL_BF16, f"Q=8 window {window}")
+    got, ref = run_case(synth.GEMMA12B, 1, 16, [333], [100], seed=27, hot_keys=2, nan_tail=True, window=window)
+    assert_close(got, ref, TOL_BF16, f"d=256 Q=16 window {window}")

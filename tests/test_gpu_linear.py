@@ -79,3 +79,10 @@ def test_repeatable_bits():
     a = run_gpu(x, w, b, binding.LIN_GELU_TANH)
     c = run_gpu(x, w, b, binding.LIN_GELU_TANH)
     assert np.array_equal(a, c)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 16, 64), (16, 16, 64), (257, 272, 64), (255, 256, 128), (256, 4096 + 16, 192)])
+def test_smallest_and_tile_edge_shapes(M, N, K):
+    """One row / one feature tile / one k-step; sizes one short of, equal to and one past a 256-wide tile."""
+    x, w, b = inputs(M, N, K, seed=100 + M + N + K)
+    assert_close(run_gpu(x, w, b, binding.LIN_GELU_TANH), O.gelu_tanh(O.linear(x, w, b)), TOL, f"{M}x{N}x{K}")
