@@ -106,6 +106,11 @@ void attention_generic_kernel(const T* __restrict__ q, const T* __restrict__ kc,
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
 // ---------------------------------------------------------------------------
+// Two merge buffers of [16 MT][D + 4] floats (plus the small per-wave tables) within the 64 KB a workgroup gets by default?
+__host__ __device__ constexpr bool attn_tree_merge(int D, int MT) {
+    return 2 * MT * 16 * (D + 4) * (int)sizeof(float) + 4096 <= 65536;
+}
+
 __device__ inline float xor16_max(float v) {        // over the 4 lane groups that share a query row
     v = fmaxf(v, __shfl_xor(v, 16, kWave));
     return fmaxf(v, __shfl_xor(v, 32, kWave));
@@ -346,27 +351,45 @@ void attention_mfma_kernel(AttnParams p) {
         m_tot[mt] = m; l_tot[mt] = l;
         if (wave == 0 && lc == 0) s_lt[r] = l;
     }
-    for (int w = 0; w < kAttnWaves; ++w) {          // waves add into the buffer one after another
-        if (wave == w) {
+    // Where two merge buffers fit in LDS the four waves are summed as (w0 + w2) + (w1 + w3): waves 0 and 1 store
+    // side by side, waves 2 and 3 add to them side by side, the readers below add the two buffers.  (One buffer with
+    // the waves taking turns took 3.6 us of an 11 us launch.)  Otherwise the waves add into one buffer in turn.
+    constexpr bool TREE = attn_tree_merge(D, MT);
+    float* s_o2 = s_o + ROWS * LDS_STRIDE;
+    auto merge_store = [&](float* buf, bool add) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    float* dst = s_o + (mt * 16 + lr) * LDS_STRIDE + nt * 16 + lc * 4;
-                    floatx4 v = acc[mt][nt];
-                    if (w > 0) v += *reinterpret_cast<floatx4*>(dst);
-                    *reinterpret_cast<floatx4*>(dst) = v;
-                }
-        }
+            for (int nt = 0; nt < NT; ++nt) {
+                float* dst = buf + (mt * 16 + lr) * LDS_STRIDE + nt * 16 + lc * 4;
+                floatx4 v = acc[mt][nt];
+                if (add) v += *reinterpret_cast<floatx4*>(dst);
+                *reinterpret_cast<floatx4*>(dst) = v;
+            }
+    };
+    if constexpr (TREE) {
+        if (wave < 2) merge_store(wave == 0 ? s_o : s_o2, false);
         __syncthreads();
+        if (wave >= 2) merge_store(wave == 2 ? s_o : s_o2, true);
+        __syncthreads();
+    } else {
+        for (int w = 0; w < kAttnWaves; ++w) {
+            if (wave == w) merge_store(s_o, w > 0);
+            __syncthreads();
+        }
     }
+    auto merged = [&](int r, int c4) -> floatx4 {
+        floatx4 v = *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
+        if constexpr (TREE) v += *reinterpret_cast<const floatx4*>(s_o2 + r * LDS_STRIDE + c4 * 4);
+        return v;
+    };
 
     // ---- write: final output if there is one split, else the partial ----
     if (p.n_split == 1) {
         for (int idx = tid; idx < rows * (D / 4); idx += kAttnThreads) {
             const int r = idx / (D / 4), c4 = idx % (D / 4);
             const int i = r / G, hh = r % G;
-            const floatx4 v = *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
+            const floatx4 v = merged(r, c4);
             const float inv = 1.0f / s_lt[r];
             bf16x4 o = {(bf16_t)(v[0] * inv), (bf16_t)(v[1] * inv), (bf16_t)(v[2] * inv), (bf16_t)(v[3] * inv)};
             const int mrow = b * p.Q + i, col = (g * G + hh) * D + c4 * 4;
@@ -378,8 +401,7 @@ void attention_mfma_kernel(AttnParams p) {
         const size_t slot = (bg * p.n_split + split) * ROWS;
         for (int idx = tid; idx < rows * (D / 4); idx += kAttnThreads) {
             const int r = idx / (D / 4), c4 = idx % (D / 4);
-            *reinterpret_cast<floatx4*>(p.part_o + (slot + r) * D + c4 * 4) =
-                *reinterpret_cast<const floatx4*>(s_o + r * LDS_STRIDE + c4 * 4);
+            *reinterpret_cast<floatx4*>(p.part_o + (slot + r) * D + c4 * 4) = merged(r, c4);
         }
         if (wave == 0 && lc == 0) {
 #pragma unroll
@@ -489,7 +511,7 @@ size_t attention_workspace(const massv_attn_desc& a) {
 
 template <int D, int MT>
 static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
-    const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) ;
+    const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) * (attn_tree_merge(D, MT) ? 2 : 1);
     launch_traced(MASSV_K_ATTENTION, attention_mfma_kernel<D, MT>, dim3(p.n_split, a.n_kv_heads, a.batch),
                   dim3(kAttnThreads), lds, st, p);
     if (p.n_split > 1)
