@@ -106,9 +106,10 @@ void attention_generic_kernel(const T* __restrict__ q, const T* __restrict__ kc,
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.
 // ---------------------------------------------------------------------------
-// Two merge buffers of [16 MT][D + 4] floats (plus the small per-wave tables) within the 64 KB a workgroup gets by default?
+// Two merge buffers of [16 MT][D + 4] floats (plus the small per-wave tables) within the 160 KB of LDS of a CU?
+// (Always, for the tile shapes built; above 64 KB the kernel's limit is raised once per device.)
 __host__ __device__ constexpr bool attn_tree_merge(int D, int MT) {
-    return 2 * MT * 16 * (D + 4) * (int)sizeof(float) + 4096 <= 65536;
+    return 2 * MT * 16 * (D + 4) * (int)sizeof(float) + 4096 <= 160 * 1024;
 }
 
 __device__ inline float xor16_max(float v) {        // over the 4 lane groups that share a query row
@@ -512,6 +513,16 @@ size_t attention_workspace(const massv_attn_desc& a) {
 template <int D, int MT>
 static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
     const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) * (attn_tree_merge(D, MT) ? 2 : 1);
+    if (lds > 48 * 1024) {                       // more dynamic LDS than a kernel may use by default
+        static bool ready[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
+        if (!ready[dev]) {
+            if (hipFuncSetAttribute((const void*)attention_mfma_kernel<D, MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds) != hipSuccess) return MASSV_ELAUNCH;
+            ready[dev] = true;
+        }
+    }
     launch_traced(MASSV_K_ATTENTION, attention_mfma_kernel<D, MT>, dim3(p.n_split, a.n_kv_heads, a.batch),
                   dim3(kAttnThreads), lds, st, p);
     if (p.n_split > 1)
