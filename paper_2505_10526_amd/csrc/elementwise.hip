@@ -267,10 +267,10 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
     bf16x8 xv = {0, 0, 0, 0, 0, 0, 0, 0};
     if (live) {
         xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
-        for (int s0 = 0; s0 < n_slabs; s0 += 4) {              // 4 slabs' loads in flight at once; summed in slab order
-            floatx4 p0[4], p1[4];
+        for (int s0 = 0; s0 < n_slabs; s0 += 8) {              // 8 slabs' loads in flight at once; summed in slab order
+            floatx4 p0[8], p1[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const bool ok = s0 + u < n_slabs;
                 const floatx4* p = reinterpret_cast<const floatx4*>(partial + (size_t)(ok ? s0 + u : 0) * slab_stride +
                                                                     (size_t)m * H + k8 * 8);
@@ -278,7 +278,7 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
                 p1[u] = ok ? p[1] : floatx4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { add[e] += p0[u][e]; add[4 + e] += p1[u][e]; }
         }
