@@ -67,7 +67,7 @@ enum Epilogue {
 };
 // Maximum, first arg-max and sum of exponentials of one piece of a logit row (pieces are merged by accept_decide_kernel).
 struct RowPartial { float m; int arg; double s; };
-struct GemmPlan { int nt, slabs, chunks_per_slab, groups; };
+struct GemmPlan { int nt, slabs, groups; };
 // Greedy accept chain from per-piece row partials: part[row][C] for the B*(gamma+1) target rows (accept.hip).
 int launch_accept_decide_greedy(const RowPartial* part, int C, const int32_t* draft_tokens, int B, int gamma, int V,
                                 int32_t* n_accepted, int32_t* out_tokens, hipStream_t st);
