@@ -143,18 +143,42 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
         const int r = (t < Q) ? b * Q + t : B * Q + b * gamma + (t - Q);
         const RowPartial* p = part + (size_t)r * C;
         float m = -INFINITY; int am = INT_MAX;
-        for (int c = lane; c < C; c += kWave) argmax_merge(m, am, p[c].m, p[c].arg);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(m, o, kWave);
-            const int oi = __shfl_xor(am, o, kWave);
-            argmax_merge(m, am, ov, oi);
-        }
         double s = 0.0;
-        if (!greedy) {
-            for (int c = lane; c < C; c += kWave)
-                if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
-            s = wave_sum(s);
+        if (C <= 4 * kWave) {                       // the usual case: every partial is loaded once, all loads in flight
+            RowPartial own[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = lane + j * kWave;
+                own[j].m = -INFINITY; own[j].arg = INT_MAX; own[j].s = 0.0;
+                if (c < C) own[j] = p[c];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) argmax_merge(m, am, own[j].m, own[j].arg);      // ascending c, as below
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(m, o, kWave);
+                const int oi = __shfl_xor(am, o, kWave);
+                argmax_merge(m, am, ov, oi);
+            }
+            if (!greedy) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (own[j].m > -INFINITY) s += own[j].s * (double)exp2f((own[j].m - m) * scale2);
+                s = wave_sum(s);
+            }
+        } else {
+            for (int c = lane; c < C; c += kWave) argmax_merge(m, am, p[c].m, p[c].arg);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(m, o, kWave);
+                const int oi = __shfl_xor(am, o, kWave);
+                argmax_merge(m, am, ov, oi);
+            }
+            if (!greedy) {
+                for (int c = lane; c < C; c += kWave)
+                    if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
+                s = wave_sum(s);
+            }
         }
         if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
     }
@@ -256,7 +280,9 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
                           const SeqSel* __restrict__ sel, const ChunkMass* __restrict__ mass,
                           int* __restrict__ out_tokens) {
     const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
+    // the selection record, the uniform and the chunk masses are independent loads: one round trip, not three
     const SeqSel s = sel[b];
+    const float u_res = uniforms[b * Q + gamma];
     __shared__ double wave_tot[kAccThreads / kWave];
     __shared__ int sh_chunk, sh_lastpos, sh_first, sh_last;
     __shared__ double sh_prefix;
@@ -272,7 +298,7 @@ void residual_pick_kernel(const float* __restrict__ target, const float* __restr
     const double incl_p = block_scan_incl(my_p, wave_tot, &tot_p);
     const int use_p = s.bonus || !(tot_r > 0.0);
     const double total = use_p ? tot_p : tot_r;
-    const double thr = (double)uniforms[b * Q + gamma] * total;
+    const double thr = (double)u_res * total;
     {
         double run = (use_p ? incl_p - my_p : incl_r - my_r);      // mass ahead of this thread's chunks
         for (int i = 0; i < per; ++i) {
