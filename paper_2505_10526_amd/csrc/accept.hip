@@ -26,7 +26,6 @@ namespace massv {
 constexpr int kAccThreads = 256;                          // 4 waves, one chunk each
 constexpr int kAccPerLane = 16;                           // 4 float4 loads per lane
 constexpr int kAccChunk = kWave * kAccPerLane;            // 1024 logits per wave
-constexpr int kPickPerThread = kAccChunk / kAccThreads;   // 4 consecutive logits per thread when locating the token
 constexpr int kMaxGamma = 15;
 
 struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d; };
@@ -72,6 +71,52 @@ __device__ inline void argmax_merge(float& v, int& i, float ov, int oi) {
     if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
 }
 
+// Inclusive prefix sum of one double per lane over the wave (lane order) with data-parallel-primitive moves:
+// four shifts inside each row of 16 lanes, then the last lane of row 0 / row 2 added to row 1 / row 3 and the last
+// lane of row 1 to rows 2 and 3.  A shift through the LDS crossbar costs a round trip of ~100 cycles per step and
+// the steps depend on each other; these moves are ordinary vector-ALU operands.
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_take(double v) {                 // lanes without a source lane, or in a masked row, read 0
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    const int slo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
+    const int shi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(shi, slo);
+}
+__device__ inline double wave_scan_incl(double v) {
+    v += dpp_take<0x111, 0xf>(v);                             // row_shr:1
+    v += dpp_take<0x112, 0xf>(v);                             // row_shr:2
+    v += dpp_take<0x114, 0xf>(v);                             // row_shr:4
+    v += dpp_take<0x118, 0xf>(v);                             // row_shr:8
+    v += dpp_take<0x142, 0xa>(v);                             // row_bcast:15 into rows 1 and 3
+    v += dpp_take<0x143, 0xc>(v);                             // row_bcast:31 into rows 2 and 3
+    return v;
+}
+__device__ inline double lane_value(double v, int src_lane) { // wave-uniform src_lane
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), src_lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), src_lane));
+}
+
+// Sum over the wave, the same value in every lane: the last lane of the prefix sum.
+__device__ inline double wave_total(double v) { return lane_value(wave_scan_incl(v), kWave - 1); }
+
+// (maximum, lowest index of it) over the wave by the same six moves; a lane without a source merges with itself.
+template <int CTRL, int ROW_MASK>
+__device__ inline void dpp_argmax_step(float& m, int& am) {
+    const float om = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(m), __float_as_int(m), CTRL, ROW_MASK, 0xf, false));
+    const int oi = __builtin_amdgcn_update_dpp(am, am, CTRL, ROW_MASK, 0xf, false);
+    argmax_merge(m, am, om, oi);
+}
+__device__ inline void wave_argmax(float& m, int& am) {       // result in every lane
+    dpp_argmax_step<0x111, 0xf>(m, am);
+    dpp_argmax_step<0x112, 0xf>(m, am);
+    dpp_argmax_step<0x114, 0xf>(m, am);
+    dpp_argmax_step<0x118, 0xf>(m, am);
+    dpp_argmax_step<0x142, 0xa>(m, am);
+    dpp_argmax_step<0x143, 0xc>(m, am);
+    m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), kWave - 1));
+    am = __builtin_amdgcn_readlane(am, kWave - 1);
+}
+
 __global__ __launch_bounds__(kAccThreads)
 void accept_stats_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                          int n_target_rows, int V, int C, TempScale ts, int greedy, int vec,
@@ -90,12 +135,7 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
 #pragma unroll
     for (int k = 1; k < kAccPerLane; ++k)
         if (x[k] > m) { m = x[k]; am = chunk_index(base, lane, k); }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(m, o, kWave);
-        int oi = __shfl_xor(am, o, kWave);
-        argmax_merge(m, am, ov, oi);
-    }
+    wave_argmax(m, am);
     double s = 0.0;
     if (!greedy) {
         float acc = 0.f;
@@ -103,7 +143,7 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
 #pragma unroll
             for (int k = 0; k < kAccPerLane; ++k) acc += exp2_raw(scaled(x[k] - m, ts));
         }
-        s = wave_sum((double)acc);
+        s = wave_total((double)acc);
     }
     if (lane == 0) {
         RowPartial p; p.m = m; p.arg = am; p.s = s;
@@ -154,30 +194,20 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) argmax_merge(m, am, own[j].m, own[j].arg);      // ascending c, as below
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const float ov = __shfl_xor(m, o, kWave);
-                const int oi = __shfl_xor(am, o, kWave);
-                argmax_merge(m, am, ov, oi);
-            }
+            wave_argmax(m, am);
             if (!greedy) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     if (own[j].m > -INFINITY) s += own[j].s * (double)exp2f((own[j].m - m) * scale2);
-                s = wave_sum(s);
+                s = wave_total(s);
             }
         } else {
             for (int c = lane; c < C; c += kWave) argmax_merge(m, am, p[c].m, p[c].arg);
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const float ov = __shfl_xor(m, o, kWave);
-                const int oi = __shfl_xor(am, o, kWave);
-                argmax_merge(m, am, ov, oi);
-            }
+            wave_argmax(m, am);
             if (!greedy) {
                 for (int c = lane; c < C; c += kWave)
                     if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
-                s = wave_sum(s);
+                s = wave_total(s);
             }
         }
         if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
@@ -248,110 +278,111 @@ void residual_mass_kernel(const float* __restrict__ target, const float* __restr
             sr += fmax(p - q, 0.0);
         }
     }
-    sr = wave_sum(sr); sp = wave_sum(sp);
+    sr = wave_total(sr); sp = wave_total(sp);
     if (lane == 0) {
         ChunkMass m; m.r = sr; m.p = sp;
         mass[(size_t)b * C + c] = m;
     }
 }
 
-// Inclusive scan of one double per thread over the 256 threads of the workgroup (thread order).
-// Returns the inclusive prefix; *total receives the sum over all threads.
-__device__ inline double block_scan_incl(double v, double* wave_tot, double* total) {
-    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const double t = __shfl_up(v, o, kWave);
-        if (lane >= o) v += t;
-    }
-    __syncthreads();                                  // wave_tot may still be read from a previous call
-    if (lane == kWave - 1) wave_tot[wave] = v;
-    __syncthreads();
-    double off = 0.0, tot = 0.0;
-#pragma unroll
-    for (int w = 0; w < kAccThreads / kWave; ++w) { if (w < wave) off += wave_tot[w]; tot += wave_tot[w]; }
-    *total = tot;
-    return v + off;
-}
+constexpr int kPickPerLane = kAccChunk / kWave;                // 16 consecutive logits per lane when locating the token
 
-__global__ __launch_bounds__(kAccThreads)
+// One wave per sequence, no LDS and no barriers: the lanes own consecutive runs of chunks, then consecutive
+// runs of tokens of the chosen chunk, so "first index whose running mass exceeds the threshold" is the first
+// lane that found one.
+__global__ __launch_bounds__(kWave)
 void residual_pick_kernel(const float* __restrict__ target, const float* __restrict__ draft,
-                          const float* __restrict__ uniforms, int gamma, int V, int C, TempScale ts,
+                          const float* __restrict__ uniforms, int gamma, int V, int C, TempScale ts, int vec,
                           const SeqSel* __restrict__ sel, const ChunkMass* __restrict__ mass,
                           int* __restrict__ out_tokens) {
-    const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
-    // the selection record, the uniform and the chunk masses are independent loads: one round trip, not three
+    const int b = blockIdx.x, lane = threadIdx.x, Q = gamma + 1;
+    // the selection record, the uniform and the chunk masses are independent loads: one round trip
     const SeqSel s = sel[b];
     const float u_res = uniforms[b * Q + gamma];
-    __shared__ double wave_tot[kAccThreads / kWave];
-    __shared__ int sh_chunk, sh_lastpos, sh_first, sh_last;
-    __shared__ double sh_prefix;
-    if (tid == 0) { sh_chunk = INT_MAX; sh_lastpos = -1; sh_first = INT_MAX; sh_last = -1; }
 
-    // ---- which chunk: every thread owns `per` consecutive chunks ----
+    // ---- which chunk: every lane owns `per` consecutive chunks ----
     const ChunkMass* m = mass + (size_t)b * C;
-    const int per = (C + kAccThreads - 1) / kAccThreads;
+    const int per = (C + kWave - 1) / kWave;
     double my_r = 0.0, my_p = 0.0;
-    for (int i = 0; i < per; ++i) { const int c = tid * per + i; if (c < C) { my_r += m[c].r; my_p += m[c].p; } }
-    double tot_r, tot_p;
-    const double incl_r = block_scan_incl(my_r, wave_tot, &tot_r);
-    const double incl_p = block_scan_incl(my_p, wave_tot, &tot_p);
+    for (int i = 0; i < per; ++i) { const int c = lane * per + i; if (c < C) { my_r += m[c].r; my_p += m[c].p; } }
+    const double incl_r = wave_scan_incl(my_r), incl_p = wave_scan_incl(my_p);
+    const double tot_r = lane_value(incl_r, kWave - 1), tot_p = lane_value(incl_p, kWave - 1);
     const int use_p = s.bonus || !(tot_r > 0.0);
     const double total = use_p ? tot_p : tot_r;
     const double thr = (double)u_res * total;
+    int found = -1, lastpos = -1;
+    double ahead_found = 0.0, ahead_last = 0.0;                // mass ahead of that chunk
     {
-        double run = (use_p ? incl_p - my_p : incl_r - my_r);      // mass ahead of this thread's chunks
+        double run = (use_p ? incl_p - my_p : incl_r - my_r);  // mass ahead of this lane's chunks
         for (int i = 0; i < per; ++i) {
-            const int c = tid * per + i;
+            const int c = lane * per + i;
             if (c >= C) break;
             const double v = use_p ? m[c].p : m[c].r;
-            if (v > 0.0) atomicMax(&sh_lastpos, c);
-            if (run + v > thr) { atomicMin(&sh_chunk, c); break; }
+            if (v > 0.0) { lastpos = c; ahead_last = run; }
+            if (run + v > thr) { found = c; ahead_found = run; break; }
             run += v;
         }
     }
-    __syncthreads();
-    const int chunk = (sh_chunk != INT_MAX) ? sh_chunk : (sh_lastpos >= 0 ? sh_lastpos : 0);
-    {   // mass ahead of the chosen chunk, recomputed by its owner in the same order as above
-        const int owner = chunk / per;
-        if (tid == owner) {
-            double run = (use_p ? incl_p - my_p : incl_r - my_r);
-            for (int c = owner * per; c < chunk; ++c) run += use_p ? m[c].p : m[c].r;
-            sh_prefix = run;
-        }
+    // the first lane that crossed the threshold; else (rounding at u -> 1) the last chunk with any mass; else chunk 0
+    const unsigned long long hit = __ballot(found >= 0), any = __ballot(lastpos >= 0);
+    int chunk = 0;
+    double prefix = 0.0;
+    if (hit) {
+        const int src = __ffsll((long long)hit) - 1;
+        chunk = __builtin_amdgcn_readlane(found, src); prefix = lane_value(ahead_found, src);
+    } else if (any) {
+        const int src = 63 - __clzll((long long)any);
+        chunk = __builtin_amdgcn_readlane(lastpos, src); prefix = lane_value(ahead_last, src);
     }
-    __syncthreads();
 
-    // ---- which token inside the chunk: every thread owns 4 consecutive tokens ----
-    const int base = chunk * kAccChunk + tid * kPickPerThread;
+    // ---- which token inside the chunk: every lane owns 16 consecutive tokens ----
+    const int base = chunk * kAccChunk + lane * kPickPerLane;
     const float* trow = target + ((size_t)b * Q + s.n) * V;
     const float* drow = s.bonus ? trow : draft + ((size_t)b * gamma + s.n) * V;      // never read when bonus
     const double inv_st = 1.0 / s.s_t, inv_sd = 1.0 / s.s_d;
-    double r[kPickPerThread];
+    float xt[kPickPerLane], xd[kPickPerLane];
+#pragma unroll
+    for (int j = 0; j < kPickPerLane / 4; ++j) {
+        const int idx = base + j * 4;
+        if (vec && idx + 3 < V) {
+            const float4 a = *reinterpret_cast<const float4*>(trow + idx);
+            xt[j * 4 + 0] = a.x; xt[j * 4 + 1] = a.y; xt[j * 4 + 2] = a.z; xt[j * 4 + 3] = a.w;
+            if (!use_p) {
+                const float4 d = *reinterpret_cast<const float4*>(drow + idx);
+                xd[j * 4 + 0] = d.x; xd[j * 4 + 1] = d.y; xd[j * 4 + 2] = d.z; xd[j * 4 + 3] = d.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                xt[j * 4 + e] = (idx + e < V) ? trow[idx + e] : -INFINITY;
+                if (!use_p) xd[j * 4 + e] = (idx + e < V) ? drow[idx + e] : -INFINITY;
+            }
+        }
+    }
+    double r[kPickPerLane];
     double tot = 0.0;
 #pragma unroll
-    for (int k = 0; k < kPickPerThread; ++k) {
-        const int idx = base + k;
+    for (int k = 0; k < kPickPerLane; ++k) {
         double v = 0.0;
-        if (idx < V) {
-            const double p = prob_of(trow[idx], s.m_t, inv_st, ts);
-            v = use_p ? p : fmax(p - prob_of(drow[idx], s.m_d, inv_sd, ts), 0.0);
+        if (base + k < V) {
+            const double p = prob_of(xt[k], s.m_t, inv_st, ts);
+            v = use_p ? p : fmax(p - prob_of(xd[k], s.m_d, inv_sd, ts), 0.0);
         }
         r[k] = v; tot += v;
     }
-    double chunk_total;
-    double run = block_scan_incl(tot, wave_tot, &chunk_total) - tot + sh_prefix;
+    double run = wave_scan_incl(tot) - tot + prefix;
     int first = INT_MAX, last = -1;
 #pragma unroll
-    for (int k = 0; k < kPickPerThread; ++k) {
+    for (int k = 0; k < kPickPerLane; ++k) {
         run += r[k];
         if (r[k] > 0.0) last = base + k;
         if (first == INT_MAX && run > thr && base + k < V) first = base + k;
     }
-    if (first != INT_MAX) atomicMin(&sh_first, first);
-    if (last >= 0) atomicMax(&sh_last, last);
-    __syncthreads();
-    if (tid == 0) out_tokens[b * Q + s.n] = (sh_first != INT_MAX) ? sh_first : (sh_last >= 0 ? sh_last : 0);
+    const unsigned long long hit2 = __ballot(first != INT_MAX), any2 = __ballot(last >= 0);
+    int token = 0;
+    if (hit2) token = __builtin_amdgcn_readlane(first, __ffsll((long long)hit2) - 1);
+    else if (any2) token = __builtin_amdgcn_readlane(last, 63 - __clzll((long long)any2));
+    if (lane == 0) out_tokens[b * Q + s.n] = token;
 }
 
 static inline int n_chunks(int V) { return (V + kAccChunk - 1) / kAccChunk; }
@@ -489,8 +520,8 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     if (!greedy) {
         launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + 3) / 4, B), dim3(kAccThreads), 0, st,
                       target_logits, draft_logits, gamma, V, C, ts, vec, (const SeqSel*)sel, mass);
-        hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kAccThreads), 0, st,
-                           target_logits, draft_logits, uniforms, gamma, V, C, ts, sel, mass, out_tokens);
+        hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kWave), 0, st,
+                           target_logits, draft_logits, uniforms, gamma, V, C, ts, vec, sel, mass, out_tokens);
     }
     return launch_status();
 }
