@@ -71,49 +71,22 @@ __device__ inline void argmax_merge(float& v, int& i, float ov, int oi) {
     if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
 }
 
-// Inclusive prefix sum of one double per lane over the wave (lane order) with data-parallel-primitive moves:
-// four shifts inside each row of 16 lanes, then the last lane of row 0 / row 2 added to row 1 / row 3 and the last
-// lane of row 1 to rows 2 and 3.  A shift through the LDS crossbar costs a round trip of ~100 cycles per step and
-// the steps depend on each other; these moves are ordinary vector-ALU operands.
-template <int CTRL, int ROW_MASK>
-__device__ inline double dpp_take(double v) {                 // lanes without a source lane, or in a masked row, read 0
-    const int lo = __double2loint(v), hi = __double2hiint(v);
-    const int slo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
-    const int shi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
-    return __hiloint2double(shi, slo);
-}
-__device__ inline double wave_scan_incl(double v) {
-    v += dpp_take<0x111, 0xf>(v);                             // row_shr:1
-    v += dpp_take<0x112, 0xf>(v);                             // row_shr:2
-    v += dpp_take<0x114, 0xf>(v);                             // row_shr:4
-    v += dpp_take<0x118, 0xf>(v);                             // row_shr:8
-    v += dpp_take<0x142, 0xa>(v);                             // row_bcast:15 into rows 1 and 3
-    v += dpp_take<0x143, 0xc>(v);                             // row_bcast:31 into rows 2 and 3
-    return v;
-}
-__device__ inline double lane_value(double v, int src_lane) { // wave-uniform src_lane
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), src_lane),
-                            __builtin_amdgcn_readlane(__double2loint(v), src_lane));
-}
-
-// Sum over the wave, the same value in every lane: the last lane of the prefix sum.
-__device__ inline double wave_total(double v) { return lane_value(wave_scan_incl(v), kWave - 1); }
-
-// (maximum, lowest index of it) over the wave by the same six moves; a lane without a source merges with itself.
+// (maximum, lowest index of it) over the wave by the six moves of the wave reductions; a lane without a source
+// merges with itself.
 template <int CTRL, int ROW_MASK>
 __device__ inline void dpp_argmax_step(float& m, int& am) {
-    const float om = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(m), __float_as_int(m), CTRL, ROW_MASK, 0xf, false));
-    const int oi = __builtin_amdgcn_update_dpp(am, am, CTRL, ROW_MASK, 0xf, false);
+    const float om = dpp_move<CTRL, ROW_MASK>(m, m);
+    const int oi = dpp_move<CTRL, ROW_MASK>(am, am);
     argmax_merge(m, am, om, oi);
 }
 __device__ inline void wave_argmax(float& m, int& am) {       // result in every lane
-    dpp_argmax_step<0x111, 0xf>(m, am);
-    dpp_argmax_step<0x112, 0xf>(m, am);
-    dpp_argmax_step<0x114, 0xf>(m, am);
-    dpp_argmax_step<0x118, 0xf>(m, am);
-    dpp_argmax_step<0x142, 0xa>(m, am);
-    dpp_argmax_step<0x143, 0xc>(m, am);
-    m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), kWave - 1));
+    dpp_argmax_step<kDppShr1, 0xf>(m, am);
+    dpp_argmax_step<kDppShr2, 0xf>(m, am);
+    dpp_argmax_step<kDppShr4, 0xf>(m, am);
+    dpp_argmax_step<kDppShr8, 0xf>(m, am);
+    dpp_argmax_step<kDppBcast15, 0xa>(m, am);
+    dpp_argmax_step<kDppBcast31, 0xc>(m, am);
+    m = lane_value(m, kWave - 1);
     am = __builtin_amdgcn_readlane(am, kWave - 1);
 }
 
@@ -143,7 +116,7 @@ void accept_stats_kernel(const float* __restrict__ target, const float* __restri
 #pragma unroll
             for (int k = 0; k < kAccPerLane; ++k) acc += exp2_raw(scaled(x[k] - m, ts));
         }
-        s = wave_total((double)acc);
+        s = wave_sum((double)acc);
     }
     if (lane == 0) {
         RowPartial p; p.m = m; p.arg = am; p.s = s;
@@ -199,7 +172,7 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     if (own[j].m > -INFINITY) s += own[j].s * (double)exp2f((own[j].m - m) * scale2);
-                s = wave_total(s);
+                s = wave_sum(s);
             }
         } else {
             for (int c = lane; c < C; c += kWave) argmax_merge(m, am, p[c].m, p[c].arg);
@@ -207,7 +180,7 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
             if (!greedy) {
                 for (int c = lane; c < C; c += kWave)
                     if (p[c].m > -INFINITY) s += p[c].s * (double)exp2f((p[c].m - m) * scale2);
-                s = wave_total(s);
+                s = wave_sum(s);
             }
         }
         if (lane == 0) { row_m[t] = (double)m; row_s[t] = s; row_arg[t] = (am == INT_MAX) ? 0 : am; }
@@ -278,7 +251,7 @@ void residual_mass_kernel(const float* __restrict__ target, const float* __restr
             sr += fmax(p - q, 0.0);
         }
     }
-    sr = wave_total(sr); sp = wave_total(sp);
+    sr = wave_sum(sr); sp = wave_sum(sp);
     if (lane == 0) {
         ChunkMass m; m.r = sr; m.p = sp;
         mass[(size_t)b * C + c] = m;

@@ -62,21 +62,55 @@ __host__ __device__ inline size_t packed_index(int m, int k, int mt_count) {
 }
 __host__ __device__ inline size_t packed_elems(int M, int K) { return (size_t)((M + 15) / 16) * 16 * K; }
 
-// ---- wavefront reductions (all 64 lanes take part, all receive the result) ----
-__device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+// ---- wavefront scans and reductions (all 64 lanes take part, all receive the result) ----
+// Built from data-parallel-primitive moves: four shifts inside each row of 16 lanes, then the last lane of
+// row 0 / row 2 combined into row 1 / row 3 and the last lane of row 1 into rows 2 and 3; lane 63 then holds the
+// combination of all lanes.  A shuffle through the LDS crossbar costs a round trip of about 100 cycles per
+// step, and the six steps depend on each other; these moves are ordinary vector-ALU operands.
+constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;      // written rows: 0xa (1 and 3), 0xc (2 and 3)
+
+// The source lane's value; `fill` in lanes that have no source lane or lie in a row that is not written.
+template <int CTRL, int ROW_MASK>
+__device__ inline int dpp_move(int v, int fill) { return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROW_MASK, 0xf, false); }
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_move(float v, float fill) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_move(double v, double fill) {
+    const int lo = __builtin_amdgcn_update_dpp(__double2loint(fill), __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(__double2hiint(fill), __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ inline float lane_value(float v, int src_lane) {  // src_lane uniform over the wave
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+__device__ inline double lane_value(double v, int src_lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), src_lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), src_lane));
+}
+// Inclusive prefix sum in lane order.
+template <typename T>
+__device__ inline T wave_scan_incl(T v) {
+    v += dpp_move<kDppShr1, 0xf>(v, (T)0);
+    v += dpp_move<kDppShr2, 0xf>(v, (T)0);
+    v += dpp_move<kDppShr4, 0xf>(v, (T)0);
+    v += dpp_move<kDppShr8, 0xf>(v, (T)0);
+    v += dpp_move<kDppBcast15, 0xa>(v, (T)0);
+    v += dpp_move<kDppBcast31, 0xc>(v, (T)0);
     return v;
 }
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
-__device__ inline double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+__device__ inline float wave_sum(float v) { return lane_value(wave_scan_incl(v), kWave - 1); }
+__device__ inline double wave_sum(double v) { return lane_value(wave_scan_incl(v), kWave - 1); }
+__device__ inline float wave_max(float v) {                   // a lane without a source combines with itself
+    v = fmaxf(v, dpp_move<kDppShr1, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<kDppShr2, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<kDppShr4, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<kDppShr8, 0xf>(v, v));
+    v = fmaxf(v, dpp_move<kDppBcast15, 0xa>(v, v));
+    v = fmaxf(v, dpp_move<kDppBcast31, 0xc>(v, v));
+    return lane_value(v, kWave - 1);
 }
 
 }  // namespace massv
