@@ -150,6 +150,7 @@ def main():
         vc = binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d))
         for b in range(B):                       # image rows carry a wider spread (input recipe)
             kc[b, :, : int(n_img_h[b])] *= 1.5
+        kc = binding.k_cache_pack(kc)
         w = binding.pack_layer_weights(w)           # projection matrices -> streaming layout (load-time step)
         layers.append((w, binding.layer_weights(w), kc, vc))
     final_norm = randn(H, std=0.1, mean=1.0)
@@ -312,7 +313,7 @@ class DeviceModel:
             if shape.qkv_bias:
                 w.update(bq=randn(nq, std=0.02), bk=randn(nkv, std=0.02), bv=randn(nkv, std=0.02))
             ws.append(binding.pack_layer_weights(w))
-            ks.append(randn(B, shape.n_kv_heads, l_max, d))
+            ks.append(binding.k_cache_pack(randn(B, shape.n_kv_heads, l_max, d)))
             vs.append(binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d)))
         self.shape, self.l_max = shape, l_max
         self.stack = binding.LayerStack(ws, ks, vs)
@@ -469,7 +470,7 @@ def extra_bandwidth(torch, binding, synth, dev, gen):
     bf = torch.bfloat16
     sets = 3
     qs = [torch.randn(B, Q, s.n_q_heads, s.head_dim, generator=gen, device=dev).to(bf) for _ in range(sets)]
-    ks = [torch.randn(B, s.n_kv_heads, l_max, s.head_dim, generator=gen, device=dev).to(bf) for _ in range(sets)]
+    ks = [binding.k_cache_pack(torch.randn(B, s.n_kv_heads, l_max, s.head_dim, generator=gen, device=dev).to(bf)) for _ in range(sets)]
     vs = [binding.v_cache_pack(torch.randn(B, s.n_kv_heads, l_max, s.head_dim, generator=gen, device=dev).to(bf))
           for _ in range(sets)]
     kv_len = torch.full((B,), L, dtype=torch.int32, device=dev)

@@ -34,7 +34,14 @@
  *     sequence b BEFORE the step, L_max = rows allocated per sequence.
  *
  * KV cache layout (dtype = f32 or bf16 elements)
- *   k_cache [B][n_kv][L_max][d]            row j of (b, g) at ((b*n_kv+g)*L_max + j)*d
+ *   k_cache, f32   [B][n_kv][L_max][d]     row j of (b, g) at ((b*n_kv+g)*L_max + j)*d
+ *   k_cache, bf16  [B][n_kv][L_max/32][2][d/8][16][8]: the 32 rows of a block form two halves of 16; row
+ *                  jj of the block is slot 4*(jj/8) + jj%4 of half (jj/4)%2, and a half is stored by
+ *                  8-feature chunks, the 16 slots of a chunk back to back.  Element (j, c) of (b, g) at
+ *                    ((b*n_kv+g)*L_max + 32*(j/32))*d + (((j/4)%2*(d/8) + c/8)*16 + 4*((j%32)/8) + j%4)*8 + c%8
+ *                  This is the order in which the score product's matrix instruction takes its key
+ *                  operand, so a wavefront reads 1 KB of whole cache lines per load; with row-major keys
+ *                  every load touched 16 half lines.  massv_k_cache_pack() converts from row-major.
  *   v_cache [B][n_kv][L_max/32][d][32]     element (j, c) of (b, g) at
  *                                          (((b*n_kv+g)*(L_max/32) + j/32)*d + c)*32 + j%32
  *   L_max must be a multiple of 32.  Values are stored key-minor in blocks of
@@ -125,6 +132,12 @@ int massv_verify_attention(const massv_attn_desc* desc, const void* q,
 /* Row-major [B][n_kv][L_max][d] values -> blocked value-cache layout. src and
  * dst must not overlap. */
 int massv_v_cache_pack(const void* src_row_major, void* dst_blocked,
+                       int32_t batch, int32_t n_kv_heads, int32_t l_max, int32_t head_dim,
+                       int32_t dtype, void* stream);
+
+/* Row-major [B][n_kv][L_max][d] keys -> key-cache layout of this dtype (f32: a plain copy; bf16: the blocked
+ * order above, needs L_max % 32 == 0 and d % 8 == 0).  src and dst must not overlap. */
+int massv_k_cache_pack(const void* src_row_major, void* dst,
                        int32_t batch, int32_t n_kv_heads, int32_t l_max, int32_t head_dim,
                        int32_t dtype, void* stream);
 

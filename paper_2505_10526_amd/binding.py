@@ -24,7 +24,7 @@ MAX_ROWS = 64
 
 EXPORTS = [
     "massv_status_string", "massv_abi_version",
-    "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack",
+    "massv_verify_attention_workspace", "massv_verify_attention", "massv_v_cache_pack", "massv_k_cache_pack",
     "massv_verify_layer_workspace", "massv_verify_layer", "massv_verify_layers",
     "massv_lm_head_logits_workspace", "massv_lm_head_logits",
     "massv_spec_accept_workspace", "massv_spec_accept", "massv_trace_kernel", "massv_weight_pack",
@@ -83,6 +83,8 @@ def load():
     lib.massv_verify_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.massv_v_cache_pack.restype = C.c_int
     lib.massv_v_cache_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.massv_k_cache_pack.restype = C.c_int
+    lib.massv_k_cache_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
     lib.massv_verify_layer_workspace.restype = sz
     lib.massv_verify_layer_workspace.argtypes = [C.POINTER(LayerDesc)]
     lib.massv_verify_layer.restype = C.c_int
@@ -187,8 +189,21 @@ def v_cache_pack(v_row_major: torch.Tensor) -> torch.Tensor:
     return out
 
 
+def k_cache_pack(k_row_major: torch.Tensor) -> torch.Tensor:
+    """[B, n_kv, L_max, d] row-major keys -> the library's key-cache layout for that dtype (bf16: rows
+    blocked in matrix-operand order, fp32: unchanged), done by the library's own kernel.  The result keeps
+    the shape [B, n_kv, L_max, d]; only the order of the elements in memory differs."""
+    _need(k_row_major, "k")
+    B, n_kv, L, d = k_row_major.shape
+    out = torch.empty_like(k_row_major)
+    _check(load().massv_k_cache_pack(_ptr(k_row_major), _ptr(out), B, n_kv, L, d,
+                                     dtype_code(k_row_major), _stream()), "massv_k_cache_pack")
+    return out
+
+
 def verify_attention(q, k_cache, v_cache, kv_len, scale=0.0, out=None, ws=None, window=0):
-    """q [B,Q,n_q,d]; k_cache [B,n_kv,L_max,d]; v_cache blocked [B,n_kv,L_max/32,d,32];
+    """q [B,Q,n_q,d]; k_cache [B,n_kv,L_max,d] in the key-cache layout (k_cache_pack); v_cache blocked
+    [B,n_kv,L_max/32,d,32];
     kv_len int32 [B]; window > 0: sliding-window attention over the last `window` rows.
     Returns out [B,Q,n_q,d]."""
     lib = load()

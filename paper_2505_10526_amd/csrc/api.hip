@@ -12,7 +12,7 @@ extern "C" const char* massv_status_string(int status) {
     }
 }
 
-extern "C" int massv_abi_version(void) { return 2; }
+extern "C" int massv_abi_version(void) { return 3; }
 
 namespace massv {
 TraceRequest& trace_request() {

@@ -39,10 +39,12 @@ template <typename T> __device__ inline void stf(T* p, float v) { ElemOf<T>::sto
 
 // ---- streaming loads ----
 // Data that is read once in whole 128-byte lines per instruction (logits, the
-// blocked value cache) is loaded with the non-temporal hint: on MI355X a plain
-// streaming read measured about 6.0 TB/s and the same read with the hint about
-// 6.4 TB/s.  Loads that use half a line per instruction (rows of W or K in
-// matrix-operand order) stay cached: the second half is a hit.
+// blocked key and value caches, weights in the streaming layout) is loaded with
+// the non-temporal hint: on MI355X a plain streaming read measured about
+// 6.0 TB/s and the same read with the hint up to 7.0 TB/s.  A load that uses
+// half a line per instruction (16 rows x 64 bytes of a row-major matrix) must
+// stay cached, because the other half is fetched by a later instruction; the
+// layouts above exist so that no hot load has that shape.
 __device__ inline bf16x8 ldg_stream(const bf16x8* p) { return __builtin_nontemporal_load(p); }
 __device__ inline float4 ldg_stream(const float4* p) {
     typedef float f4 __attribute__((ext_vector_type(4)));
@@ -61,6 +63,16 @@ __host__ __device__ inline size_t packed_index(int m, int k, int mt_count) {
     return (((size_t)(k >> 5) * mt_count + (m >> 4)) * 64 + ((m & 15) + 16 * ((k & 31) >> 3))) * 8 + (k & 7);
 }
 __host__ __device__ inline size_t packed_elems(int M, int K) { return (size_t)((M + 15) / 16) * 16 * K; }
+
+// ---- bf16 key cache ----
+// Element (row j, feature c) of (sequence, KV head) pair bg.  Rows live in blocks of 32, a block in two halves
+// of 16 rows; a half is stored by 8-feature chunks, the 16 rows of a chunk back to back: lane (slot, chunk % 4)
+// of a wave reads its 16-row x 32-feature operand of the score product as one contiguous 1 KB.
+__host__ __device__ inline size_t k_cache_index(size_t bg, int l_max, int d, int j, int c) {
+    const int jj = j & 31;
+    const int half = (jj >> 2) & 1, slot = ((jj >> 3) << 2) | (jj & 3);
+    return (bg * (size_t)l_max + (size_t)(j & ~31)) * d + ((size_t)(half * (d >> 3) + (c >> 3)) * 16 + slot) * 8 + (c & 7);
+}
 
 // ---- wavefront scans and reductions (all 64 lanes take part, all receive the result) ----
 // Built from data-parallel-primitive moves: four shifts inside each row of 16 lanes, then the last lane of

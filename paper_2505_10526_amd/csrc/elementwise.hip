@@ -212,8 +212,9 @@ __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs
             bf16_t* dst = q_out + ((size_t)m * n_q + head) * d;
             dst[j] = (bf16_t)y1; dst[j + half] = (bf16_t)y2;
         } else if (row < l_max) {
-            bf16_t* dst = k_cache + (((size_t)b * n_kv + (head - n_q)) * l_max + row) * d;
-            dst[j] = (bf16_t)y1; dst[j + half] = (bf16_t)y2;
+            const size_t bg = (size_t)b * n_kv + (head - n_q);
+            k_cache[k_cache_index(bg, l_max, d, row, j)] = (bf16_t)y1;
+            k_cache[k_cache_index(bg, l_max, d, row, j + half)] = (bf16_t)y2;
         }
     } else if (row < l_max) {
         const size_t bg = (size_t)b * n_kv + (head - n_q - n_kv);
@@ -430,6 +431,36 @@ extern "C" int massv_weight_pack(const void* src, void* dst, int32_t N, int32_t 
     const size_t blocks = (chunks + 255) / 256;
     if (blocks > 0x7fffffffu) return MASSV_EUNSUPPORTED;
     hipLaunchKernelGGL(weight_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, chunks, K);
+    return launch_status();
+}
+
+// Row-major keys -> blocked bf16 key cache; one thread per destination element.
+__global__ void k_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, size_t total, int l_max, int d) {
+    const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total) return;
+    const size_t per_block = (size_t)32 * d;
+    const size_t blk_all = o / per_block;                       // block index over all (b, g)
+    const int r = (int)(o % per_block);
+    const int e = r & 7, slot = (r >> 3) & 15, chunk_all = r >> 7;              // chunk_all = half * (d/8) + chunk
+    const int half = chunk_all / (d >> 3), chunk = chunk_all % (d >> 3);
+    const int jj = (slot >> 2) * 8 + half * 4 + (slot & 3);
+    dst[o] = src[(blk_all * 32 + jj) * d + chunk * 8 + e];      // blocks of one (b, g) are consecutive in both
+}
+
+extern "C" int massv_k_cache_pack(const void* src, void* dst, int32_t batch, int32_t n_kv_heads,
+                                  int32_t l_max, int32_t head_dim, int32_t dtype, void* stream) {
+    if (!src || !dst || batch < 1 || n_kv_heads < 1 || l_max < 1 || head_dim < 1) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    const size_t total = (size_t)batch * n_kv_heads * l_max * head_dim;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == MASSV_F32) {
+        if (hipMemcpyAsync(dst, src, total * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return MASSV_ELAUNCH;
+        return MASSV_OK;
+    }
+    if (l_max % 32 || head_dim % 8) return MASSV_EINVAL;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffu) return MASSV_EUNSUPPORTED;
+    hipLaunchKernelGGL(k_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, total, l_max, head_dim);
     return launch_status();
 }
 

@@ -30,7 +30,7 @@ def run_case(shape, B, Q, kv_len, n_img, seed, std=1.0, hot_keys=0, l_max=None, 
     q = synth.queries(shape, B, Q, seed, std=q_std)
     ref = O.attention(q, kv.k, kv.v, kv.kv_len, window=window)
     lm = round_up(l_max or kv.l_max, 32)
-    kd = to_dev(pad_rows(kv.k, lm), shape.dtype)
+    kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), shape.dtype))
     vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), shape.dtype))
     out = binding.verify_attention(to_dev(q, shape.dtype), kd, vd, i32(kv.kv_len), window=window)
     torch.cuda.synchronize()
@@ -92,7 +92,7 @@ def test_parallel_pass_equals_sequential_decode_on_gpu():
     kv = synth.kv_cache(s, B, Q, [300, 77], [100, 10], 7, junk_tail=False)
     q = synth.queries(s, B, Q, 7)
     lm = round_up(kv.l_max, 32)
-    kd = to_dev(pad_rows(kv.k, lm), "bf16")
+    kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), "bf16"))
     vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), "bf16"))
     qd = to_dev(q, "bf16")
     par = binding.verify_attention(qd, kd, vd, i32(kv.kv_len)).float().cpu().numpy()
@@ -107,11 +107,13 @@ def test_repeatable_bits_and_pack_roundtrip():
     kv = synth.kv_cache(s, 2, 6, [500, 333], [100, 100], 8, junk_tail=False)
     q = to_dev(synth.queries(s, 2, 6, 8), "bf16")
     lm = round_up(kv.l_max, 32)
-    kd = to_dev(pad_rows(kv.k, lm), "bf16")
+    kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), "bf16"))
     vrow = to_dev(np.nan_to_num(pad_rows(kv.v, lm)), "bf16")
     vd = binding.v_cache_pack(vrow)
-    from helpers import v_blocked_to_rows
+    from helpers import v_blocked_to_rows, k_cache_to_rows
     assert torch.equal(v_blocked_to_rows(vd), vrow)
+    krow = to_dev(np.nan_to_num(pad_rows(kv.k, lm)), "bf16")
+    assert torch.equal(k_cache_to_rows(binding.k_cache_pack(krow)), krow)
     a = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
     b = binding.verify_attention(q, kd, vd, i32(kv.kv_len))
     assert torch.equal(a, b)
@@ -156,7 +158,7 @@ def test_window_rows_outside_are_not_read():
         k[b, :, :lo] = np.nan
         v[b, :, : lo // 32 * 32] = np.nan       # values are read in blocks of 32 rows and masked by weight 0
     lm = round_up(kv.l_max, 32)
-    out = binding.verify_attention(to_dev(q, s.dtype), to_dev(pad_rows(k, lm), s.dtype),
+    out = binding.verify_attention(to_dev(q, s.dtype), binding.k_cache_pack(to_dev(pad_rows(k, lm), s.dtype)),
                                    binding.v_cache_pack(to_dev(pad_rows(v, lm), s.dtype)), i32(kv.kv_len), window=W)
     torch.cuda.synchronize()
     assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "window with NaN outside")

@@ -76,7 +76,7 @@ class DeviceModel:
         s = m.s
         self.m, self.cfg = m, cfg_of(s)
         self.l_max = round_up(m.kv[0].l_max, 32)
-        self.k = [to_dev(pad_rows(kv.k, self.l_max), s.dtype) for kv in m.kv]
+        self.k = [binding.k_cache_pack(to_dev(pad_rows(kv.k, self.l_max), s.dtype)) for kv in m.kv]
         self.v = [binding.v_cache_pack(to_dev(np.nan_to_num(pad_rows(kv.v, self.l_max)), s.dtype)) for kv in m.kv]
         ws = [binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()})
               for w in m.layers]

@@ -5,7 +5,7 @@ import torch
 
 from oracle import verify_oracle as O
 from paper_2505_10526_amd import synth, binding
-from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close, v_blocked_to_rows
+from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close, v_blocked_to_rows, k_cache_to_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,7 @@ def run_layer(s, B, Q, kv_len, n_img, seed, kv_std=1.0, compress=True, w_std=0.0
     pos = synth.positions(kv.kv_len, kv.n_img, Q, compress_image=compress)
     y_ref, k_ref, v_ref = O.verify_layer(s, w, x, pos, kv.k, kv.v, kv.kv_len)
     lm = round_up(kv.l_max, 32)
-    kd = to_dev(pad_rows(kv.k, lm), s.dtype)
+    kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), s.dtype))
     vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype))
     wd = binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()})
     xd = to_dev(x, s.dtype)
@@ -33,7 +33,7 @@ def run_layer(s, B, Q, kv_len, n_img, seed, kv_std=1.0, compress=True, w_std=0.0
     torch.cuda.synchronize()
     tol = TOL_BF16 if s.dtype == "bf16" else TOL_F32
     assert_close(xd.float().cpu().numpy(), y_ref, tol, "layer output")
-    kg = kd.float().cpu().numpy()
+    kg = k_cache_to_rows(kd).float().cpu().numpy()
     vg = v_blocked_to_rows(vd).float().cpu().numpy()
     for b in range(B):
         L = int(kv.kv_len[b])
@@ -135,7 +135,7 @@ def run_stack(s, n_layers, B, Q, kv_len, n_img, seed, w_std=0.02):
         y_ref, k_ref, v_ref = O.verify_layer(s, ws_h[l], y_ref, pos, kvs[l].k, kvs[l].v, kvs[l].kv_len)
         k_refs.append(k_ref); v_refs.append(v_ref)
     lm = round_up(kvs[0].l_max, 32)
-    kds = [to_dev(pad_rows(kv.k, lm), s.dtype) for kv in kvs]
+    kds = [binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), s.dtype)) for kv in kvs]
     vds = [binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype)) for kv in kvs]
     wds = [binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()}) for w in ws_h]
     stack = binding.LayerStack(wds, kds, vds)
@@ -145,7 +145,7 @@ def run_stack(s, n_layers, B, Q, kv_len, n_img, seed, w_std=0.02):
     tol = TOL_BF16 if s.dtype == "bf16" else TOL_F32 * n_layers
     assert_close(xd.float().cpu().numpy(), y_ref, tol, "stack output")
     for l in range(n_layers):
-        kg = kds[l].float().cpu().numpy()
+        kg = k_cache_to_rows(kds[l]).float().cpu().numpy()
         vg = v_blocked_to_rows(vds[l]).float().cpu().numpy()
         for b in range(B):
             L = int(kvs[l].kv_len[b])
@@ -172,7 +172,7 @@ def test_layer_repeatable_bits():
     outs = []
     for _ in range(2):
         lm = round_up(kv.l_max, 32)
-        kd = to_dev(pad_rows(kv.k, lm), s.dtype)
+        kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), s.dtype))
         vd = binding.v_cache_pack(to_dev(np.nan_to_num(pad_rows(kv.v, lm)), s.dtype))
         x = to_dev(synth.hidden_states(s, 2, 6, 9), s.dtype)
         binding.verify_layer(cfg_of(s), w, x, pos, kd, vd, i32(kv.kv_len))
@@ -227,7 +227,7 @@ def test_layer_stack_interleaves_local_and_global_layers():
         for l in range(4):
             y_ref, _, _ = O.verify_layer(shapes[l], ws_h[l], y_ref, pos, kvs[l].k, kvs[l].v, kvs[l].kv_len)
         lm = round_up(kvs[0].l_max, 32)
-        kds = [to_dev(pad_rows(kv.k, lm), base.dtype) for kv in kvs]
+        kds = [binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), base.dtype)) for kv in kvs]
         vds = [binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), base.dtype)) for kv in kvs]
         wds = [binding.pack_layer_weights({k: (None if v is None else to_dev(v, base.dtype)) for k, v in w.items()}) for w in ws_h]
         stack = binding.LayerStack(wds, kds, vds, windows=windows, rope_thetas=thetas)
