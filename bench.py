@@ -542,9 +542,10 @@ def extra_bandwidth(torch, binding, synth, dev, gen):
 
 
 def cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, seed):
-    """The CPU checker, as it stands, on a bounded sample of the same workload: ONE decoder layer
-    over all sequences, the vocabulary projection and the accept step; the layer's time is scaled
-    by the layer count."""
+    """The CPU checker, as it stands, on a bounded sample of the same workload: decoder-layer passes over all
+    sequences until about 10 s have gone by (at most the workload's layer count; one layer's synthetic weights
+    are reused, the arithmetic per pass is that of any layer), the vocabulary projection and the accept step.
+    The mean pass time is scaled by the layer count."""
     from oracle import verify_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -557,9 +558,13 @@ def cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, seed):
     kv = synth.kv_cache(shape, B, Q, kv_len_h, n_img_h, seed, junk_tail=False)
     x = synth.hidden_states(shape, B, Q, seed)
     pos = synth.positions(kv_len_h, n_img_h, Q)
-    t0 = time.perf_counter()
-    y, _, _ = O.verify_layer(shape, w, x, pos, kv.k, kv.v, kv.kv_len)
-    t_layer = time.perf_counter() - t0
+    t_layers, passes, y = 0.0, 0, x
+    while passes < N and t_layers < 10.0:
+        t0 = time.perf_counter()
+        y, _, _ = O.verify_layer(shape, w, y, pos, kv.k, kv.v, kv.kv_len)
+        t_layers += time.perf_counter() - t0
+        passes += 1
+    t_layer = t_layers / passes
     del w, kv
     lw = synth.lm_head_weights(shape, seed)
     t0 = time.perf_counter()
@@ -574,7 +579,7 @@ def cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, seed):
     t_step = N * t_layer + t_lm + t_acc
     return {"value": round(float((n + 1).sum()) / t_step, 3), "unit": "tokens/s", "cores": int(cores),
             "kind": "oracle",
-            "sample": f"1 of {N} layers (all {B} sequences) timed {t_layer:.2f}s and scaled x{N}, "
+            "sample": f"{passes} of {N} layer passes (all {B} sequences) timed {t_layers:.2f}s, mean scaled x{N}, "
                       f"+ lm_head {t_lm:.2f}s + accept {t_acc:.2f}s; float64 NumPy",
             "est_ms_per_step": round(t_step * 1e3, 1)}
 
