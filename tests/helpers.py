@@ -39,11 +39,13 @@ def v_blocked_to_rows(vb):
     return vb.permute(0, 1, 2, 4, 3).reshape(B, n, nb * kb, d)
 
 
-def k_cache_to_rows(kc):
+def k_cache_to_rows(kc, blocked=None):
     """Library key-cache layout (shape [B, n_kv, L, d]) -> row-major [B, n_kv, L, d] (host side, for checks).
     fp32 caches are row-major already; bf16 caches hold blocks of 32 rows as [half][d/8][slot 16][8] with
     row jj of a block = slot 4*(jj/8) + jj%4 of half (jj/4)%2."""
-    if kc.dtype != torch.bfloat16:
+    if blocked is None:
+        blocked = kc.dtype == torch.bfloat16
+    if not blocked:
         return kc
     B, n, L, d = kc.shape
     t = kc.reshape(B, n, L // 32, 2, d // 8, 4, 4, 8)          # [.., half, chunk, jj/8, jj%4, e]

@@ -109,6 +109,31 @@ def test_attention_argument_checks(lib):
     assert call(binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16, scale=-1.0)) == binding.EINVAL
 
 
+def test_cache_pack_argument_checks(lib):
+    for f in (lib.massv_k_cache_pack, lib.massv_v_cache_pack):
+        assert f(None, FAKE, 2, 4, 64, 128, binding.BF16, None) == binding.EINVAL
+        assert f(FAKE, None, 2, 4, 64, 128, binding.BF16, None) == binding.EINVAL
+        assert f(FAKE, FAKE, 0, 4, 64, 128, binding.BF16, None) == binding.EINVAL
+        assert f(FAKE, FAKE, 2, 4, 64, 128, 7, None) == binding.EINVAL
+        assert f(FAKE, FAKE, 2, 4, 70, 128, binding.BF16, None) == binding.EINVAL        # rows in blocks of 32
+    assert lib.massv_k_cache_pack(FAKE, FAKE, 2, 4, 64, 124, binding.BF16, None) == binding.EINVAL   # 8-feature chunks
+
+
+def test_key_cache_layout_formula():
+    """The element offset stated in the header for bf16 keys, written out here, against the un-blocking that the
+    GPU tests use to read a cache back (tests/helpers.py): both must describe the same permutation."""
+    import torch
+    from helpers import k_cache_to_rows
+    B, n_kv, L, d = 2, 3, 96, 64
+    rows = torch.arange(B * n_kv * L * d, dtype=torch.float32).reshape(B, n_kv, L, d)
+    packed = torch.empty(B * n_kv * L * d, dtype=torch.float32)
+    b, g, j, c = torch.meshgrid(torch.arange(B), torch.arange(n_kv), torch.arange(L), torch.arange(d), indexing="ij")
+    off = ((b * n_kv + g) * L + 32 * (j // 32)) * d + (((j // 4) % 2 * (d // 8) + c // 8) * 16 + 4 * ((j % 32) // 8) + j % 4) * 8 + c % 8
+    assert torch.equal(torch.sort(off.reshape(-1)).values, torch.arange(B * n_kv * L * d))      # a permutation
+    packed[off.reshape(-1)] = rows.reshape(-1)
+    assert torch.equal(k_cache_to_rows(packed.reshape(B, n_kv, L, d), blocked=True), rows)
+
+
 def test_negative_window_is_rejected(lib):
     d = binding.attn_desc(2, 6, 28, 4, 128, 2080, binding.BF16, window=-1)
     assert lib.massv_verify_attention_workspace(C.byref(d)) == 0
