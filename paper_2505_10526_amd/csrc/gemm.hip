@@ -325,16 +325,45 @@ int gemm_supported(const GemmArgs& g) {
     return MASSV_OK;
 }
 
+// Narrow outputs (fewer than 256 workgroups at full K): K is cut into slabs and the slab sums are left to the
+// row-wise kernel that follows.  Tiles per wave and slabs are chosen by an estimate of the launch plus its share of
+// that kernel, in microseconds, fitted to sweeps of the three split projections of the 7B-shaped layer (M = 48):
+//   weights at 6.5 TB/s, stretched when fewer than 256 workgroups pull them;
+//   X, re-read from L2 once per workgroup column: (T / nt) * K/32 * MT KB, at 14 TB/s;
+//   0.8 us per MB of partial sums (written here, read back by the next kernel).
+// Measured against the earlier rule "as many slabs as fill 256 workgroups, largest tile count": q/k/v (8 tiles, 7
+// slabs) -> (4, 3) -1.9 us, output projection (7, 7) -> (4, 4) -1.0 us, down projection (7, 8) unchanged.
+static GemmPlan plan_split(const GemmArgs& g, int mt, int T) {
+    GemmPlan best = {0, 1, 0};
+    const int n_steps = g.K / 32;
+    int max_slabs = n_steps / (4 * kGemmWaves); if (max_slabs < 1) max_slabs = 1; if (max_slabs > 32) max_slabs = 32;
+    const double w_us = (double)n_total(g) * g.K * 2.0 / 6.5e6;
+    const double slab_us = (double)(mt * 16) * n_total(g) * 4.0 / 1e6 * 0.8;
+    static const int cand[] = {8, 7, 4};
+    double best_t = 1e30;
+    for (int nt : cand) {
+        if (mt == 4 && nt > 4) continue;                       // register budget of four row tiles
+        const int groups = (T + nt - 1) / nt;
+        if (groups >= kCUs) continue;
+        const double x_us = (double)groups * n_steps * mt * 1024.0 / 1e6 * 0.07;
+        for (int slabs = 1; slabs <= max_slabs && groups * slabs <= kCUs; ++slabs) {
+            const double t = w_us * (1.0 + 0.44 * ((double)kCUs / (groups * slabs) - 1.0)) + x_us + slabs * slab_us;
+            if (t < best_t) { best_t = t; best.nt = nt; best.slabs = slabs; best.groups = groups; }
+        }
+    }
+    return best;
+}
+
 // Tiles per wave and K slabs for one launch.  T: 16-feature tiles to produce.
 //   wide output  (>= 256 groups): slabs = 1, NT chosen so that the last round of workgroups is as full as possible;
-//   narrow output: K is cut into slabs (at least four 32-steps per wave each) so that groups*slabs approaches 256;
-//   the kernel deals the K/32 steps evenly over the slabs.
+//   narrow output with the partial-sum epilogue: plan_split; the kernel deals the K/32 steps evenly over the slabs.
 GemmPlan gemm_plan(const GemmArgs& g) {
     GemmPlan best = {0, 1, 0};
     if (g.dtype != MASSV_BF16) return best;
     const int mt = (g.M + 15) / 16;
     const int T = (g.epilogue == EPI_GATED) ? 2 * (g.n[0] / 16) : n_total(g) / 16;
     const int n_chunks = (g.K + 127) / 128;
+    if (g.epilogue == EPI_PARTIAL && (T + 3) / 4 < kCUs) return plan_split(g, mt, T);
     static const int cand_partial[] = {8, 7, 4}, cand_gated[] = {10, 8, 4}, cand_logits[] = {10, 8, 4};
     const int* cand = g.epilogue == EPI_GATED ? cand_gated : (g.epilogue == EPI_LOGITS || g.epilogue == EPI_ARGMAX) ? cand_logits : cand_partial;
     double best_score = -1.0;
