@@ -81,10 +81,11 @@ __device__ inline bf16x8 ld8_stream(const bf16_t* p, bool ok) {      // weights:
 }
 
 
-// Tiles of LDS reduced per round: at most 48 KB of fp32 fragments at a time.
+// Tiles of LDS reduced per round: at most 128 KB of fp32 fragments at a time -- one round for every shape built
+// (10 tiles x 3 row tiles x 4 waves = 120 KB); rounds of 48 KB cost two more barrier pairs per launch.
 template <int MT, int NT>
 struct ReduceGroup {
-    static constexpr int kMax = 48 / (MT * kGemmWaves);
+    static constexpr int kMax = 128 / (MT * kGemmWaves);
     static constexpr int raw = (NT < kMax) ? NT : kMax;
     static constexpr int value = (raw >= 2) ? (raw / 2) * 2 : 1;     // even, so gate/up pairs stay together
 };
@@ -402,19 +403,30 @@ size_t gemm_partial_bytes(const GemmArgs& g) {
 }
 
 template <int MT, int NT, int EPI>
-static void launch_stream(const GemmDev& d, const GemmPlan& p, int kid, hipStream_t st) {
+static int launch_stream(const GemmDev& d, const GemmPlan& p, int kid, hipStream_t st) {
     constexpr int GRP = ReduceGroup<MT, NT>::value;
     const size_t lds = (size_t)kGemmWaves * GRP * MT * kWave * sizeof(floatx4);
+    if (lds > 48 * 1024) {                       // more dynamic LDS than a kernel may use by default
+        static bool ready[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
+        if (!ready[dev]) {
+            if (hipFuncSetAttribute((const void*)gemm_stream_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds) != hipSuccess) return MASSV_ELAUNCH;
+            ready[dev] = true;
+        }
+    }
     launch_traced(kid, gemm_stream_kernel<MT, NT, EPI>, dim3(p.groups, p.slabs), dim3(kGemmWaves * kWave), lds, st, d);
+    return MASSV_OK;
 }
 
 template <int MT, int EPI>
 static int launch_stream_nt(const GemmDev& d, const GemmPlan& p, int kid, hipStream_t st) {
     switch (p.nt) {
-        case 4: launch_stream<MT, 4, EPI>(d, p, kid, st); return MASSV_OK;
-        case 7: if constexpr (EPI == EPI_PARTIAL && MT <= 3) { launch_stream<MT, 7, EPI>(d, p, kid, st); return MASSV_OK; } break;
-        case 8: if constexpr (MT <= 3) { launch_stream<MT, 8, EPI>(d, p, kid, st); return MASSV_OK; } break;
-        case 10: if constexpr (EPI != EPI_PARTIAL && MT <= 3) { launch_stream<MT, 10, EPI>(d, p, kid, st); return MASSV_OK; } break;
+        case 4: return launch_stream<MT, 4, EPI>(d, p, kid, st);
+        case 7: if constexpr (EPI == EPI_PARTIAL && MT <= 3) return launch_stream<MT, 7, EPI>(d, p, kid, st); break;
+        case 8: if constexpr (MT <= 3) return launch_stream<MT, 8, EPI>(d, p, kid, st); break;
+        case 10: if constexpr (EPI != EPI_PARTIAL && MT <= 3) return launch_stream<MT, 10, EPI>(d, p, kid, st); break;
     }
     return MASSV_EUNSUPPORTED;
 }
