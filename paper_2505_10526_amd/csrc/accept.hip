@@ -23,7 +23,8 @@
 
 namespace massv {
 
-constexpr int kAccThreads = 256;                          // 4 waves, one chunk each
+constexpr int kAccThreads = 128;                          // 2 waves, one chunk each (64: 73 us, 128: 66 us, 256: 67 us,
+                                                          // 1024: 75 us for the sampling call on the long-context shape)
 constexpr int kAccPerLane = 16;                           // 4 float4 loads per lane
 constexpr int kAccChunk = kWave * kAccPerLane;            // 1024 logits per wave
 constexpr int kMaxGamma = 15;
@@ -485,13 +486,13 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
                     (greedy || (uintptr_t)draft_logits % 16 == 0);
     const int rows = greedy ? B * Q : B * (Q + gamma);
 
-    launch_traced(MASSV_K_ACCEPT_STATS, accept_stats_kernel, dim3((C + 3) / 4, rows), dim3(kAccThreads), 0, st,
+    launch_traced(MASSV_K_ACCEPT_STATS, accept_stats_kernel, dim3((C + kAccThreads / kWave - 1) / (kAccThreads / kWave), rows), dim3(kAccThreads), 0, st,
                   target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
                        target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
                        ts.hi, greedy, part, sel, n_accepted, out_tokens);
     if (!greedy) {
-        launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + 3) / 4, B), dim3(kAccThreads), 0, st,
+        launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + kAccThreads / kWave - 1) / (kAccThreads / kWave), B), dim3(kAccThreads), 0, st,
                       target_logits, draft_logits, gamma, V, C, ts, vec, (const SeqSel*)sel, mass);
         hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kWave), 0, st,
                            target_logits, draft_logits, uniforms, gamma, V, C, ts, vec, sel, mass, out_tokens);
