@@ -159,7 +159,8 @@ int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_le
 
 // bf16 path: the q/k/v projection leaves fp32 partial sums per K slab; this kernel sums them, adds the
 // bias, optionally normalises the query / key head, applies the rotary embedding and scatters q / k / v.
-// Same grid as rope_append_kernel.
+// Grid (heads, rows): consecutive workgroups read adjacent pieces of one row of partial sums (with rows as the
+// fast index the 28-layer step measured 11 us slower).
 __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
                                   const bf16_t* __restrict__ bq, const bf16_t* __restrict__ bk,
                                   const bf16_t* __restrict__ bv, const int32_t* __restrict__ pos,
@@ -167,7 +168,7 @@ __global__ void qkv_finish_kernel(const float* __restrict__ partial, int n_slabs
                                   bf16_t* __restrict__ k_cache, bf16_t* __restrict__ v_cache,
                                   const bf16_t* __restrict__ q_norm, const bf16_t* __restrict__ k_norm, float eps,
                                   int Q, int n_q, int n_kv, int d, int l_max, double log2_theta) {
-    const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
+    const int m = blockIdx.y, head = blockIdx.x, j = threadIdx.x;
     const int half = d / 2;
     const bf16_t* hn = head < n_q ? q_norm : head < n_q + n_kv ? k_norm : nullptr;
     if (j >= half && !hn) return;                        // with a head norm every thread reaches the block sum
@@ -228,7 +229,7 @@ int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, con
                       void* v_cache, const void* q_norm, const void* k_norm, float eps,
                       const massv_attn_desc& a, float theta, hipStream_t st) {
     const int M = a.batch * a.n_query;
-    dim3 grid(M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
+    dim3 grid(a.n_q_heads + 2 * a.n_kv_heads, M), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
     hipLaunchKernelGGL(qkv_finish_kernel, grid, block, 0, st, partial, n_slabs, slab_stride, (const bf16_t*)bq,
                        (const bf16_t*)bk, (const bf16_t*)bv, pos, kv_len, (bf16_t*)q_out, (bf16_t*)k_cache,
                        (bf16_t*)v_cache, (const bf16_t*)q_norm, (const bf16_t*)k_norm, eps,
