@@ -107,7 +107,11 @@ void gemm_stream_kernel(GemmDev g) {
     // a unit is one tile (a gate/up tile pair for the gated epilogue); units are dealt to the workgroups
     // as evenly as possible, so a workgroup may own fewer than its NT tile slots
     constexpr int UT = gated ? 2 : 1;
-    const int bx = blockIdx.x;
+    // split-K launches: the slab is the fast grid index, so that the workgroups of one slab -- which read the same
+    // piece of X -- have linear indices that are congruent modulo the slab count and fall on the same XCDs
+    constexpr bool SLAB_FAST = (EPI == EPI_PARTIAL);
+    const int bx = SLAB_FAST ? blockIdx.y : blockIdx.x;
+    const int n_slabs = SLAB_FAST ? gridDim.x : gridDim.y;
     const int unit0 = bx * g.unit_base + (bx < g.unit_rem ? bx : g.unit_rem);
     const int n_units = g.unit_base + (bx < g.unit_rem ? 1 : 0);
 #pragma unroll
@@ -142,8 +146,8 @@ void gemm_stream_kernel(GemmDev g) {
     // a slab the waves take chunks of four steps in turn (so the workgroup reads contiguous 16 KB runs of a tile), and
     // the last, incomplete round of 16 steps is split evenly: no wave does more than one step above the average.
     const int n_steps = K / 32;
-    const int sb = n_steps / (int)gridDim.y, sr = n_steps % (int)gridDim.y;
-    const int by = blockIdx.y;
+    const int sb = n_steps / n_slabs, sr = n_steps % n_slabs;
+    const int by = SLAB_FAST ? blockIdx.x : blockIdx.y;
     const int s_begin = by * sb + (by < sr ? by : sr);
     const int s_count = sb + (by < sr ? 1 : 0);
     const int rounds = s_count / (4 * WK);
@@ -235,7 +239,7 @@ void gemm_stream_kernel(GemmDev g) {
                     for (int i = 0; i < 4; ++i)                   // ascending columns: a tie keeps the lower one
                         if (s[i] > best_v[mt] || (s[i] == best_v[mt] && col + i < best_i[mt])) { best_v[mt] = s[i]; best_i[mt] = col + i; }
                 } else if (m < g.M) {
-                    float* dst = (float*)g.y + (EPI == EPI_PARTIAL ? (size_t)blockIdx.y * g.slab_stride : 0) +
+                    float* dst = (float*)g.y + (EPI == EPI_PARTIAL ? (size_t)by * g.slab_stride : 0) +
                                  (size_t)m * g.ldy + col;
                     *reinterpret_cast<floatx4*>(dst) = s;
                 }
@@ -416,7 +420,8 @@ static int launch_stream(const GemmDev& d, const GemmPlan& p, int kid, hipStream
             ready[dev] = true;
         }
     }
-    launch_traced(kid, gemm_stream_kernel<MT, NT, EPI>, dim3(p.groups, p.slabs), dim3(kGemmWaves * kWave), lds, st, d);
+    const dim3 grid = (EPI == EPI_PARTIAL) ? dim3(p.slabs, p.groups) : dim3(p.groups, p.slabs);
+    launch_traced(kid, gemm_stream_kernel<MT, NT, EPI>, grid, dim3(kGemmWaves * kWave), lds, st, d);
     return MASSV_OK;
 }
 
