@@ -341,7 +341,7 @@ int gemm_supported(const GemmArgs& g) {
 static GemmPlan plan_split(const GemmArgs& g, int mt, int T) {
     GemmPlan best = {0, 1, 0};
     const int n_steps = g.K / 32;
-    int max_slabs = n_steps / (4 * kGemmWaves); if (max_slabs < 1) max_slabs = 1; if (max_slabs > 32) max_slabs = 32;
+    int max_slabs = n_steps / kGemmWaves; if (max_slabs < 1) max_slabs = 1; if (max_slabs > 32) max_slabs = 32;   // a step per wave at least
     const double w_us = (double)n_total(g) * g.K * 2.0 / 6.5e6;
     const double slab_us = (double)(mt * 16) * n_total(g) * 4.0 / 1e6 * 0.8;
     static const int cand[] = {8, 7, 4};
