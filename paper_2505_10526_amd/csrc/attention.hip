@@ -234,19 +234,8 @@ void attention_mfma_kernel(AttnParams p) {
     //     block needs no cross-lane maximum and no rescaling of the output accumulators.  The result
     //     acc / l does not depend on which reference is used.
     constexpr float kLazy = 8.0f;
-    auto process_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
-        const bool tail = (blk + 1) * kBlk > n_total;         // block reaches past the valid rows
-        if (tail) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (blk * kBlk + lc * 8 + e >= n_total) vreg[nt][e] = (bf16_t)0.f;
-        }
-        const bool masked = blk >= first_masked_blk || blk * kBlk < low_mask_end;
-
-        // ---- S^T tile pairs: lane holds keys 8 lc + (0..7) of query row 16 mt + lr ----
-        floatx4 s0[MT], s1[MT];
+    // Score product of one block: S^T tile pairs, lane holds keys 8 lc + (0..7) of query row 16 mt + lr.
+    auto block_scores = [&](bf16x8 (&kreg)[2][KS], floatx4 (&s0)[MT], floatx4 (&s1)[MT]) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) { s0[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; s1[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
@@ -257,6 +246,18 @@ void attention_mfma_kernel(AttnParams p) {
                 s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qv, s0[mt], 0, 0, 0);
                 s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qv, s1[mt], 0, 0, 0);
             }
+    };
+    // Mask, streaming softmax and O^T += V^T P^T of one block, from its scores.
+    auto block_finish = [&](int blk, floatx4 (&s0)[MT], floatx4 (&s1)[MT], bf16x8 (&vreg)[NT]) {
+        const bool tail = (blk + 1) * kBlk > n_total;         // block reaches past the valid rows
+        if (tail) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (blk * kBlk + lc * 8 + e >= n_total) vreg[nt][e] = (bf16_t)0.f;
+        }
+        const bool masked = blk >= first_masked_blk || blk * kBlk < low_mask_end;
 
         bf16x8 pv[MT];
 #pragma unroll
@@ -301,6 +302,12 @@ void attention_mfma_kernel(AttnParams p) {
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[nt], pv[mt], acc[mt][nt], 0, 0, 0);
     };
 
+    auto process_block = [&](int blk, bf16x8 (&kreg)[2][KS], bf16x8 (&vreg)[NT]) {
+        floatx4 s0[MT], s1[MT];
+        block_scores(kreg, s0, s1);
+        block_finish(blk, s0, s1, vreg);
+    };
+
     // The wave's blocks are blk_begin + wave, + 4, ...; the loads of the next one are in flight while
     // the current one is processed (two register sets), unless the tile shape leaves no registers.
     if constexpr (PREFETCH) {
@@ -318,6 +325,22 @@ void attention_mfma_kernel(AttnParams p) {
                 for (int ks = 0; ks < KS; ++ks) kc[t][ks] = kn[t][ks];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) vc[nt] = vn[nt];
+        }
+    } else if constexpr (D <= 128) {
+        // One register set, refilled in halves: the key registers are free once the scores are formed, so the next
+        // block's keys are requested before the softmax and the second product; its values right after that
+        // (long-context shape 91.9 -> 90.9 us; at d = 256 the longer live ranges spill, so that shape keeps the
+        // plain loop below).
+        bf16x8 k0[2][KS], v0[NT];
+        int blk = blk_begin + wave;
+        if (blk < blk_end) load_block(blk, k0, v0);
+        for (; blk < blk_end; blk += kAttnWaves) {
+            const int nb = blk + kAttnWaves;
+            floatx4 s0[MT], s1[MT];
+            block_scores(k0, s0, s1);
+            if (nb < blk_end) load_k(nb, k0);
+            block_finish(blk, s0, s1, v0);
+            if (nb < blk_end) load_v(nb, v0);
         }
     } else {
         bf16x8 k0[2][KS], v0[NT];
