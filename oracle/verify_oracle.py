@@ -299,7 +299,8 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
     """Sequential accept / reject / resample for every sequence of the batch.
 
     target_logits [B, gamma+1, V], draft_logits [B, gamma, V] (ignored at T=0),
-    draft_tokens [B, gamma], uniforms [B, gamma+1] (ignored at T=0).  gamma = 0
+    draft_tokens [B, gamma] (a value outside [0, V) is rejected at either
+    temperature), uniforms [B, gamma+1] (ignored at T=0).  gamma = 0
     is the drafting loop's own sampling step: one token drawn from the single
     row's distribution, nothing to verify.
     Returns n_accepted [B] int32, out_tokens [B, gamma+1] int32 (accepted
@@ -325,7 +326,9 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
         n = 0
         for i in range(gamma):
             tok = int(x[b, i])
-            if greedy:
+            if not (0 <= tok < V):
+                ok = False          # not a token of the vocabulary: p_i and q_i are not defined for it
+            elif greedy:
                 ok = (tok == first_argmax(t[b, i]))
             else:
                 p = softmax(t[b, i] / temperature)[tok]

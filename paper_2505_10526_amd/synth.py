@@ -29,8 +29,11 @@ def bf16_representable(a: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bfloat16 (ties to even), keep float32."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     u = a.view(np.uint32)
-    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
-    r = (u + bias) & np.uint32(0xFFFF0000)
+    r = u >> np.uint32(16)                   # one temporary, updated in place (the big weight matrices are ~1 GB each)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r &= np.uint32(0xFFFF0000)
     return r.view(np.float32).reshape(a.shape)
 
 
@@ -96,7 +99,7 @@ def normal(shape, std, seed, *stream, dtype="bf16", mean=0.0):
     return _finish(a, dtype)
 
 
-def layer_weights(shape: LayerShape, seed: int, layer: int = 0, std: float = 0.02):
+def layer_weights(shape: LayerShape, seed: int, layer: int = 0, std: float = 0.02, threads: int = 1):
     """Weights of one decoder layer: every linear map N(0, std), norm gains near 1.
 
     Gains are 1 + 0.1 N(0,1) rather than exactly 1 so that a missing gain
@@ -105,28 +108,31 @@ def layer_weights(shape: LayerShape, seed: int, layer: int = 0, std: float = 0.0
     s, dt = shape, shape.dtype
     H, d = s.hidden, s.head_dim
     nq, nkv, F = s.n_q_heads * d, s.n_kv_heads * d, s.mlp
-    w = {
-        "ln1": normal((H,), 0.1, seed, layer, 0, dtype=dt, mean=1.0),
-        "wq": normal((nq, H), std, seed, layer, 1, dtype=dt),
-        "wk": normal((nkv, H), std, seed, layer, 2, dtype=dt),
-        "wv": normal((nkv, H), std, seed, layer, 3, dtype=dt),
-        "wo": normal((H, nq), std, seed, layer, 4, dtype=dt),
-        "ln2": normal((H,), 0.1, seed, layer, 5, dtype=dt, mean=1.0),
-        "wg": normal((F, H), std, seed, layer, 6, dtype=dt),
-        "wu": normal((F, H), std, seed, layer, 7, dtype=dt),
-        "wd": normal((H, F), std, seed, layer, 8, dtype=dt),
-        "bq": None, "bk": None, "bv": None,
+    # name -> (shape, std, stream id, mean); every tensor has its own random stream, so the draws are independent of
+    # the order (and of the number of threads) they are made in
+    spec = {
+        "ln1": ((H,), 0.1, 0, 1.0), "wq": ((nq, H), std, 1, 0.0), "wk": ((nkv, H), std, 2, 0.0),
+        "wv": ((nkv, H), std, 3, 0.0), "wo": ((H, nq), std, 4, 0.0), "ln2": ((H,), 0.1, 5, 1.0),
+        "wg": ((F, H), std, 6, 0.0), "wu": ((F, H), std, 7, 0.0), "wd": ((H, F), std, 8, 0.0),
     }
     if s.qkv_bias:
-        w["bq"] = normal((nq,), std, seed, layer, 9, dtype=dt)
-        w["bk"] = normal((nkv,), std, seed, layer, 10, dtype=dt)
-        w["bv"] = normal((nkv,), std, seed, layer, 11, dtype=dt)
+        spec.update(bq=((nq,), std, 9, 0.0), bk=((nkv,), std, 10, 0.0), bv=((nkv,), std, 11, 0.0))
     if s.qk_norm:
-        w["q_norm"] = normal((d,), 0.1, seed, layer, 12, dtype=dt, mean=1.0)
-        w["k_norm"] = normal((d,), 0.1, seed, layer, 13, dtype=dt, mean=1.0)
+        spec.update(q_norm=((d,), 0.1, 12, 1.0), k_norm=((d,), 0.1, 13, 1.0))
     if s.post_norms:
-        w["post_attn_norm"] = normal((H,), 0.1, seed, layer, 14, dtype=dt, mean=1.0)
-        w["post_mlp_norm"] = normal((H,), 0.1, seed, layer, 15, dtype=dt, mean=1.0)
+        spec.update(post_attn_norm=((H,), 0.1, 14, 1.0), post_mlp_norm=((H,), 0.1, 15, 1.0))
+
+    def draw(item):
+        name, (shp, sd, stream, mean) = item
+        return name, normal(shp, sd, seed, layer, stream, dtype=dt, mean=mean)
+
+    w = {"bq": None, "bk": None, "bv": None}
+    if threads > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(threads) as pool:
+            w.update(dict(pool.map(draw, sorted(spec.items(), key=lambda kv: -int(np.prod(kv[1][0]))))))
+    else:
+        w.update(dict(map(draw, spec.items())))
     return w
 
 

@@ -3,9 +3,15 @@ and uniforms (paper Section 2.1).  Integer outputs are compared bit-exactly.
 
 Where a floating-point comparison decides a token (the accept test u < p/q and
 the inverse-CDF draw) the checker reports how far that comparison was from
-flipping.  Sequences whose margin exceeds TOL must match exactly; for the few
-below it the GPU's choice must still be a valid answer once the threshold is
-moved by TOL (the neighbouring token of the cumulative distribution)."""
+flipping.  The kernels form exponentials in float and carry every deciding sum
+in double: cumulative masses are good to about 1e-6 of the total.  TOL is ten
+times that.  Seeds are chosen (with the checker alone, on the CPU) so that every
+accept comparison and -- for vocabularies up to 8192 and the large-vocabulary
+cases below unless stated -- every draw clears TOL; those must match exactly.
+A draw closer than TOL to a boundary of the cumulative distribution may fall on
+either side of it: the GPU's token must then be the checker's or the nearest
+token with non-zero mass next to it, and its own interval must hold the
+threshold once moved by TOL."""
 import numpy as np
 import pytest
 import torch
@@ -14,7 +20,7 @@ from oracle import verify_oracle as O
 from paper_2505_10526_amd import synth, binding
 
 pytestmark = pytest.mark.gpu
-TOL = 1e-4          # relative decision margin above which results must be identical
+TOL = 1e-5          # relative decision margin above which results must be identical
 
 
 def run_gpu(a, temperature):
@@ -29,7 +35,8 @@ def run_gpu(a, temperature):
     return n.cpu().numpy(), out.cpu().numpy()
 
 
-def check(a, temperature, min_exact=0.8):
+def check(a, temperature, min_exact=1.0):
+    """min_exact: fraction of the sequences whose draw must clear TOL (and is then compared exactly)."""
     temperature = float(np.float32(temperature))
     n_g, out_g = run_gpu(a, temperature)
     n_o, out_o, margin, masses = O.spec_accept(a.target_logits, a.draft_logits, a.draft_tokens, a.uniforms,
@@ -46,34 +53,48 @@ def check(a, temperature, min_exact=0.8):
         n = int(n_o[b])
         assert np.array_equal(out_g[b, :n], out_o[b, :n])
         assert np.all(out_g[b, n + 1:] == -1)
-        k = int(out_g[b, n])
+        k, k_o = int(out_g[b, n]), int(out_o[b, n])
         if margin[b, 1] > TOL:
-            assert k == out_o[b, n], (b, k, out_o[b, n], margin[b])
+            assert k == k_o, (b, k, k_o, margin[b])
             exact += 1
         else:
             r = masses[b]
+            nz = np.nonzero(r > 0)[0]
+            at = int(np.searchsorted(nz, k_o))
+            assert k in nz[max(at - 1, 0): at + 2], (b, k, k_o)       # the checker's token or its neighbour in mass
             c = np.cumsum(r)
             thr = float(a.uniforms[b, Q - 1]) * c[-1]
             lo = c[k - 1] if k > 0 else 0.0
-            assert 0 <= k < len(r) and r[k] > 0
-            assert lo - TOL * c[-1] <= thr <= c[k] + TOL * c[-1], (b, k, out_o[b, n])
-    assert exact >= min_exact * B
+            assert lo - TOL * c[-1] <= thr <= c[k] + TOL * c[-1], (b, k, k_o)
+    assert exact >= min_exact * B, f"pick another seed: only {exact} of {B} draws clear the margin"
     return n_o
 
 
 @pytest.mark.parametrize("temperature", [0.0, 1.0])
 def test_tiny_config(temperature):
     """B=1, gamma=5, V=4096, draft = target + N(0,1)."""
-    for seed in range(4):
+    for seed in (0, 1, 2, 4):
         a = synth.accept_inputs(1, 5, 4096, temperature, seed=seed, noise_std=1.0)
-        check(a, temperature, min_exact=0.0)
+        check(a, temperature)
+
+
+# seeds on which every draw of the three sequences clears TOL (found with the checker on the CPU)
+VOCAB_SEEDS = {(152064, 1.0): 13, (4096 + 5, 1.0): 11, (1000, 1.0): 12, (262144, 1.0): 23,
+               (152064, 0.7): 12, (4096 + 5, 0.7): 11, (1000, 0.7): 11, (262144, 0.7): 16}
 
 
 @pytest.mark.parametrize("temperature", [0.0, 1.0, 0.7])
 @pytest.mark.parametrize("V", [152064, 4096 + 5, 1000, 262144])
 def test_vocab_sizes_and_ragged_tail(V, temperature):
-    a = synth.accept_inputs(3, 5, V, temperature, seed=11, target_std=2.0, noise_std=1.5)
-    check(a, temperature, min_exact=0.0)
+    a = synth.accept_inputs(3, 5, V, temperature, seed=VOCAB_SEEDS.get((V, temperature), 11), target_std=2.0, noise_std=1.5)
+    check(a, temperature)
+
+
+def test_thin_margins_at_a_large_vocabulary():
+    """A seed on which two of the three draws land within TOL of a boundary (a token there holds ~7e-6 of the
+    mass): the neighbour rule of check() is what passes or fails them."""
+    a = synth.accept_inputs(3, 5, 152064, 1.0, seed=11, target_std=2.0, noise_std=1.5)
+    check(a, 1.0, min_exact=0.3)
 
 
 @pytest.mark.parametrize("temperature", [0.0, 1.0])
@@ -84,17 +105,17 @@ def test_peaked_logits_cover_every_accept_length(temperature):
 
 
 def test_long_context_stress_shape():
-    """B=32, gamma=7, V=152064, correlated logits, T=0.7."""
+    """B=32, gamma=7, V=152064, correlated logits, T=0.7 (31 of the 32 draws clear TOL)."""
     a = synth.accept_inputs(32, 7, 152064, 0.7, seed=0, target_std=3.0, corr=0.8)
-    check(a, 0.7)
+    check(a, 0.7, min_exact=0.9)
 
 
 @pytest.mark.parametrize("temperature", [0.0, 1.0])
 def test_extreme_sizes(temperature):
     """Smallest and largest speculation lengths, vocabularies smaller than a wave / a chunk."""
-    for B, gamma, V, seed in ((1, 1, 3, 20), (2, 15, 700, 21), (5, 2, 63, 22), (1, 15, 1025, 23)):
+    for B, gamma, V, seed in ((1, 1, 3, 20), (2, 15, 700, 22), (5, 2, 63, 22), (1, 15, 1025, 23)):
         a = synth.accept_inputs(B, gamma, V, temperature, seed=seed, noise_std=0.5, peak=3.0)
-        check(a, temperature, min_exact=0.0)
+        check(a, temperature)
 
 
 def test_ties_resolve_to_lowest_index():
@@ -113,11 +134,11 @@ def test_ties_resolve_to_lowest_index():
 
 def test_identical_and_disjoint_distributions():
     V, gamma, B = 5000, 4, 6
-    a = synth.accept_inputs(B, gamma, V, 1.0, seed=3)
+    a = synth.accept_inputs(B, gamma, V, 1.0, seed=10)
     a.draft_logits = a.target_logits[:, :gamma].copy()            # p == q: everything accepted
     n, out = run_gpu(a, 1.0)
     assert np.all(n == gamma)
-    check(a, 1.0, min_exact=0.0)
+    check(a, 1.0)
     t = np.full((B, gamma + 1, V), -np.inf, dtype=np.float32)      # disjoint supports: reject at once
     d = np.full((B, gamma, V), -np.inf, dtype=np.float32)
     t[:, :, : V // 2] = a.target_logits[:, :, : V // 2]
@@ -126,14 +147,21 @@ def test_identical_and_disjoint_distributions():
     a.draft_tokens = synth.draft_tokens_from(d, 1.0, 9)
     n, out = run_gpu(a, 1.0)
     assert np.all(n == 0) and np.all(out[:, 0] < V // 2)
-    check(a, 1.0, min_exact=0.0)
+    check(a, 1.0)
 
 
-def test_out_of_range_draft_token_is_rejected():
-    a = synth.accept_inputs(2, 3, 3000, 0.0, seed=4)
-    a.draft_tokens[:] = np.array([[-1, 0, 0], [3000, 0, 0]], dtype=np.int32)
-    n, out = run_gpu(a, 0.0)
-    assert np.all(n == 0)
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_out_of_range_draft_token_is_rejected(temperature):
+    """Ids outside [0, V) end the chain where they stand, at either temperature; the final token comes from
+    that position's rows."""
+    a = synth.accept_inputs(4, 3, 3000, temperature, seed=4, noise_std=0.3, peak=5.0)
+    a.draft_tokens[0, 0] = -1
+    a.draft_tokens[1, 0] = 3000
+    a.draft_tokens[2, 1] = 2 ** 31 - 1
+    a.draft_tokens[3, 2] = -(2 ** 31)
+    n, out = run_gpu(a, temperature)
+    assert n[0] == 0 and n[1] == 0 and n[2] <= 1 and n[3] <= 2
+    check(a, temperature)
 
 
 def test_repeatable_bits():
@@ -149,7 +177,7 @@ def test_sampling_step_without_drafts(B, V, temperature):
     """gamma = 0: one token per sequence drawn from the single row (the drafting loop's own draw)."""
     a = synth.accept_inputs(B, 0, V, temperature, seed=31, target_std=2.0)
     assert a.target_logits.shape == (B, 1, V)
-    n = check(a, temperature, min_exact=0.0)
+    n = check(a, temperature, min_exact=0.5 if V > 8192 else 1.0)
     assert np.all(n == 0)
 
 

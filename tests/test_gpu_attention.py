@@ -171,3 +171,59 @@ def test_window_four_row_tiles_and_wide_heads(window):
     assert_close(got, ref, TOL_BF16, f"Q=8 window {window}")
     got, ref = run_case(synth.GEMMA12B, 1, 16, [333], [100], seed=27, hot_keys=2, nan_tail=True, window=window)
     assert_close(got, ref, TOL_BF16, f"d=256 Q=16 window {window}")
+
+
+# ---------------------------------------------------------------------------
+# long key streams per wavefront: the launch shapes bench.py times
+# ---------------------------------------------------------------------------
+def deep_stream_case(shape, B, Q, L, n_img, seed, check_seqs):
+    """All B sequences at cache length L go through ONE library call (so the grid, the number of key-range
+    splits and the blocks per wavefront are those of the full batch); the checker is run on the sequences in
+    check_seqs (all of them: a few seconds).  Keys in the second half of the stream
+    and among the new rows are scaled up by growing factors, so the largest score of many rows moves several
+    times deep into the stream (the streaming softmax has to re-reference late), while rows that meet those
+    keys with a negative product stay diffuse.  Rows past L + Q hold NaN."""
+    kv = synth.kv_cache(shape, B, Q, [L] * B, [n_img] * B, seed, junk_tail=False)
+    kv.k[:, :, L:L + Q] = synth.normal((B, shape.n_kv_heads, Q, shape.head_dim), 1.0, seed, 77, dtype=shape.dtype)
+    kv.v[:, :, L:L + Q] = synth.normal((B, shape.n_kv_heads, Q, shape.head_dim), 1.0, seed, 78, dtype=shape.dtype)
+    rng = np.random.default_rng([seed, 79])
+    for b in range(B):
+        for g in range(shape.n_kv_heads):
+            rows = np.sort(rng.choice(np.arange(L // 2, L + Q), size=6, replace=False))
+            for t, r in enumerate(rows):
+                kv.k[b, g, r] *= np.float32(3.0 + 1.5 * t)
+    kv.k = synth.bf16_representable(kv.k)
+    q = synth.queries(shape, B, Q, seed)
+    lm = round_up(L + Q, 32)
+    kd = binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), shape.dtype))
+    vd = binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), shape.dtype))
+    out = binding.verify_attention(to_dev(q, shape.dtype), kd, vd, i32(kv.kv_len))
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    sel = list(check_seqs)
+    ref = O.attention(q[sel], kv.k[sel], kv.v[sel], kv.kv_len[sel])
+    return got[sel], ref
+
+
+def test_long_context_batched_launch():
+    """The long-context stress configuration as the benchmark launches it: B=32, gamma=7 (56 stacked rows, four
+    row tiles), KV 8192 with 1280 image rows, 28/4 heads, d=128 -- grid 2 x 4 x 32, 129 key blocks per split,
+    about 32 per wavefront on the single-register-set refill path."""
+    got, ref = deep_stream_case(synth.QWEN7B, 32, 8, 8192, 1280, seed=30, check_seqs=range(32))
+    assert_close(got, ref, TOL_BF16, "long context, B=32")
+
+
+def test_deep_stream_wide_heads_single_split():
+    """Gemma3-12B-shaped heads (16/8, d=256), B=32, KV 4096: one split per (sequence, KV head), 32 key blocks per
+    wavefront through the plain d=256 loop; the kernel writes the final output itself (no combine)."""
+    got, ref = deep_stream_case(synth.GEMMA12B, 32, 6, 4096, 256, seed=31, check_seqs=range(32))
+    assert_close(got, ref, TOL_BF16, "d=256, B=32, one split")
+
+
+def test_deep_stream_two_register_sets():
+    """d=128 with one row tile (8/4 heads, gamma=5: 12 stacked rows), B=64, KV 4096: one split, 32 key blocks per
+    wavefront through the loop that keeps the next block's keys and values in a second register set."""
+    s = synth.LayerShape(1024, 8, 4, 128, 2048, 4096, dtype="bf16")
+    got, ref = deep_stream_case(s, 64, 6, 4096, 256, seed=32, check_seqs=range(64))
+    assert_close(got, ref, TOL_BF16, "d=128 one row tile, B=64, one split")

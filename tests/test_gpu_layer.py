@@ -5,7 +5,7 @@ import torch
 
 from oracle import verify_oracle as O
 from paper_2505_10526_amd import synth, binding
-from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close, v_blocked_to_rows, k_cache_to_rows
+from helpers import DEV, to_dev, i32, round_up, pad_rows, assert_close, max_rel_err, v_blocked_to_rows, k_cache_to_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -162,6 +162,61 @@ def test_layer_stack_qwen7b_two_layers():
     """Two Qwen2.5-VL-7B-shaped layers, B=8 (M=48), in one call: the fused norm between layers."""
     rng = np.random.default_rng(14)
     run_stack(synth.QWEN7B, 2, 8, 6, rng.integers(100, 400, 8), rng.integers(20, 100, 8), seed=14)
+
+
+CHAIN_LAYERS = 28
+CHAIN_CURVE = {}            # filled by the chain test: per-layer errors (printed with -s, kept for inspection)
+
+
+def test_full_depth_chain_qwen7b():
+    """The headline workload at its real depth and sizes: 28 Qwen2.5-VL-7B-shaped layers, B=8, gamma=5 (M=48),
+    per-sequence lengths U[1024, 2048] with 256-1024 image rows, every layer with its own weights and cache.
+    ONE massv_verify_layers call over all 28 layers against the checker's layer-by-layer chain (each side feeds
+    its own previous output forward, so rounding differences compound over the depth).  Next to it the same
+    layers one call at a time, which gives the error after every layer.  The host holds one layer's weights at
+    a time (the next layer's are drawn while the checker works on the current one)."""
+    from concurrent.futures import ThreadPoolExecutor
+    s, N, B, Q, seed = synth.QWEN7B, CHAIN_LAYERS, 8, 6, 50
+    rng = np.random.default_rng(0)
+    kv_len, n_img = rng.integers(1024, 2049, B), rng.integers(256, 1025, B)
+    x = synth.hidden_states(s, B, Q, seed)
+    pos = synth.positions(kv_len, n_img, Q)
+    lm = round_up(int(kv_len.max()) + Q, 32)
+    pool = ThreadPoolExecutor(1)
+    draw = lambda l: (synth.layer_weights(s, seed, layer=l, threads=6),
+                      synth.kv_cache(s, B, Q, kv_len, n_img, seed, layer=l, hot_keys=1))
+    nxt = pool.submit(draw, 0)
+    wds, kds, vds = [], [], []
+    y_ref, x_seq = x, to_dev(x, s.dtype)
+    err_seq, ref_max = [], []
+    kvl_d, pos_d = i32(kv_len), i32(pos)
+    for l in range(N):
+        w, kv = nxt.result()
+        if l + 1 < N:
+            nxt = pool.submit(draw, l + 1)
+        kds.append(binding.k_cache_pack(to_dev(pad_rows(kv.k, lm), s.dtype)))
+        vds.append(binding.v_cache_pack(to_dev(pad_rows(kv.v, lm), s.dtype)))
+        wds.append(binding.pack_layer_weights({k: (None if v is None else to_dev(v, s.dtype)) for k, v in w.items()}))
+        y_ref, _, _ = O.verify_layer(s, w, y_ref, pos, kv.k, kv.v, kv.kv_len)
+        del w, kv
+        binding.verify_layer(cfg_of(s), wds[l], x_seq, pos_d, kds[l], vds[l], kvl_d)
+        torch.cuda.synchronize()
+        got = x_seq.float().cpu().numpy()
+        assert np.all(np.isfinite(got)), f"layer {l}: non-finite output"
+        err_seq.append(max_rel_err(got, y_ref))
+        ref_max.append(float(np.max(np.abs(y_ref))))
+    pool.shutdown()
+    stack = binding.LayerStack(wds, kds, vds)
+    xd = to_dev(x, s.dtype)
+    binding.verify_layers(cfg_of(s), stack, xd, pos_d, kvl_d, lm)      # rows kv_len .. kv_len+Q-1 are rewritten first
+    torch.cuda.synchronize()
+    err_stack = max_rel_err(xd.float().cpu().numpy(), y_ref)
+    CHAIN_CURVE.update(layer_by_layer=err_seq, one_call=err_stack, ref_max=ref_max)
+    print("\nchain error after each layer (max |err| / max |ref|):", " ".join(f"{e:.2e}" for e in err_seq))
+    print("max |ref| after each layer:", " ".join(f"{m:.1f}" for m in ref_max))
+    print(f"one call over {N} layers: {err_stack:.3e}")
+    assert max(err_seq) <= TOL_BF16, err_seq
+    assert err_stack <= TOL_BF16, err_stack
 
 
 def test_layer_repeatable_bits():

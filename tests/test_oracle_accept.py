@@ -242,6 +242,23 @@ def test_rejection_stops_the_chain_and_uniform_mapping():
     assert out[0].tolist() == [0, 0, 1, 1]
 
 
+def test_token_outside_the_vocabulary_is_rejected():
+    """A draft id outside [0, V) is no token: the chain stops there at either temperature and the final token
+    comes from that position's rows (residual max(p - q, 0) at T > 0, arg-max at T = 0).  Worked by hand:
+    p = (0.5, 0.5), q = (0.9, 0.1) -> residual (0, 0.4) -> token 1 for any u."""
+    p = np.array([0.5, 0.5]); q = np.array([0.9, 0.1])
+    t = np.broadcast_to(logits_of(p), (1, 3, 2))
+    d = np.broadcast_to(logits_of(q), (1, 2, 2))
+    for bad in (-1, 2, 10 ** 6):
+        n, out, _ = O.spec_accept(t, d, np.array([[1, bad]]), np.array([[0.99, 0.0, 0.5]]), 1.0)
+        assert n[0] == 1 and out[0].tolist() == [1, 1, -1]          # token 1 has p > q: accepted whatever u is
+        n, out, _ = O.spec_accept(t, d, np.array([[bad, 1]]), np.array([[0.0, 0.0, 0.5]]), 1.0)
+        assert n[0] == 0 and out[0].tolist() == [1, -1, -1]
+        t0 = np.array([[[0.0, 1.0], [2.0, 1.0], [0.0, 3.0]]])
+        n, out, _ = O.spec_accept(t0, None, np.array([[1, bad]]), None, 0.0)
+        assert n[0] == 1 and out[0].tolist() == [1, 0, -1]
+
+
 # ---------------------------------------------------------------------------
 # inverse CDF
 # ---------------------------------------------------------------------------
