@@ -314,3 +314,135 @@ def test_lm_head_is_norm_then_projection():
     r = math.sqrt(12.5)
     hand = O.lm_head_logits(np.array([[3.0, 4.0]]), np.array([2.0, 1.0]), np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]]), 0.0)
     np.testing.assert_allclose(hand, [[6.0 / r, 4.0 / r, 10.0 / r]], rtol=1e-15)
+
+
+
+# ---------------------------------------------------------------------------
+# variants of the Gemma 3 family: sliding window, query/key norm, block-output norms
+# ---------------------------------------------------------------------------
+def brute_window_attention(q, k, v, kv_len, scale, W):
+    """Scalar loops: the query at cache row r sees rows max(0, r - W + 1) .. r."""
+    B, Q, n_q, d = q.shape
+    G = n_q // k.shape[1]
+    out = np.zeros((B, Q, n_q, d))
+    for b in range(B):
+        for i in range(Q):
+            r = int(kv_len[b]) + i
+            rows = [j for j in range(r + 1) if r - j < W]
+            for h in range(n_q):
+                sc = [scale * sum(float(q[b, i, h, c]) * float(k[b, h // G, j, c]) for c in range(d)) for j in rows]
+                mx = max(sc)
+                ws = [math.exp(t - mx) for t in sc]
+                for c in range(d):
+                    out[b, i, h, c] = sum(wt * float(v[b, h // G, j, c]) for wt, j in zip(ws, rows)) / sum(ws)
+    return out
+
+
+@pytest.mark.parametrize("W", [1, 2, 4, 7, 12, 100])
+def test_window_attention_matches_brute_force(W):
+    q, k, v, kv_len = small_case(3)
+    got = O.attention(q, k, v, kv_len, window=W)
+    want = brute_window_attention(q, k, v, kv_len, 1.0 / math.sqrt(q.shape[-1]), W)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+def test_window_special_cases():
+    q, k, v, kv_len = small_case(4)
+    B, Q = q.shape[:2]
+    full = O.attention(q, k, v, kv_len)
+    assert np.array_equal(O.attention(q, k, v, kv_len, window=0), full)
+    np.testing.assert_allclose(O.attention(q, k, v, kv_len, window=int(kv_len.max()) + Q), full, rtol=1e-14)
+    one = O.attention(q, k, v, kv_len, window=1)                   # only the own row: its value, whatever the key
+    for b in range(B):
+        for i in range(Q):
+            for h in range(q.shape[2]):
+                np.testing.assert_allclose(one[b, i, h], v[b, h // 2, kv_len[b] + i], rtol=1e-14)
+    # a change to a key outside every window is invisible, one inside is not
+    k2 = k.copy(); k2[:, :, 0] += 5.0
+    W = 3
+    assert np.array_equal(O.attention(q, k2, v, kv_len, window=W), O.attention(q, k, v, kv_len, window=W))
+    k3 = k.copy(); k3[0, :, kv_len[0] - 1] += 5.0
+    assert not np.allclose(O.attention(q, k3, v, kv_len, window=W)[0, 0], O.attention(q, k, v, kv_len, window=W)[0, 0])
+
+
+def gemma_layer_case(dtype="f32", seed=0):
+    s = synth.LayerShape(32, 4, 2, 8, 48, 64, synth.ACT_GELU_TANH, False, rope_theta=1e4, dtype=dtype,
+                         window=5, qk_norm=True, post_norms=True)
+    w = synth.layer_weights(s, seed, std=0.2)
+    kv = synth.kv_cache(s, 2, 3, [6, 9], [2, 4], seed)
+    x = synth.hidden_states(s, 2, 3, seed)
+    pos = synth.positions(kv.kv_len, kv.n_img, 3, compress_image=True)
+    return s, w, kv, x, pos
+
+
+def test_gemma_style_layer_against_torch_float64():
+    """The layer with window, query/key norm and block-output norms rebuilt from torch float64 routines and
+    explicit band masks: a norm applied after instead of before the rotation, a norm on the wrong operand,
+    an off-by-one window edge or a missing output norm shows up here."""
+    s, w, kv, x, pos = gemma_layer_case()
+    y, kc, vc = O.verify_layer(s, w, x, pos, kv.k, kv.v, kv.kv_len)
+    T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    rms = lambda t, g: torch.nn.functional.rms_norm(t, (t.shape[-1],), T(g), eps=s.norm_eps)
+    B, Q, H = x.shape
+    d, nq, nkv, W = s.head_dim, s.n_q_heads, s.n_kv_heads, s.window
+    tx = T(x)
+    xn = rms(tx, w["ln1"])
+    q = rms((xn @ T(w["wq"]).T).reshape(B, Q, nq, d), w["q_norm"])
+    k = rms((xn @ T(w["wk"]).T).reshape(B, Q, nkv, d), w["k_norm"])
+    v = (xn @ T(w["wv"]).T).reshape(B, Q, nkv, d)
+    inv = s.rope_theta ** (-torch.arange(0, d // 2, dtype=torch.float64) * 2 / d)
+    ang = T(pos)[..., None, None] * inv
+    def rot(t):
+        a, b = t[..., :d // 2], t[..., d // 2:]
+        return torch.cat([a * ang.cos() - b * ang.sin(), b * ang.cos() + a * ang.sin()], -1)
+    q, k = rot(q), rot(k)
+    kc2, vc2 = T(kv.k).clone(), T(kv.v).clone()
+    attn = torch.zeros(B, Q, nq, d, dtype=torch.float64)
+    for b in range(B):
+        L = int(kv.kv_len[b])
+        kc2[b, :, L:L + Q] = k[b].permute(1, 0, 2).float().double()
+        vc2[b, :, L:L + Q] = v[b].permute(1, 0, 2).float().double()
+        rows = (L + torch.arange(Q))[:, None]
+        cols = torch.arange(L + Q)[None, :]
+        mask = (cols > rows) | (rows - cols >= W)
+        for h in range(nq):
+            sc = (q[b, :, h] @ kc2[b, h // 2, :L + Q].T) / math.sqrt(d)
+            attn[b, :, h] = torch.softmax(sc.masked_fill(mask, float("-inf")), -1) @ vc2[b, h // 2, :L + Q]
+    h1 = tx + rms(attn.reshape(B, Q, nq * d) @ T(w["wo"]).T, w["post_attn_norm"])
+    hn = rms(h1, w["ln2"])
+    mlp = (torch.nn.functional.gelu(hn @ T(w["wg"]).T, approximate="tanh") * (hn @ T(w["wu"]).T)) @ T(w["wd"]).T
+    want = h1 + rms(mlp, w["post_mlp_norm"])
+    np.testing.assert_allclose(y, want.float().double().numpy(), rtol=1e-6, atol=1e-6)
+    for b in range(B):
+        L = int(kv.kv_len[b])
+        np.testing.assert_allclose(kc[b, :, :L + Q], kc2[b, :, :L + Q].numpy(), rtol=1e-6, atol=1e-7)
+
+
+def test_query_key_norm_removes_projection_scale():
+    """With the head norms on (and eps negligible) the layer's output does not change when the query or
+    key projection is scaled by a constant; without them it does."""
+    s, w, kv, x, pos = gemma_layer_case()
+    s.norm_eps = 1e-30
+    y0, _, _ = O.verify_layer(s, w, x, pos, kv.k, kv.v, kv.kv_len)
+    w2 = dict(w, wq=w["wq"] * 3.0)
+    y1, _, _ = O.verify_layer(s, w2, x, pos, kv.k, kv.v, kv.kv_len)
+    np.testing.assert_allclose(y1, y0, rtol=0, atol=1e-6)
+    w3 = dict(w2, q_norm=None); w4 = dict(w, q_norm=None)
+    y3, _, _ = O.verify_layer(s, w3, x, pos, kv.k, kv.v, kv.kv_len)
+    y4, _, _ = O.verify_layer(s, w4, x, pos, kv.k, kv.v, kv.kv_len)
+    assert np.max(np.abs(y3 - y4)) > 1e-3
+
+
+def test_gelu_erf_and_projector_against_torch():
+    """Exact GELU against the library routine; the two-layer projector (Section 3.1) rebuilt from torch float64
+    matmuls, with the hidden activation stored in bf16 in between."""
+    x = np.linspace(-6, 6, 101)
+    np.testing.assert_allclose(O.gelu_erf(x), torch.nn.functional.gelu(torch.from_numpy(x)).numpy(), rtol=1e-12, atol=1e-15)
+    rng = np.random.default_rng(5)
+    h = synth.bf16_representable(rng.standard_normal((7, 12)).astype(np.float32))
+    w1 = synth.bf16_representable((rng.standard_normal((20, 12)) * 0.3).astype(np.float32)); b1 = synth.bf16_representable(rng.standard_normal(20).astype(np.float32))
+    w2 = synth.bf16_representable((rng.standard_normal((5, 20)) * 0.3).astype(np.float32)); b2 = synth.bf16_representable(rng.standard_normal(5).astype(np.float32))
+    T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    mid = torch.nn.functional.gelu(T(h) @ T(w1).T + T(b1)).to(torch.bfloat16).double()
+    want = (mid @ T(w2).T + T(b2)).numpy()
+    np.testing.assert_allclose(O.projector_mlp(h, w1, b1, w2, b2, "bf16"), want, rtol=1e-12, atol=1e-12)
