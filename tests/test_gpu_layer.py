@@ -168,7 +168,7 @@ CHAIN_LAYERS = 28
 CHAIN_CURVE = {}            # filled by the chain test: per-layer errors (printed with -s, kept for inspection)
 
 
-def test_full_depth_chain_qwen7b():
+def test_full_depth_chain_qwen7b(capsys):
     """The headline workload at its real depth and sizes: 28 Qwen2.5-VL-7B-shaped layers, B=8, gamma=5 (M=48),
     per-sequence lengths U[1024, 2048] with 256-1024 image rows, every layer with its own weights and cache.
     ONE massv_verify_layers call over all 28 layers against the checker's layer-by-layer chain (each side feeds
@@ -205,6 +205,9 @@ def test_full_depth_chain_qwen7b():
         assert np.all(np.isfinite(got)), f"layer {l}: non-finite output"
         err_seq.append(max_rel_err(got, y_ref))
         ref_max.append(float(np.max(np.abs(y_ref))))
+        if l % 4 == 3:
+            with capsys.disabled():          # a progress line from the work itself: the test runs for minutes
+                print(f"[chain] layer {l + 1}/{N}: error {err_seq[-1]:.2e}, max |ref| {ref_max[-1]:.1f}", flush=True)
     pool.shutdown()
     stack = binding.LayerStack(wds, kds, vds)
     xd = to_dev(x, s.dtype)
@@ -212,9 +215,10 @@ def test_full_depth_chain_qwen7b():
     torch.cuda.synchronize()
     err_stack = max_rel_err(xd.float().cpu().numpy(), y_ref)
     CHAIN_CURVE.update(layer_by_layer=err_seq, one_call=err_stack, ref_max=ref_max)
-    print("\nchain error after each layer (max |err| / max |ref|):", " ".join(f"{e:.2e}" for e in err_seq))
-    print("max |ref| after each layer:", " ".join(f"{m:.1f}" for m in ref_max))
-    print(f"one call over {N} layers: {err_stack:.3e}")
+    with capsys.disabled():
+        print("[chain] error after each layer (max |err| / max |ref|):", " ".join(f"{e:.2e}" for e in err_seq))
+        print("[chain] max |ref| after each layer:", " ".join(f"{m:.1f}" for m in ref_max))
+        print(f"[chain] one call over {N} layers: {err_stack:.3e}", flush=True)
     assert max(err_seq) <= TOL_BF16, err_seq
     assert err_stack <= TOL_BF16, err_stack
 
