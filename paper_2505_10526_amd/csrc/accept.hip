@@ -457,11 +457,10 @@ extern "C" size_t massv_spec_accept_workspace(int32_t B, int32_t gamma, int32_t 
     return accept_layout(B, gamma, V).total;
 }
 
-extern "C" int massv_spec_accept(const float* target_logits, const float* draft_logits,
-                                 const int32_t* draft_tokens, const float* uniforms,
-                                 float temperature, int32_t B, int32_t gamma, int32_t V,
-                                 int32_t* n_accepted, int32_t* out_tokens,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by the two entry points (everything except the scratch space).
+static int check_accept_args(const float* target_logits, const float* draft_logits, const int32_t* draft_tokens,
+                             const float* uniforms, float temperature, int32_t B, int32_t gamma, int32_t V,
+                             const int32_t* n_accepted, const int32_t* out_tokens) {
     if (B < 1 || gamma < 0 || V < 1) return MASSV_EINVAL;
     if (!(temperature >= 0.f) || isinf(temperature)) return MASSV_EINVAL;     // also catches NaN
     if (!target_logits || !n_accepted || !out_tokens) return MASSV_EINVAL;
@@ -469,12 +468,16 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     const int greedy = (temperature == 0.f);
     if (!greedy && (!uniforms || (gamma > 0 && !draft_logits))) return MASSV_EINVAL;
     if (gamma > kMaxGamma) return MASSV_EUNSUPPORTED;
-    if ((size_t)B * (gamma + 1) > 65535 || (size_t)B > 65535) return MASSV_EUNSUPPORTED;   // grid.y limit
-    const AcceptLayout lay = accept_layout(B, gamma, V);
-    if (!workspace || workspace_bytes < lay.total) return MASSV_EWORKSPACE;
-    if ((size_t)B * (2 * gamma + 1) > 65535) return MASSV_EUNSUPPORTED;
+    if ((size_t)B * (2 * gamma + 1) > 65535) return MASSV_EUNSUPPORTED;       // grid.y limit of pass 1
+    return MASSV_OK;
+}
 
-    hipStream_t st = (hipStream_t)stream;
+// The four launches of one call; `workspace` holds accept_layout(B, gamma, V).total bytes.
+static int run_accept(const float* target_logits, const float* draft_logits, const int32_t* draft_tokens,
+                      const float* uniforms, float temperature, int32_t B, int32_t gamma, int32_t V,
+                      int32_t* n_accepted, int32_t* out_tokens, void* workspace, hipStream_t st) {
+    const AcceptLayout lay = accept_layout(B, gamma, V);
+    const int greedy = (temperature == 0.f);
     char* ws = (char*)workspace;
     RowPartial* part = (RowPartial*)(ws + lay.part);
     SeqSel* sel = (SeqSel*)(ws + lay.sel);
@@ -498,6 +501,19 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
                            target_logits, draft_logits, uniforms, gamma, V, C, ts, vec, sel, mass, out_tokens);
     }
     return launch_status();
+}
+
+extern "C" int massv_spec_accept(const float* target_logits, const float* draft_logits,
+                                 const int32_t* draft_tokens, const float* uniforms,
+                                 float temperature, int32_t B, int32_t gamma, int32_t V,
+                                 int32_t* n_accepted, int32_t* out_tokens,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_accept_args(target_logits, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V,
+                                     n_accepted, out_tokens);
+    if (rc != MASSV_OK) return rc;
+    if (!workspace || workspace_bytes < accept_layout(B, gamma, V).total) return MASSV_EWORKSPACE;
+    return run_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V, n_accepted,
+                      out_tokens, workspace, (hipStream_t)stream);
 }
 
 namespace massv {

@@ -33,6 +33,8 @@
 // fp32 configuration.
 #include "kernels.h"
 
+#include <atomic>
+
 namespace massv {
 
 constexpr int kAttnWaves = 4;
@@ -142,7 +144,6 @@ void attention_mfma_kernel(AttnParams p) {
     // shuffling than it hid -- the plain loop measured 95 us, K double-buffering 101 us, full double
     // buffering 124 us on the 56-row, 8192-key shape.
     constexpr bool PREFETCH = (D * MT <= 256) && (D <= 128);
-    constexpr bool QLDS = false;                   // Q operand tiles in LDS instead of registers (measured: no gain)
     constexpr int KS = D / 32;          // k-steps of the score product
     constexpr int NT = D / 16;          // 16-dim tiles of the output
     constexpr int ROWS = MT * 16;
@@ -167,9 +168,9 @@ void attention_mfma_kernel(AttnParams p) {
     const int first_masked_blk = L / kBlk;      // blocks before it hold cached positions only
 
     // ---- Q operand: lane (lr, lc) holds Q[row = 16 mt + lr][32 ks + 8 lc .. +8] ----
-    extern __shared__ float s_dyn[];             // [ROWS][LDS_STRIDE] merge buffer, then (QLDS) the Q operand tiles
-    bf16x8* q_lds = reinterpret_cast<bf16x8*>(s_dyn + ROWS * LDS_STRIDE);      // [MT][KS][64]
-    bf16x8 qreg[QLDS ? 1 : MT][QLDS ? 1 : KS];
+    // (kept in registers for the whole kernel; operand tiles in LDS measured no gain)
+    extern __shared__ float s_dyn[];             // [ROWS][LDS_STRIDE] merge buffer(s)
+    bf16x8 qreg[MT][KS];
     int qi[MT];                                 // query position of this lane's row in tile mt (clamped)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -177,20 +178,13 @@ void attention_mfma_kernel(AttnParams p) {
         const int i = r / G, hh = r % G;
         qi[mt] = i < p.Q ? i : p.Q - 1;
         const bf16_t* qr = p.q + (((size_t)b * p.Q + (i < p.Q ? i : 0)) * p.n_q + g * G + hh) * D;
-        if (QLDS && (mt % kAttnWaves) != wave) continue;          // each tile is fetched by one wave
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
             if (r < rows) v = *reinterpret_cast<const bf16x8*>(qr + ks * 32 + lc * 8);
-            if constexpr (QLDS) q_lds[(mt * KS + ks) * kWave + lane] = v;
-            else qreg[mt][ks] = v;
+            qreg[mt][ks] = v;
         }
     }
-    if constexpr (QLDS) __syncthreads();
-    auto q_operand = [&](int mt, int ks) -> bf16x8 {
-        if constexpr (QLDS) return q_lds[(mt * KS + ks) * kWave + lane];
-        else return qreg[mt][ks];
-    };
 
     floatx4 acc[MT][NT];
     float m_run[MT], l_run[MT];
@@ -242,7 +236,7 @@ void attention_mfma_kernel(AttnParams p) {
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const bf16x8 qv = q_operand(mt, ks);
+                const bf16x8 qv = qreg[mt][ks];
                 s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qv, s0[mt], 0, 0, 0);
                 s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qv, s1[mt], 0, 0, 0);
             }
@@ -541,13 +535,13 @@ template <int D, int MT>
 static int launch_mfma(const massv_attn_desc& a, AttnParams p, hipStream_t st) {
     const size_t lds = (size_t)MT * 16 * (D + 4) * sizeof(float) * (attn_tree_merge(D, MT) ? 2 : 1);
     if (lds > 48 * 1024) {                       // more dynamic LDS than a kernel may use by default
-        static bool ready[64] = {};
+        static std::atomic<bool> ready[64];       // zero-initialised; calls may come from several threads
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
-        if (!ready[dev]) {
+        if (!ready[dev].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute((const void*)attention_mfma_kernel<D, MT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds) != hipSuccess) return MASSV_ELAUNCH;
-            ready[dev] = true;
+            ready[dev].store(true, std::memory_order_release);
         }
     }
     launch_traced(MASSV_K_ATTENTION, attention_mfma_kernel<D, MT>, dim3(p.n_split, a.n_kv_heads, a.batch),

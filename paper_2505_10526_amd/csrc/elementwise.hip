@@ -1,5 +1,5 @@
 // Row-wise kernels of the decoder layer: RMSNorm, rotary embedding with KV
-// append, gated activation, value-cache packing.  All traffic here is a few
+// append, cache and weight packing.  All traffic here is a few
 // hundred KB per call; the kernels are written for clarity and coalescing,
 // the math is fp32 (angles in double).
 #include "kernels.h"
@@ -68,11 +68,8 @@ int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, f
     return launch_status();
 }
 
-int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st) {
-    if (dtype == MASSV_F32)
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y, H, eps);
-    else
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)g, (bf16_t*)y, H, eps);
+int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)x, (const float*)g, (float*)y, H, eps);
     return launch_status();
 }
 
@@ -255,20 +252,32 @@ __device__ inline float finish_block_sum(float v, float* part /* [kFinishThreads
 }
 
 // post != nullptr: the projection's output row is RMS-normalised with these gains before it is added.
+// The row the sum is added to comes from h_in (fp32) when given, else from x (bf16); the result goes to h_out (fp32)
+// when given, else to x (rounded to bf16).  A layer uses both: the stream between its attention block and its MLP
+// block stays in fp32 (one rounding of the residual stream per layer, at the layer's output, instead of two).
 __global__ __launch_bounds__(kFinishThreads)
 void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size_t slab_stride,
-                            bf16_t* __restrict__ x, const bf16_t* __restrict__ post, const bf16_t* __restrict__ ln,
+                            bf16_t* __restrict__ x, const float* __restrict__ h_in, float* __restrict__ h_out,
+                            const bf16_t* __restrict__ post, const bf16_t* __restrict__ ln,
                             bf16_t* __restrict__ xn, int H, float eps, int mt_count) {
     const int m = blockIdx.x, tid = threadIdx.x;
     const int k8 = tid;
     const bool live = k8 < H / 8;
     __shared__ float part[kFinishThreads / kWave];
-    float v[8];
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float ss = 0.f;
-    bf16x8 xv = {0, 0, 0, 0, 0, 0, 0, 0};
     if (live) {
-        xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
+        if (h_in) {
+            const floatx4* hp = reinterpret_cast<const floatx4*>(h_in + (size_t)m * H + k8 * 8);
+            const floatx4 a = hp[0], b = hp[1];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+        } else {
+            const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)m * H + k8 * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = (float)xv[e];
+        }
         for (int s0 = 0; s0 < n_slabs; s0 += 8) {              // 8 slabs' loads in flight at once; summed in slab order
             floatx4 p0[8], p1[8];
 #pragma unroll
@@ -297,10 +306,18 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
         }
     }
     if (live) {
-        bf16x8 o;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { v[e] = (float)xv[e] + add[e]; o[e] = (bf16_t)v[e]; ss += v[e] * v[e]; }
-        *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
+        for (int e = 0; e < 8; ++e) { v[e] += add[e]; ss += v[e] * v[e]; }
+        if (h_out) {
+            floatx4* hp = reinterpret_cast<floatx4*>(h_out + (size_t)m * H + k8 * 8);
+            hp[0] = floatx4{v[0], v[1], v[2], v[3]};
+            hp[1] = floatx4{v[4], v[5], v[6], v[7]};
+        } else {
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+            *reinterpret_cast<bf16x8*>(x + (size_t)m * H + k8 * 8) = o;
+        }
     }
     if (!ln) return;
     const float rstd = 1.0f / sqrtf(finish_block_sum(ss, part) / (float)H + eps);
@@ -313,11 +330,11 @@ void residual_finish_kernel(const float* __restrict__ partial, int n_slabs, size
     }
 }
 
-int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* post,
-                           const void* ln, void* xn_packed, int M, int H, float eps, hipStream_t st) {
+int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const float* h_in, float* h_out,
+                           const void* post, const void* ln, void* xn_packed, int M, int H, float eps, hipStream_t st) {
     if (H % 8 || H > 8 * kFinishThreads) return MASSV_EUNSUPPORTED;
     hipLaunchKernelGGL(residual_finish_kernel, dim3(M), dim3(kFinishThreads), 0, st, partial, n_slabs, slab_stride,
-                       (bf16_t*)x, (const bf16_t*)post, (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
+                       (bf16_t*)x, h_in, h_out, (const bf16_t*)post, (const bf16_t*)ln, (bf16_t*)xn_packed, H, eps, (M + 15) / 16);
     return launch_status();
 }
 
@@ -336,30 +353,6 @@ void postnorm_residual_kernel(float* __restrict__ x, const float* __restrict__ y
 
 int launch_postnorm_residual(void* x, const void* y, const void* g, int M, int H, float eps, hipStream_t st) {
     hipLaunchKernelGGL(postnorm_residual_kernel, dim3(M), dim3(256), 0, st, (float*)x, (const float*)y, (const float*)g, H, eps);
-    return launch_status();
-}
-
-// ---------------------------------------------------------------------------
-// h = act(g) * u
-// ---------------------------------------------------------------------------
-__device__ inline float act_fn(float x, int act) {
-    if (act == MASSV_ACT_SILU) return x / (1.0f + expf(-x));
-    const float c = 0.7978845608028654f;      // sqrt(2/pi)
-    return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
-}
-
-template <typename T>
-__global__ void act_mul_kernel(const T* __restrict__ g, const T* __restrict__ u, T* __restrict__ h, size_t n, int act) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) stf(h + i, act_fn(ldf(g + i), act) * ldf(u + i));
-}
-
-int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int dtype, hipStream_t st) {
-    const unsigned blocks = (unsigned)((n + 255) / 256);
-    if (dtype == MASSV_F32)
-        hipLaunchKernelGGL(act_mul_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)g, (const float*)u, (float*)h, n, act);
-    else
-        hipLaunchKernelGGL(act_mul_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)g, (const bf16_t*)u, (bf16_t*)h, n, act);
     return launch_status();
 }
 

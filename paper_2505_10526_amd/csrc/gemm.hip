@@ -42,6 +42,7 @@
 #include "kernels.h"
 
 #include <limits.h>
+#include <atomic>
 
 namespace massv {
 
@@ -367,8 +368,8 @@ GemmPlan gemm_plan(const GemmArgs& g) {
     if (g.dtype != MASSV_BF16) return best;
     const int mt = (g.M + 15) / 16;
     const int T = (g.epilogue == EPI_GATED) ? 2 * (g.n[0] / 16) : n_total(g) / 16;
-    const int n_chunks = (g.K + 127) / 128;
     if (g.epilogue == EPI_PARTIAL && (T + 3) / 4 < kCUs) return plan_split(g, mt, T);
+    // wide output (or a partial-sum output wide enough for 256 workgroups at full K): one slab
     static const int cand_partial[] = {8, 7, 4}, cand_gated[] = {10, 8, 4}, cand_logits[] = {10, 8, 4};
     const int* cand = g.epilogue == EPI_GATED ? cand_gated : (g.epilogue == EPI_LOGITS || g.epilogue == EPI_ARGMAX) ? cand_logits : cand_partial;
     double best_score = -1.0;
@@ -377,25 +378,14 @@ GemmPlan gemm_plan(const GemmArgs& g) {
         if (mt == 4 && nt > 4) continue;                       // register budget of four row tiles
         const int ut = (g.epilogue == EPI_GATED) ? 2 : 1;      // tiles per unit
         int groups = (T + nt - 1) / nt;
-        if (groups < kCUs && g.epilogue != EPI_PARTIAL) {       // one round: spread the units over as many CUs as there are
-            const int units = T / ut;
+        if (groups < kCUs) {                                    // one round: spread the units over as many CUs as there are
+            const int units = T / ut;                           // (never a partial-sum launch: those went to plan_split)
             groups = units < kCUs ? units : kCUs;
         }
-        int slabs = 1, cps = n_chunks;
-        double eff;
-        if (groups >= kCUs || g.epilogue != EPI_PARTIAL) {
-            const int rounds = (groups + kCUs - 1) / kCUs;
-            eff = (double)T / ((double)nt * rounds * kCUs);
-        } else {
-            int max_slabs = n_chunks / kGemmWaves; if (max_slabs < 1) max_slabs = 1;
-            slabs = kCUs / groups; if (slabs > max_slabs) slabs = max_slabs; if (slabs > 32) slabs = 32;
-            cps = (n_chunks + slabs - 1) / slabs;
-            slabs = (n_chunks + cps - 1) / cps;
-            eff = (double)T * slabs / ((double)nt * kCUs) ;
-            if (eff > 1.0) eff = 1.0;
-        }
+        const int rounds = (groups + kCUs - 1) / kCUs;
+        const double eff = (double)T / ((double)nt * rounds * kCUs);
         const double score = eff + 0.004 * nt;                 // near ties go to the larger tile count (less X traffic)
-        if (score > best_score) { best_score = score; best.nt = nt; best.slabs = slabs; best.groups = groups; }
+        if (score > best_score) { best_score = score; best.nt = nt; best.slabs = 1; best.groups = groups; }
     }
     return best;
 }
@@ -411,13 +401,13 @@ static int launch_stream(const GemmDev& d, const GemmPlan& p, int kid, hipStream
     constexpr int GRP = ReduceGroup<MT, NT>::value;
     const size_t lds = (size_t)kGemmWaves * GRP * MT * kWave * sizeof(floatx4);
     if (lds > 48 * 1024) {                       // more dynamic LDS than a kernel may use by default
-        static bool ready[64] = {};
+        static std::atomic<bool> ready[64];       // zero-initialised; calls may come from several threads
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
-        if (!ready[dev]) {
+        if (!ready[dev].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute((const void*)gemm_stream_kernel<MT, NT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds) != hipSuccess) return MASSV_ELAUNCH;
-            ready[dev] = true;
+            ready[dev].store(true, std::memory_order_release);
         }
     }
     const dim3 grid = (EPI == EPI_PARTIAL) ? dim3(p.slabs, p.groups) : dim3(p.groups, p.slabs);

@@ -27,7 +27,7 @@ inline void launch_traced(int kid, K kernel, dim3 grid, dim3 block, size_t lds, 
 
 // ---- small row-wise kernels (elementwise.hip) ----
 // y[m,:] = x[m,:] * g / sqrt(mean(x[m,:]^2) + eps)
-int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, int dtype, hipStream_t st);
+int launch_rmsnorm(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st);      // fp32 rows
 // bf16 only: same, output in operand order (packed_index); g == nullptr re-lays the rows out without normalising.
 int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, float eps, hipStream_t st);
 // Rotates the q and k heads of qkv[M][(n_q+2n_kv)*d] by pos[m], writes q to
@@ -36,7 +36,6 @@ int launch_rmsnorm_packed(const void* x, const void* g, void* y, int M, int H, f
 int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_len, void* q_out,
                        void* k_cache, void* v_cache, const void* q_norm, const void* k_norm, float eps,
                        const massv_attn_desc& a, float theta, hipStream_t st);
-int launch_act_mul(const void* g, const void* u, void* h, size_t n, int act, int dtype, hipStream_t st);
 // bf16: sums the K slabs of the q/k/v projection's partial sums [slabs][Mp][(n_q+2n_kv)*d], adds the biases
 // (nullptr = none), normalises the q / k heads (q_norm, k_norm; nullptr = no), rotates q and k, writes q to
 // q_out[M][n_q][d] and k / v to their cache rows.
@@ -44,10 +43,11 @@ int launch_qkv_finish(const float* partial, int n_slabs, size_t slab_stride, con
                       const void* bv, const int32_t* pos, const int32_t* kv_len, void* q_out, void* k_cache,
                       void* v_cache, const void* q_norm, const void* k_norm, float eps,
                       const massv_attn_desc& a, float theta, hipStream_t st);
-// bf16: y[m,:] = sum over slabs of partial[s][m,:]; x[m,:] += (post ? rmsnorm(y, post) : y); if ln != nullptr
-// also writes rmsnorm(x, ln) in operand order to xn_packed.
-int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const void* post,
-                           const void* ln, void* xn_packed, int M, int H, float eps, hipStream_t st);
+// bf16: y[m,:] = sum over slabs of partial[s][m,:]; r = base + (post ? rmsnorm(y, post) : y) with base = h_in (fp32
+// rows) when given, else x; r is written to h_out (fp32) when given, else to x (bf16); if ln != nullptr also
+// rmsnorm(r, ln) in operand order to xn_packed.
+int launch_residual_finish(const float* partial, int n_slabs, size_t slab_stride, void* x, const float* h_in, float* h_out,
+                           const void* post, const void* ln, void* xn_packed, int M, int H, float eps, hipStream_t st);
 // fp32: x[m,:] += rmsnorm(y[m,:], g).
 int launch_postnorm_residual(void* x, const void* y, const void* g, int M, int H, float eps, hipStream_t st);
 

@@ -5,7 +5,7 @@
 
 namespace massv {
 
-struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, proj, partial, attn_ws, total; };
+struct LayerLayout { size_t xn, qkv, qrot, attn, h, gu, proj, h32, partial, attn_ws, total; };
 
 // The four projections of a layer as launch_gemm sees them (pointers filled in by the caller).
 struct LayerGemms { GemmArgs qkv, op, gu, dn; };
@@ -46,6 +46,7 @@ static LayerLayout layer_layout(const massv_layer_desc& d) {
     l.h = o;    o = align_up(o + Mp * d.mlp * es, 256);
     l.gu = o;   o = align_up(o + (bf ? 0 : M * 2 * d.mlp * 4), 256);
     l.proj = o; o = align_up(o + (bf ? 0 : M * d.hidden * 4), 256);   // fp32: a block's output ahead of its output norm
+    l.h32 = o;  o = align_up(o + (bf ? M * d.hidden * 4 : 0), 256);   // bf16: the stream between the two blocks, fp32
     l.partial = o; o = align_up(o + part, 256);
     l.attn_ws = o; o = align_up(o + attention_workspace(a), 256);
     l.total = o;
@@ -117,7 +118,7 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
     if ((rc = gemm_supported(g.dn)) != MASSV_OK) return rc;
 
     if (!bf) {
-        if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rmsnorm(x, w->ln1, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.qkv, st)) != MASSV_OK) return rc;
         if ((rc = launch_rope_append(ws + lay.qkv, pos, kv_len, ws + lay.qrot, k_cache, v_cache, w->q_norm, w->k_norm,
                                      desc->norm_eps, a, desc->rope_theta, st)) != MASSV_OK) return rc;
@@ -125,7 +126,7 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
         if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
         if (w->post_attn_norm &&
             (rc = launch_postnorm_residual(x, ws + lay.proj, w->post_attn_norm, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
-        if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, a.dtype, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rmsnorm(x, w->ln2, ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
         if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
         if (w->post_mlp_norm) return launch_postnorm_residual(x, ws + lay.proj, w->post_mlp_norm, M, H, desc->norm_eps, st);
@@ -141,11 +142,12 @@ static int run_layer(const massv_layer_desc* desc, const massv_layer_weights* w,
                                 desc->norm_eps, a, desc->rope_theta, st)) != MASSV_OK) return rc;
     if ((rc = launch_attention(a, ws + lay.qrot, k_cache, v_cache, kv_len, ws + lay.attn, ws + lay.attn_ws, true, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.op, st)) != MASSV_OK) return rc;
-    if ((rc = launch_residual_finish(partial, gemm_plan(g.op).slabs, Mp * H, x, w->post_attn_norm, w->ln2, ws + lay.xn,
-                                     M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
+    float* h32 = (float*)(ws + lay.h32);
+    if ((rc = launch_residual_finish(partial, gemm_plan(g.op).slabs, Mp * H, x, nullptr, h32, w->post_attn_norm, w->ln2,
+                                     ws + lay.xn, M, H, desc->norm_eps, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.gu, st)) != MASSV_OK) return rc;
     if ((rc = launch_gemm(g.dn, st)) != MASSV_OK) return rc;
-    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, w->post_mlp_norm, next_ln,
+    return launch_residual_finish(partial, gemm_plan(g.dn).slabs, Mp * H, x, h32, nullptr, w->post_mlp_norm, next_ln,
                                   next_ln ? ws + lay.xn : nullptr, M, H, desc->norm_eps, st);
 }
 
@@ -217,7 +219,7 @@ extern "C" int massv_lm_head_logits(const void* x, const void* final_norm, const
         if ((rc = launch_rmsnorm_packed(x, final_norm, workspace, M, H, norm_eps, st)) != MASSV_OK) return rc;
         g.x = workspace;
     } else if (final_norm) {
-        if ((rc = launch_rmsnorm(x, final_norm, workspace, M, H, norm_eps, dtype, st)) != MASSV_OK) return rc;
+        if ((rc = launch_rmsnorm(x, final_norm, workspace, M, H, norm_eps, st)) != MASSV_OK) return rc;
         g.x = workspace;
     }
     g.w[0] = w_lm; g.n[0] = V; g.y = logits; g.M = M; g.K = H;

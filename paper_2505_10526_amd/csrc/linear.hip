@@ -19,6 +19,8 @@
 // and then has to shuffle 256 accumulator registers every iteration.
 #include "kernels.h"
 
+#include <atomic>
+
 namespace massv {
 
 constexpr int kLinTile = 256;            // rows / features per workgroup
@@ -162,8 +164,16 @@ void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict
         step(ks + 1, gB, gA);
     }
     if (ks < KS2) step(ks, gA, gB);
-    // the compiler does not know that the assembly above is a matrix instruction whose result arrives late
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // The matrix instructions above are assembly the compiler cannot see into: it does not know that their results
+    // arrive up to 16 passes (64 cycles) after issue, so it inserts no wait before the epilogue reads the
+    // accumulators.  The wait is written here -- 4 x 16 idle cycles -- and tied to the data: the two statements take
+    // every accumulator as an in/out operand, so neither a matrix instruction nor an accumulator read can be
+    // scheduled across them (two statements because one takes at most 30 operands; volatile keeps their order).
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
+                 : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                   "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]));
+    asm volatile("" : "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                      "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
 
     // epilogue: lane holds features 32 i + 8 g + 4 (lane / 32) + r (g, r = 0..3) of row 32 j + lane % 32
 #pragma unroll
@@ -218,15 +228,15 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     if (!x || !w || !y) return MASSV_EINVAL;
     if (!workspace || workspace_bytes < massv_linear_workspace(M, N, K, dtype)) return MASSV_EWORKSPACE;
     // the tile kernel needs more LDS than a kernel gets by default: raise its limit once per device
-    static bool lds_ready[64] = {};
+    static std::atomic<bool> lds_ready[64];       // zero-initialised; calls may come from several threads
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
-    if (!lds_ready[dev]) {
+    if (!lds_ready[dev].load(std::memory_order_acquire)) {
         const void* kernels[4] = {(const void*)linear_tile_kernel<MASSV_LIN_NONE>, (const void*)linear_tile_kernel<MASSV_LIN_SILU>,
                                   (const void*)linear_tile_kernel<MASSV_LIN_GELU_TANH>, (const void*)linear_tile_kernel<MASSV_LIN_GELU_ERF>};
         for (const void* k : kernels)
             if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLds) != hipSuccess) return MASSV_ELAUNCH;
-        lds_ready[dev] = true;
+        lds_ready[dev].store(true, std::memory_order_release);
     }
     hipStream_t st = (hipStream_t)stream;
     const size_t chunks = packed_elems(M, K) / 8;
