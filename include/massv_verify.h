@@ -271,6 +271,32 @@ int massv_spec_accept(const float* target_logits, const float* draft_logits,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- */
+/* spec_accept_static: massv_spec_accept for callers that cannot allocate or   */
+/* carry a workspace -- code under HIP graph capture, tight serving loops,     */
+/* harnesses that forbid hipMalloc.  Same arguments without the workspace,     */
+/* same kernels, bit-identical results.  The partial results of the call       */
+/* (per-chunk row statistics, the per-sequence selection records, per-chunk    */
+/* residual masses) live in a fixed array of MASSV_SPEC_ACCEPT_STATIC_BYTES of */
+/* device memory inside the library; every GPU the library is used on holds    */
+/* its own copy until the process ends.  The call allocates and frees nothing. */
+/*   - Sizes whose scratch need, massv_spec_accept_workspace(B, gamma, V),     */
+/*     exceeds the array return MASSV_EUNSUPPORTED before anything is launched */
+/*     (the long-context shape B=32, gamma=7, V=152064 needs 1.2 MB).          */
+/*   - All calls on one GPU share that GPU's array: calls that overlap in time */
+/*     on one GPU (two streams, two threads) race; serialise them.  The array  */
+/*     keeps the last call's contents; nothing in it needs clearing, every     */
+/*     record read is written earlier in the same call.                       */
+/*   - The first call on a device looks the array's address up (no allocation);*/
+/*     make that call before a stream capture begins.                          */
+/* ------------------------------------------------------------------------- */
+#define MASSV_SPEC_ACCEPT_STATIC_BYTES (4u << 20)
+size_t massv_spec_accept_static_limit(void);      /* = MASSV_SPEC_ACCEPT_STATIC_BYTES */
+int massv_spec_accept_static(const float* target_logits, const float* draft_logits,
+                             const int32_t* draft_tokens, const float* uniforms,
+                             float temperature, int32_t B, int32_t gamma, int32_t V,
+                             int32_t* n_accepted, int32_t* out_tokens, void* stream);
+
+/* ------------------------------------------------------------------------- */
 /* lm_head_greedy_accept: massv_lm_head_logits followed by massv_spec_accept   */
 /* at temperature 0 (Section 2.1: a draft is kept iff it is the arg-max of the */
 /* target's distribution at its position), without writing the logits: the     */

@@ -31,6 +31,7 @@ EXPORTS = [
     "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
     "massv_linear_workspace", "massv_linear",
     "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
+    "massv_spec_accept_static_limit", "massv_spec_accept_static",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR = range(10)
 LIN_NONE, LIN_SILU, LIN_GELU_TANH, LIN_GELU_ERF = range(4)
@@ -102,6 +103,10 @@ def load():
     lib.massv_spec_accept_workspace.argtypes = [i32, i32, i32]
     lib.massv_spec_accept.restype = C.c_int
     lib.massv_spec_accept.argtypes = [vp, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.massv_spec_accept_static_limit.restype = sz
+    lib.massv_spec_accept_static_limit.argtypes = []
+    lib.massv_spec_accept_static.restype = C.c_int
+    lib.massv_spec_accept_static.argtypes = [vp, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]
     lib.massv_weight_pack.restype = C.c_int
     lib.massv_weight_pack.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.massv_trace_kernel.restype = C.c_int
@@ -390,6 +395,19 @@ def spec_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature
     _check(lib.massv_spec_accept(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(uniforms),
                                  float(temperature), B, gamma, V, _ptr(n_accepted), _ptr(out_tokens),
                                  _ptr(ws), ws.numel(), _stream()), "massv_spec_accept")
+    return n_accepted, out_tokens
+
+
+def spec_accept_static(target_logits, draft_logits, draft_tokens, uniforms, temperature, n_accepted, out_tokens):
+    """massv_spec_accept_static: as spec_accept, scratch space inside the library; the caller passes every
+    tensor, outputs included (this wrapper allocates nothing either)."""
+    _need(target_logits, "target_logits", torch.float32)
+    _need(n_accepted, "n_accepted", torch.int32)
+    _need(out_tokens, "out_tokens", torch.int32)
+    B, Q, V = target_logits.shape
+    _check(load().massv_spec_accept_static(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(uniforms),
+                                           float(temperature), B, Q - 1, V, _ptr(n_accepted), _ptr(out_tokens),
+                                           _stream()), "massv_spec_accept_static")
     return n_accepted, out_tokens
 
 

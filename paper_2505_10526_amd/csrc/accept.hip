@@ -20,6 +20,7 @@
 #include "kernels.h"
 
 #include <limits.h>
+#include <atomic>
 
 namespace massv {
 
@@ -514,6 +515,44 @@ extern "C" int massv_spec_accept(const float* target_logits, const float* draft_
     if (!workspace || workspace_bytes < accept_layout(B, gamma, V).total) return MASSV_EWORKSPACE;
     return run_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V, n_accepted,
                       out_tokens, workspace, (hipStream_t)stream);
+}
+
+// ---- the same call for callers that cannot allocate: scratch space inside the library ----
+// A fixed array in device memory replaces the workspace argument.  Each GPU the library is used on holds its own
+// copy of the array at its own address for the life of the process; the address is asked for once per device, with
+// that device current, and kept.  In host code the array's name is only a handle for that query, never an address.
+constexpr size_t kStaticScratchBytes = MASSV_SPEC_ACCEPT_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static std::atomic<void*> scratch_ptr[64];        // per device; zero-initialised
+
+static int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
+    void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {                                   // two threads may both ask; they get the same answer
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MASSV_ELAUNCH;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return MASSV_OK;
+}
+
+extern "C" size_t massv_spec_accept_static_limit(void) { return kStaticScratchBytes; }
+
+extern "C" int massv_spec_accept_static(const float* target_logits, const float* draft_logits,
+                                        const int32_t* draft_tokens, const float* uniforms,
+                                        float temperature, int32_t B, int32_t gamma, int32_t V,
+                                        int32_t* n_accepted, int32_t* out_tokens, void* stream) {
+    int rc = check_accept_args(target_logits, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V,
+                               n_accepted, out_tokens);
+    if (rc != MASSV_OK) return rc;
+    if (accept_layout(B, gamma, V).total > kStaticScratchBytes) return MASSV_EUNSUPPORTED;   // use massv_spec_accept
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != MASSV_OK) return rc;
+    // nothing has to start at zero: every record the later kernels read is written by an earlier kernel of this call
+    return run_accept(target_logits, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V, n_accepted,
+                      out_tokens, ws, (hipStream_t)stream);
 }
 
 namespace massv {
