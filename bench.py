@@ -139,7 +139,8 @@ def main():
     pos = torch.from_numpy(synth.positions(kv_len_h, n_img_h, Q)).to(dev)
 
     layers = []
-    for _ in range(N):
+    raw0 = None                                  # layer 0 before packing, kept for the parity leg
+    for li in range(N):
         w = {"ln1": randn(H, std=0.1, mean=1.0), "wq": randn(nq, H, std=0.02), "wk": randn(nkv, H, std=0.02),
              "wv": randn(nkv, H, std=0.02), "wo": randn(H, nq, std=0.02), "ln2": randn(H, std=0.1, mean=1.0),
              "wg": randn(F, H, std=0.02), "wu": randn(F, H, std=0.02), "wd": randn(H, F, std=0.02),
@@ -147,14 +148,20 @@ def main():
         if shape.qkv_bias:
             w.update(bq=randn(nq, std=0.02), bk=randn(nkv, std=0.02), bv=randn(nkv, std=0.02))
         kc = randn(B, shape.n_kv_heads, l_max, d)
-        vc = binding.v_cache_pack(randn(B, shape.n_kv_heads, l_max, d))
+        vc_rows = randn(B, shape.n_kv_heads, l_max, d)
         for b in range(B):                       # image rows carry a wider spread (input recipe)
             kc[b, :, : int(n_img_h[b])] *= 1.5
+        if li == 0 and not args.no_cpu:
+            raw0 = {"w": w, "k": kc.clone(), "v": vc_rows}
+        vc = binding.v_cache_pack(vc_rows)
         kc = binding.k_cache_pack(kc)
         w = binding.pack_layer_weights(w)           # projection matrices -> streaming layout (load-time step)
         layers.append((w, binding.layer_weights(w), kc, vc))
     final_norm = randn(H, std=0.1, mean=1.0)
-    w_lm = binding.weight_pack(randn(V, H, std=0.02))
+    w_lm_rows = randn(V, H, std=0.02)
+    w_lm = binding.weight_pack(w_lm_rows)
+    if args.no_cpu:
+        del w_lm_rows
     x0 = randn(B, Q, H)
     x = torch.empty_like(x0)
     logits = torch.empty((M, V), dtype=torch.float32, device=dev)
@@ -249,6 +256,14 @@ def main():
                 "achieved_TFLOPs": round(2.0 * M * 2 * F * H / (k_ms * 1e-3) / 1e12, 1),
                 "mfma_cap_TFLOPs_at_this_M": round(M * HBM_PEAK_GBS / 1e3, 1),     # M flops per weight byte x 8 TB/s
                 "step_weight_stream_GBps": round(weight_bytes_step / (ms_per_step * 1e-3) / 1e9, 1)}
+    # the whole step against the same roof: every byte the step has to move once (weights, the caches of all layers,
+    # the fp32 logits written and read back by the accept call)
+    kv_bytes_step = N * int(sum(2 * (int(L) + Q) * nkv * 2 for L in kv_len_h))
+    logit_bytes_step = 2 * M * V * 4
+    step_bytes = weight_bytes_step + kv_bytes_step + logit_bytes_step
+    roofline["whole_step"] = {"what": "all launches of one step; the figure above is the gate/up kernel's alone",
+                              "bytes": step_bytes, "achieved": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                              "unit": "GB/s", "frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
     # "peaked" variant of the same step: target logits x 8 before the same draft noise is added, which puts the
     # accepted lengths in the regime the paper reports (tau 2.5-3.3) instead of ~0; the step time does not depend
@@ -289,7 +304,10 @@ def main():
         result["extra"] = extra_bandwidth(torch, binding, synth, dev, gen)
         result["extra"]["linear_prefill"] = lin
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, args.seed)
+        par, cpu = cpu_legs(torch, binding, wl, shape, cfg, raw0, layers[0], x0, x, pos, kv_len, kv_len_h, l_max,
+                            final_norm, w_lm_rows, logits, draft_logits, draft_tokens, uniforms, n_acc, out_tok, T, ws)
+        result["parity"] = par
+        result["cpu_baseline"] = cpu
     print(json.dumps(result))
 
 
@@ -541,47 +559,106 @@ def extra_bandwidth(torch, binding, synth, dev, gen):
     }
 
 
-def cpu_baseline(synth, wl, shape, kv_len_h, n_img_h, seed):
-    """The CPU checker, as it stands, on a bounded sample of the same workload: decoder-layer passes over all
-    sequences until about 10 s have gone by (at most the workload's layer count; one layer's synthetic weights
-    are reused, the arithmetic per pass is that of any layer), the vocabulary projection and the accept step.
-    The mean pass time is scaled by the layer count."""
+def cpu_legs(torch, binding, wl, shape, cfg, raw0, layer0, x0, x_final, pos, kv_len, kv_len_h, l_max,
+             final_norm, w_lm_rows, logits, draft_logits, draft_tokens, uniforms, n_acc, out_tok, T, ws):
+    """The CPU checker on the very tensors the timed step ran on (downloaded from the device), outside the timed
+    region.  Returns (parity, cpu_baseline).
+
+    parity: layer 0 (the timed stack's first layer, re-run alone on the step's input x0; the cache rows the timed
+    run itself appended in layer 0), the vocabulary projection (the timed run's final hidden rows -> its logits) and
+    the accept rule (the timed run's logits and drafts -> its n_accepted / out_tokens).  The 27 layers between are
+    covered by the chain test, not here: the checker would need every layer's weights on the host.
+    cpu_baseline: the same checker calls timed -- pinned to one thread, then with all cores -- on a bounded sample:
+    one layer pass (single thread) / layer passes until ~10 s (all cores) with layer 0's weights, scaled by the
+    layer count, + the vocabulary projection + the accept rule."""
     from oracle import verify_oracle as O
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = 1
+    from threadpoolctl import threadpool_limits, threadpool_info
     B, gamma, N = wl["batch"], wl["gamma"], wl["layers"]
     Q = gamma + 1
-    w = synth.layer_weights(shape, seed)
-    kv = synth.kv_cache(shape, B, Q, kv_len_h, n_img_h, seed, junk_tail=False)
-    x = synth.hidden_states(shape, B, Q, seed)
-    pos = synth.positions(kv_len_h, n_img_h, Q)
-    t_layers, passes, y = 0.0, 0, x
+    f32 = lambda t: t.float().cpu().numpy()
+    rel = lambda g, r: float(np.max(np.abs(np.asarray(g, np.float64) - r)) / max(np.max(np.abs(r)), 1e-30))
+    cores = len(os.sched_getaffinity(0))
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
+
+    # ---- layer 0 ----
+    w = {k: (None if v is None else f32(v)) for k, v in raw0["w"].items()}
+    xh, kh, vh, posh = f32(x0), f32(raw0["k"]), f32(raw0["v"]), pos.cpu().numpy()
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        y_ref, k_ref, v_ref = O.verify_layer(shape, w, xh, posh, kh, vh, kv_len_h)
+        t_layer_1 = time.perf_counter() - t0
+    x1 = x0.clone()
+    stack1 = binding.LayerStack([layer0[1]], [layer0[2]], [layer0[3]])
+    desc1 = binding.layer_desc(cfg, B, Q, l_max, binding.BF16)
+    binding.verify_layers(cfg, stack1, x1, pos, kv_len, l_max, ws=ws, desc=desc1)
+    torch.cuda.synchronize()
+    e_layer = rel(f32(x1), y_ref)
+    # cache rows appended by the timed run (library layouts -> rows)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    k_rows = layer0[2].reshape(B, nkv, l_max // 32, 2, d // 8, 4, 4, 8).permute(0, 1, 2, 5, 3, 6, 4, 7).reshape(B, nkv, l_max, d)
+    v_rows = layer0[3].permute(0, 1, 2, 4, 3).reshape(B, nkv, l_max, d)
+    kg, vg = f32(k_rows), f32(v_rows)
+    e_k = max(rel(kg[b, :, L:L + Q], k_ref[b, :, L:L + Q]) for b, L in enumerate(int(v) for v in kv_len_h))
+    e_v = max(rel(vg[b, :, L:L + Q], v_ref[b, :, L:L + Q]) for b, L in enumerate(int(v) for v in kv_len_h))
+    # all cores: passes with the same weights until ~10 s have gone by
+    t_layers, passes, y = 0.0, 0, xh
     while passes < N and t_layers < 10.0:
         t0 = time.perf_counter()
-        y, _, _ = O.verify_layer(shape, w, y, pos, kv.k, kv.v, kv.kv_len)
+        y, _, _ = O.verify_layer(shape, w, y, posh, kh, vh, kv_len_h)
         t_layers += time.perf_counter() - t0
         passes += 1
-    t_layer = t_layers / passes
-    del w, kv
-    lw = synth.lm_head_weights(shape, seed)
+    t_layer_n = t_layers / passes
+    del w, kh, vh, kg, vg
+
+    # ---- vocabulary projection on the timed run's final hidden rows ----
+    xf, gn, wl_h = f32(x_final).reshape(B * Q, -1), f32(final_norm), f32(w_lm_rows)
     t0 = time.perf_counter()
-    logits = O.lm_head_logits(y.reshape(B * Q, -1), lw["final_norm"], lw["w_lm"], shape.norm_eps)
-    t_lm = time.perf_counter() - t0
-    del lw
-    a = synth.accept_inputs(B, gamma, shape.vocab, wl["temperature"], seed, noise_std=wl["noise"],
-                            target_logits=logits.astype(np.float32))
+    logits_ref = O.lm_head_logits(xf, gn, wl_h, shape.norm_eps)
+    t_lm_n = time.perf_counter() - t0
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        O.lm_head_logits(xf, gn, wl_h, shape.norm_eps)
+        t_lm_1 = time.perf_counter() - t0
+    del wl_h
+    lg = logits.cpu().numpy()
+    e_logits = rel(lg, logits_ref)
+    del logits_ref
+
+    # ---- accept rule on the timed run's own logits ----
+    tl = lg.reshape(B, Q, -1)
+    dl = draft_logits.cpu().numpy() if T > 0 else None
+    u = uniforms.cpu().numpy() if T > 0 else None
     t0 = time.perf_counter()
-    n, _, _ = O.spec_accept(a.target_logits, a.draft_logits, a.draft_tokens, a.uniforms, wl["temperature"])
+    n_ref, out_ref, margin = O.spec_accept(tl, dl, draft_tokens.cpu().numpy(), u, T)
     t_acc = time.perf_counter() - t0
-    t_step = N * t_layer + t_lm + t_acc
-    return {"value": round(float((n + 1).sum()) / t_step, 3), "unit": "tokens/s", "cores": int(cores),
-            "kind": "oracle",
-            "sample": f"{passes} of {N} layer passes (all {B} sequences) timed {t_layers:.2f}s, mean scaled x{N}, "
-                      f"+ lm_head {t_lm:.2f}s + accept {t_acc:.2f}s; float64 NumPy",
-            "est_ms_per_step": round(t_step * 1e3, 1)}
+    n_g, out_g = n_acc.cpu().numpy(), out_tok.cpu().numpy()
+    clear = bool(np.all(margin > 1e-5))
+    parity = {"what": "CPU checker on the tensors of the timed run: layer 0 re-run alone on the step's input, the cache "
+                      "rows the timed run appended in layer 0, its logits from its final hidden rows, its accept outputs "
+                      "from its logits",
+              "layer0_max_rel_err": round(e_layer, 5), "appended_k_max_rel_err": round(e_k, 5),
+              "appended_v_max_rel_err": round(e_v, 5), "logits_max_rel_err": round(e_logits, 5), "bound": 2e-2,
+              "n_accepted_equal": bool(np.array_equal(n_g, n_ref)), "out_tokens_equal": bool(np.array_equal(out_g, out_ref)),
+              "decision_margins_clear": clear,
+              "ok": bool(max(e_layer, e_k, e_v, e_logits) <= 2e-2 and np.array_equal(n_g, n_ref) and
+                         (np.array_equal(out_g, out_ref) or not clear))}
+    emitted = float((n_ref + 1).sum())
+    t_step_n = N * t_layer_n + t_lm_n + t_acc
+    t_step_1 = N * t_layer_1 + t_lm_1 + t_acc
+    blas = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    cpu = {"value": round(emitted / t_step_n, 3), "unit": "tokens/s", "cores": int(min(cores, blas)), "kind": "oracle",
+           "sample": f"all cores: {passes} of {N} layer passes (all {B} sequences, layer 0's weights) timed {t_layers:.2f}s, "
+                     f"mean scaled x{N}, + lm_head {t_lm_n:.2f}s + accept {t_acc:.2f}s; float64 NumPy on the timed run's tensors",
+           "est_ms_per_step": round(t_step_n * 1e3, 1),
+           "single_thread": {"value": round(emitted / t_step_1, 4), "cores": 1, "est_ms_per_step": round(t_step_1 * 1e3, 1),
+                             "sample": f"1 layer pass {t_layer_1:.2f}s scaled x{N} + lm_head {t_lm_1:.2f}s + accept {t_acc:.2f}s"},
+           "affinity_cores": cores, "cpu_model": cpu_model}
+    return parity, cpu
 
 
 if __name__ == "__main__":

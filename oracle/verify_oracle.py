@@ -50,6 +50,11 @@ What it leaves open, and the reading taken here:
       before the rotary embedding; (c) an RMSNorm of the attention block's and
       of the MLP block's output before each is added to the residual stream.
       All are optional and off for the Qwen-shaped configurations.
+  R14 Prompt pass (Section 2.2): the image features are ordinary positions of the
+      sequence placed ahead of the text, attended causally like any other
+      position.  Optionally (off by default) the leading image block attends
+      within itself in both directions, as the Gemma 3 family's public
+      description has it; the paper does not say.
 
 Pins (tests/test_oracle_*.py): brute-force attention loops, closed forms for
 constant keys / values, causality and grouped-head invariants, equivalence of
@@ -181,6 +186,39 @@ def attention(q, k_cache, v_cache, kv_len, scale=None, window=0):
                 lo = max(0, n_vis - int(window)) if window else 0
                 s = scale * (k_cache[b, g, lo:n_vis] @ q[b, i, h])
                 out[b, i, h] = softmax(s) @ v_cache[b, g, lo:n_vis]
+    return out
+
+
+def prefill_attention(q, k_cache, v_cache, kv_len, n_new, scale=None, window=0, n_bidir=None):
+    """Attention of the prompt pass that fills the cache (Section 2.2: the m projected image features V_1..V_m
+    enter the sequence ahead of the text tokens and the language model conditions on all of them): many new
+    positions per sequence instead of gamma+1, otherwise the definition of `attention`.
+
+    q: [B, L_q, n_q, d], of which rows i < n_new[b] are sequence b's new positions; k_cache, v_cache:
+    [B, n_kv, L_max, d] with rows [0, kv_len[b] + n_new[b]) valid (the new positions already appended; kv_len[b] > 0
+    when the prompt is fed in several pieces).  The query at cache row r = kv_len[b] + i sees rows 0 .. r (reading R1).
+    window W > 0: rows max(0, r - W + 1) .. r only (R13a).  n_bidir[b] = m (R14, optional): the first m rows are an
+    image-token block whose members see the whole block, i.e. a query at row r < m sees rows 0 .. m-1.
+    Returns [B, L_q, n_q, d] float64; rows i >= n_new[b] are zero."""
+    q = np.asarray(q, dtype=np.float64)
+    k_cache = np.asarray(k_cache, dtype=np.float64)
+    v_cache = np.asarray(v_cache, dtype=np.float64)
+    B, Lq, n_q, d = q.shape
+    G = n_q // k_cache.shape[1]
+    if scale is None or scale == 0:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros_like(q)
+    for b in range(B):
+        L, n = int(kv_len[b]), int(n_new[b])
+        m = int(n_bidir[b]) if n_bidir is not None else 0
+        for i in range(n):
+            r = L + i
+            hi = max(r + 1, min(m, L + n)) if r < m else r + 1        # one past the last visible row
+            lo = max(0, r + 1 - int(window)) if window else 0
+            for h in range(n_q):
+                g = h // G
+                s = scale * (k_cache[b, g, lo:hi] @ q[b, i, h])
+                out[b, i, h] = softmax(s) @ v_cache[b, g, lo:hi]
     return out
 
 

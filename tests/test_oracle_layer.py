@@ -446,3 +446,99 @@ def test_gelu_erf_and_projector_against_torch():
     mid = torch.nn.functional.gelu(T(h) @ T(w1).T + T(b1)).to(torch.bfloat16).double()
     want = (mid @ T(w2).T + T(b2)).numpy()
     np.testing.assert_allclose(O.projector_mlp(h, w1, b1, w2, b2, "bf16"), want, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# prompt-pass attention (Section 2.2: image positions ahead of the text)
+# ---------------------------------------------------------------------------
+def prefill_case(seed=0, B=2, Lq=9, n_q=4, n_kv=2, d=8, kv_len=(0, 3), n_new=(9, 5)):
+    rng = np.random.default_rng(seed)
+    L_max = max(a + b for a, b in zip(kv_len, n_new)) + 2
+    q = rng.standard_normal((B, Lq, n_q, d))
+    k = rng.standard_normal((B, n_kv, L_max, d))
+    v = rng.standard_normal((B, n_kv, L_max, d))
+    return q, k, v, np.array(kv_len), np.array(n_new)
+
+
+def brute_prefill(q, k, v, kv_len, n_new, scale, W=0, n_bidir=None):
+    """Scalar loops, no matrix products: weights exp(s_j - max) over the visible rows, normalised."""
+    B, Lq, n_q, d = q.shape
+    G = n_q // k.shape[1]
+    out = np.zeros_like(q)
+    for b in range(B):
+        for i in range(int(n_new[b])):
+            r = int(kv_len[b]) + i
+            for h in range(n_q):
+                vis = []
+                for j in range(int(kv_len[b]) + int(n_new[b])):
+                    causal = j <= r
+                    if n_bidir is not None and r < n_bidir[b] and j < n_bidir[b]:
+                        causal = True
+                    if causal and (W == 0 or j > r - W):
+                        vis.append(j)
+                s = [scale * sum(q[b, i, h, c] * k[b, h // G, j, c] for c in range(d)) for j in vis]
+                mx = max(s)
+                e = [math.exp(t - mx) for t in s]
+                z = sum(e)
+                for c in range(d):
+                    out[b, i, h, c] = sum(e[t] * v[b, h // G, j, c] for t, j in enumerate(vis)) / z
+    return out
+
+
+@pytest.mark.parametrize("W", [0, 1, 3, 100])
+def test_prefill_attention_matches_brute_force(W):
+    q, k, v, kv_len, n_new = prefill_case()
+    got = O.prefill_attention(q, k, v, kv_len, n_new, window=W)
+    np.testing.assert_allclose(got, brute_prefill(q, k, v, kv_len, n_new, 1 / math.sqrt(8), W), rtol=1e-12, atol=1e-14)
+    assert np.all(got[1, 5:] == 0)                               # rows past n_new[b] are not positions
+    nb = np.array([4, 6])                                        # image block of 4 / 6 rows, the second straddles the cached piece
+    got = O.prefill_attention(q, k, v, kv_len, n_new, window=W, n_bidir=nb)
+    np.testing.assert_allclose(got, brute_prefill(q, k, v, kv_len, n_new, 1 / math.sqrt(8), W, nb), rtol=1e-12, atol=1e-14)
+
+
+def test_prefill_attention_against_library_causal_attention():
+    """A fresh prompt (nothing cached, every row a position) is plain causal attention: torch's
+    scaled_dot_product_attention in float64 with the KV heads repeated over their query-head groups."""
+    import torch
+    q, k, v, _, _ = prefill_case(seed=3, B=2, Lq=12, n_q=6, n_kv=2, d=16, kv_len=(0, 0), n_new=(12, 12))
+    got = O.prefill_attention(q, k[:, :, :12], v[:, :, :12], [0, 0], [12, 12])
+    tq = torch.from_numpy(q).permute(0, 2, 1, 3)
+    tk = torch.from_numpy(k[:, :, :12]).repeat_interleave(3, dim=1)
+    tv = torch.from_numpy(v[:, :, :12]).repeat_interleave(3, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+    # image block of 5 rows attending within itself: an explicit boolean mask
+    mask = torch.tril(torch.ones(12, 12, dtype=torch.bool))
+    mask[:5, :5] = True
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask).permute(0, 2, 1, 3).numpy()
+    got = O.prefill_attention(q, k[:, :, :12], v[:, :, :12], [0, 0], [12, 12], n_bidir=[5, 5])
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+def test_prefill_attention_closed_forms_and_invariants():
+    q, k, v, kv_len, n_new = prefill_case(seed=4)
+    # equal keys: every visible row has the same weight, so the output is the mean of the visible value rows --
+    # this pins the COUNT of visible rows (kv_len + i + 1) and the mapping of query heads to KV heads
+    k_const = np.broadcast_to(k[:, :, :1], k.shape)
+    got = O.prefill_attention(q, k_const, v, kv_len, n_new)
+    for b in range(2):
+        for i in range(int(n_new[b])):
+            r = int(kv_len[b]) + i
+            for h in range(4):
+                np.testing.assert_allclose(got[b, i, h], v[b, h // 2, :r + 1].mean(0), rtol=1e-12)
+    # causality: rows after a query's own row do not influence it
+    k2, v2 = k.copy(), v.copy()
+    k2[:, :, 6:] += 100.0
+    v2[:, :, 6:] -= 50.0
+    a, b_ = O.prefill_attention(q, k, v, kv_len, n_new), O.prefill_attention(q, k2, v2, kv_len, n_new)
+    assert np.array_equal(a[0, :6], b_[0, :6])                   # sequence 0: rows 0..5
+    assert np.array_equal(a[1, :3], b_[1, :3])                   # sequence 1 starts at row 3: rows 3..5
+    assert not np.allclose(a[0, 6:], b_[0, 6:])
+    # the prompt fed in two pieces equals the prompt fed at once (Section 2.1: a position conditions on all earlier ones,
+    # however they got into the cache)
+    whole = O.prefill_attention(q[:1], k[:1], v[:1], [0], [9])
+    first = O.prefill_attention(q[:1, :4], k[:1], v[:1], [0], [4])
+    second = O.prefill_attention(q[:1, 4:], k[:1], v[:1], [4], [5])
+    np.testing.assert_allclose(np.concatenate([first[:, :4], second[:, :5]], 1), whole, rtol=1e-13)
+    # and the verify pass is the same definition with gamma+1 new positions
+    np.testing.assert_allclose(O.prefill_attention(q[:, :5], k, v, kv_len, [5, 5]), O.attention(q[:, :5], k, v, kv_len), rtol=1e-13)
