@@ -107,11 +107,12 @@ def main():
     if args.workload == "sd_iteration":
         print(json.dumps(iteration_bench(torch, binding, synth, dev, args)))
         return
-    lin = None
+    lin = pfa = None
     if not args.no_extra:
         g0 = torch.Generator(device=dev)
         g0.manual_seed(args.seed + 1)
         lin = linear_prefill(torch, binding, synth, dev, g0)
+        pfa = prefill_attention_bench(torch, binding, synth, dev, g0)
     wl = dict(WORKLOADS[args.workload])
     if args.layers:
         wl["layers"] = args.layers
@@ -303,6 +304,7 @@ def main():
     if not args.no_extra:
         result["extra"] = extra_bandwidth(torch, binding, synth, dev, gen)
         result["extra"]["linear_prefill"] = lin
+        result["extra"]["prefill_attention"] = pfa
     if not args.no_cpu:
         par, cpu = cpu_legs(torch, binding, wl, shape, cfg, raw0, layers[0], x0, x, pos, kv_len, kv_len_h, l_max,
                             final_norm, w_lm_rows, logits, draft_logits, draft_tokens, uniforms, n_acc, out_tok, T, ws)
@@ -475,6 +477,28 @@ def linear_prefill(torch, binding, synth, dev, gen):
             "call_us": st["median_us"], "p10_us": st["p10_us"], "p90_us": st["p90_us"], "mean_back_to_back_us": round(lin_ms * 1e3, 1),
             "what": "whole call: operand re-layout kernel (about 25 us) + tile kernel",
             "TFLOPs": round(lin_flops / t / 1e12, 1), "peak_TFLOPs": 2500.0, "frac_of_bf16_peak": round(lin_flops / t / 2.5e15, 4)}
+
+
+def prefill_attention_bench(torch, binding, synth, dev, gen):
+    """Prompt-pass attention (compute-bound): 8 fresh prompts of 2048 positions (1280 image rows first), 28/4 heads,
+    d=128, causal.  Flops = 4 d n_q sum_i (visible keys of position i)."""
+    s = synth.QWEN7B
+    bf = torch.bfloat16
+    B, L = 8, 2048
+    q = torch.randn(B, L, s.n_q_heads, s.head_dim, generator=gen, device=dev).to(bf)
+    k = binding.k_cache_pack(torch.randn(B, s.n_kv_heads, L, s.head_dim, generator=gen, device=dev).to(bf))
+    v = binding.v_cache_pack(torch.randn(B, s.n_kv_heads, L, s.head_dim, generator=gen, device=dev).to(bf))
+    zero = torch.zeros(B, dtype=torch.int32, device=dev)
+    n_new = torch.full((B,), L, dtype=torch.int32, device=dev)
+    out = torch.empty_like(q)
+    st = {}
+    mean_ms = time_calls(torch, lambda: binding.prefill_attention(q, k, v, zero, n_new, out=out), 20, 5, stats=st)
+    flops = 4.0 * s.head_dim * s.n_q_heads * B * (L * (L + 1) / 2)
+    t = st["median_us"] * 1e-6
+    return {"shape": f"B={B}, {L} new positions each (fresh prompt), 28/4 heads, d=128, causal, bf16", "bound": "mfma",
+            "flops": flops, "call_us": st["median_us"], "p10_us": st["p10_us"], "p90_us": st["p90_us"],
+            "mean_back_to_back_us": round(mean_ms * 1e3, 1), "TFLOPs": round(flops / t / 1e12, 1),
+            "peak_TFLOPs": 2500.0, "frac_of_bf16_peak": round(flops / t / 2.5e15, 4)}
 
 
 def extra_bandwidth(torch, binding, synth, dev, gen):

@@ -129,6 +129,30 @@ int massv_verify_attention(const massv_attn_desc* desc, const void* q,
                            const int32_t* kv_len, void* out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------- */
+/* prefill_attention: the same attention for the prompt pass that fills the    */
+/* cache.  Section 2.2: the m projected image features V_1..V_m enter the      */
+/* sequence ahead of the text tokens and the language model conditions on all  */
+/* of them; here they are rows of the cache like any other position.  Sequence */
+/* b brings n_new[b] <= L_q new positions (their keys and values already at    */
+/* cache rows kv_len[b] .. kv_len[b]+n_new[b]-1; kv_len[b] > 0 when a prompt   */
+/* is fed in several pieces); the query at cache row r sees rows 0 .. r, with  */
+/* desc->window = W > 0 rows max(0, r-W+1) .. r only.  n_bidir (may be NULL):  */
+/* n_bidir[b] = m makes the first m cache rows of sequence b a block whose     */
+/* members see the whole block (a query at row r < m sees rows 0 .. m-1), the  */
+/* way the Gemma 3 family treats an image's positions; the paper itself does   */
+/* not say, the default is causal.                                             */
+/*   desc: n_query = L_q (rows allocated per sequence in q and out), the other */
+/*         fields as for verify_attention; no limit on G*L_q.  No workspace.   */
+/*   q, out [B][L_q][n_q][d] (dtype); rows i >= n_new[b] of out are not        */
+/*   written.  Caches in the layouts above.  kv_len, n_new, n_bidir [B] int32  */
+/*   device; kv_len[b] + n_new[b] <= l_max is the caller's duty (clamped).     */
+/* ------------------------------------------------------------------------- */
+int massv_prefill_attention(const massv_attn_desc* desc, const void* q,
+                            const void* k_cache, const void* v_cache,
+                            const int32_t* kv_len, const int32_t* n_new, const int32_t* n_bidir,
+                            void* out, void* stream);
+
 /* Row-major [B][n_kv][L_max][d] values -> blocked value-cache layout. src and
  * dst must not overlap. */
 int massv_v_cache_pack(const void* src_row_major, void* dst_blocked,
@@ -392,7 +416,8 @@ typedef enum {
     MASSV_K_LMHEAD = 6,       /* vocabulary projection of lm_head_logits */
     MASSV_K_ACCEPT_STATS = 7, /* pass 1 of spec_accept over all logit rows */
     MASSV_K_RESIDUAL_MASS = 8,/* pass 2 of spec_accept over the resampled rows */
-    MASSV_K_LINEAR = 9        /* the tile kernel of massv_linear */
+    MASSV_K_LINEAR = 9,       /* the tile kernel of massv_linear */
+    MASSV_K_PREFILL_ATTENTION = 10  /* the bf16 kernel of prefill_attention */
 } massv_kernel_id;
 
 int massv_trace_kernel(int kernel_id, void* start_event, void* stop_event);

@@ -31,9 +31,9 @@ EXPORTS = [
     "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
     "massv_linear_workspace", "massv_linear",
     "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
-    "massv_spec_accept_static_limit", "massv_spec_accept_static",
+    "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention",
 ]
-K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR = range(10)
+K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR, K_PREFILL_ATTENTION = range(11)
 LIN_NONE, LIN_SILU, LIN_GELU_TANH, LIN_GELU_ERF = range(4)
 
 
@@ -82,6 +82,8 @@ def load():
     lib.massv_verify_attention_workspace.argtypes = [C.POINTER(AttnDesc)]
     lib.massv_verify_attention.restype = C.c_int
     lib.massv_verify_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.massv_prefill_attention.restype = C.c_int
+    lib.massv_prefill_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     lib.massv_v_cache_pack.restype = C.c_int
     lib.massv_v_cache_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
     lib.massv_k_cache_pack.restype = C.c_int
@@ -225,6 +227,23 @@ def verify_attention(q, k_cache, v_cache, kv_len, scale=0.0, out=None, ws=None, 
         ws = workspace(need, q.device)
     _check(lib.massv_verify_attention(C.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
                                       _ptr(out), _ptr(ws), ws.numel(), _stream()), "massv_verify_attention")
+    return out
+
+
+def prefill_attention(q, k_cache, v_cache, kv_len, n_new, n_bidir=None, scale=0.0, out=None, window=0):
+    """q [B,L_q,n_q,d]; caches as for verify_attention; kv_len, n_new (and n_bidir) int32 [B].
+    Returns out [B,L_q,n_q,d]; rows i >= n_new[b] are left as they were (zeros for a fresh `out`)."""
+    for t, n in ((q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _need(t, n, q.dtype)
+    for t, n in ((kv_len, "kv_len"), (n_new, "n_new")) + (((n_bidir, "n_bidir"),) if n_bidir is not None else ()):
+        _need(t, n, torch.int32)
+    B, Lq, n_q, d = q.shape
+    n_kv, l_max = k_cache.shape[1], k_cache.shape[2]
+    desc = attn_desc(B, Lq, n_q, n_kv, d, l_max, dtype_code(q), scale, window)
+    if out is None:
+        out = torch.zeros_like(q)
+    _check(load().massv_prefill_attention(C.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
+                                          _ptr(n_new), _ptr(n_bidir), _ptr(out), _stream()), "massv_prefill_attention")
     return out
 
 

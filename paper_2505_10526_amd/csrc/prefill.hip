@@ -1,0 +1,328 @@
+// prefill_attention: attention of the prompt pass that fills the cache (paper Section 2.2: the projected image
+// features enter the sequence ahead of the text tokens, and the language model conditions on all of them).  Same
+// definition as verify_attention -- the query at cache row r sees rows 0 .. r -- but with hundreds to thousands
+// of new positions per sequence instead of gamma+1, so the work is a dense contraction and the matrix cores are
+// the roof, not HBM.
+//
+// bf16 kernel:
+//   * The caches are read in the library's blocked layouts, the same operand-order tiles verify_attention uses:
+//     a wave's key tile (16 keys x 32 dims) and value tile (16 dims x 32 keys) are each one 16-byte load per lane,
+//     no LDS staging and no transposes.
+//   * The G query heads that share a KV head are stacked with the positions into rows (row = position * G + head),
+//     so every key / value tile fetched serves all G heads.
+//   * A wave owns 16*MT stacked rows (64 for d <= 128) for the whole key range: Q stays in registers as the B
+//     operand, scores are formed transposed (S^T = K Q^T) so that the probabilities already sit in the operand
+//     layout of O^T += V^T P^T, and the streaming softmax keeps (reference, sum, O) in registers.  Nothing is
+//     merged between waves; each writes its own rows.  64 rows per wave is what makes the operand traffic
+//     affordable: a key tile loaded once is multiplied against four row tiles.
+//   * The four waves of a workgroup take neighbouring row ranges, so they walk the same key blocks at nearly
+//     the same time and share them through the CU's vector cache; workgroups of one (sequence, KV head) pair
+//     have linear ids congruent modulo the pair count, which (8 dies, round-robin dispatch) puts them on one
+//     die whenever the pair count is a multiple of 8, so the pair's keys and values are fetched into one L2.
+//   * Only blocks that cross some row's first or last visible key pay for masks.
+// fp32: the plain one-workgroup-per-(position, head) kernel below, for the small configuration.
+#include "kernels.h"
+
+namespace massv {
+
+constexpr int kPfWaves = 4;
+constexpr int kPfThreads = kPfWaves * kWave;
+constexpr int kPfBlk = MASSV_V_BLOCK;
+
+struct PrefillParams {
+    const bf16_t* q; const bf16_t* kc; const bf16_t* vc;
+    const int32_t* kv_len; const int32_t* n_new; const int32_t* n_bidir;     // n_bidir may be null
+    bf16_t* out;
+    int Lq, n_q, n_kv, l_max, window, n_tiles;
+    float scale_log2;            // scale * log2(e)
+};
+
+// One past the last row visible to the query at cache row r: r + 1, or the end of the leading block of m rows
+// that attends within itself when r lies inside it (never beyond the rows that exist, `total`).
+__host__ __device__ inline int pf_hi(int r, int m, int total) {
+    if (r < m) { const int e = m < total ? m : total; return e > r + 1 ? e : r + 1; }
+    return r + 1;
+}
+__host__ __device__ inline int pf_lo(int r, int W) { return (W > 0 && r + 1 > W) ? r + 1 - W : 0; }
+
+__device__ inline float pf_xor16_max(float v) {
+    v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    return fmaxf(v, __shfl_xor(v, 32, kWave));
+}
+__device__ inline float pf_xor16_sum(float v) {
+    v += __shfl_xor(v, 16, kWave);
+    return v + __shfl_xor(v, 32, kWave);
+}
+
+template <int D, int MT>
+__global__ __launch_bounds__(kPfThreads)
+void prefill_attention_kernel(PrefillParams p) {
+    constexpr int KS = D / 32;          // k-steps of the score product
+    constexpr int NT = D / 16;          // 16-dim tiles of the output
+    constexpr int RW = MT * 16;         // stacked rows per wave
+    const int pair = blockIdx.x, b = pair / p.n_kv, g = pair % p.n_kv;
+    const int tile = p.n_tiles - 1 - (int)blockIdx.y;                 // the longest key ranges are started first
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int lr = lane % 16, lc = lane / 16;
+    const int G = p.n_q / p.n_kv;
+    int L = p.kv_len[b]; L = L < 0 ? 0 : L;
+    int n = p.n_new[b]; n = n < 0 ? 0 : (n > p.Lq ? p.Lq : n);
+    if (L + n > p.l_max) n = p.l_max - L > 0 ? p.l_max - L : 0;
+    const int rows = n * G;
+    const int r0 = (tile * kPfWaves + wave) * RW;                     // first stacked row of this wave
+    if (r0 >= rows) return;                                            // (no barriers below: waves are independent)
+    const int total = L + n;
+    const int m_bidir = p.n_bidir ? p.n_bidir[b] : 0;
+    const int W = p.window;
+    const size_t bg = (size_t)b * p.n_kv + g;
+
+    // ---- rows of this wave: position, visible key range; Q operand in registers ----
+    bf16x8 qreg[MT][KS];
+    int hi_row[MT], lo_row[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int r = r0 + mt * 16 + lr;
+        if (r >= rows) r = rows - 1;                                   // padding rows repeat the last one; never stored
+        const int i = r / G, hh = r % G;
+        hi_row[mt] = pf_hi(L + i, m_bidir, total);
+        lo_row[mt] = pf_lo(L + i, W);
+        const bf16_t* qr = p.q + (((size_t)b * p.Lq + i) * p.n_q + g * G + hh) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[mt][ks] = *reinterpret_cast<const bf16x8*>(qr + ks * 32 + lc * 8);
+    }
+    const int i_first = r0 / G;
+    const int r_last = (r0 + RW - 1 < rows - 1) ? r0 + RW - 1 : rows - 1;
+    const int i_last = r_last / G;
+    // both limits grow with the position: the wave's key range and the part of it that needs masks
+    const int min_hi = pf_hi(L + i_first, m_bidir, total), max_hi = pf_hi(L + i_last, m_bidir, total);
+    const int min_lo = pf_lo(L + i_first, W), max_lo = pf_lo(L + i_last, W);
+    const int blk_begin = min_lo / kPfBlk, blk_end = (max_hi + kPfBlk - 1) / kPfBlk;
+
+    floatx4 acc[MT][NT];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY; l_run[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const bf16_t* kbase = p.kc + bg * (size_t)p.l_max * D;
+    const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D;
+    // Loads stay cached: the other waves of the workgroup and the other row tiles of the pair read the same blocks.
+    auto load_k = [&](int blk, bf16x8 (&kreg)[2][KS]) {
+        const bf16_t* kb = kbase + (size_t)blk * kPfBlk * D + lane * 8;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kreg[t][ks] = *reinterpret_cast<const bf16x8*>(kb + (t * KS + ks) * 512);
+    };
+    auto load_v = [&](int blk, bf16x8 (&vreg)[NT]) {
+        const bf16_t* vb = vbase + (size_t)blk * D * kPfBlk + lc * 8;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            vreg[nt] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kPfBlk);
+    };
+
+    constexpr float kLazy = 8.0f;       // a row's reference exponent is raised only when exceeded by 2^8
+    // d <= 128: the next block's keys are requested as soon as the scores are formed, its values after the second
+    // product (one register set, refilled in halves).  d = 256: loads at the top of the loop -- the longer live
+    // ranges of the refill scheme spill there.
+    constexpr bool REFILL = D <= 128;
+    bf16x8 k0[2][KS], v0[NT];
+    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const bool more = REFILL && blk + 1 < blk_end;
+        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
+        // ---- S^T = K Q^T: lane holds keys 8 lc + (0..7) of the block for query row 16 mt + lr ----
+        floatx4 s0[MT], s1[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { s0[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; s1[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[0][ks], qreg[mt][ks], s0[mt], 0, 0, 0);
+                s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[1][ks], qreg[mt][ks], s1[mt], 0, 0, 0);
+            }
+        if (more) load_k(blk + 1, k0);                     // the key registers are free: next block's keys
+        const int key0 = blk * kPfBlk + lc * 8;
+        if ((blk + 1) * kPfBlk > total) {                  // rows past the valid length may hold anything
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (key0 + e >= total) v0[nt][e] = (bf16_t)0.f;
+        }
+        const bool masked = (blk + 1) * kPfBlk > min_hi || blk * kPfBlk < max_lo;
+        bf16x8 pv[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float sv[8] = {s0[mt][0], s0[mt][1], s0[mt][2], s0[mt][3], s1[mt][0], s1[mt][1], s1[mt][2], s1[mt][3]};
+            if (masked) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (key0 + e >= hi_row[mt] || key0 + e < lo_row[mt]) sv[e] = -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            mx *= p.scale_log2;
+            if (__any(mx > m_run[mt] + kLazy)) {
+                mx = pf_xor16_max(mx);
+                if (mx > m_run[mt] + kLazy) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - mx);     // m_run = -inf gives 0
+                    l_run[mt] *= alpha;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= alpha;
+                    m_run[mt] = mx;
+                }
+            }
+            const float neg_m = (m_run[mt] == -INFINITY) ? 0.f : -m_run[mt];
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], p.scale_log2, neg_m));
+                ps += pe;
+                pv[mt][e] = (bf16_t)pe;
+            }
+            l_run[mt] += ps;
+        }
+        // ---- O^T += V^T P^T ----
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v0[nt], pv[mt], acc[mt][nt], 0, 0, 0);
+        if (more) load_v(blk + 1, v0);
+    }
+
+    // ---- write this wave's rows: lane (lr, lc) holds dims 16 nt + 4 lc + (0..3) of row 16 mt + lr ----
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const float l = pf_xor16_sum(l_run[mt]);
+        const int r = r0 + mt * 16 + lr;
+        if (r >= rows) continue;
+        const float inv = 1.0f / l;                        // every row sees at least its own key
+        const int i = r / G, hh = r % G;
+        bf16_t* dst = p.out + (((size_t)b * p.Lq + i) * p.n_q + g * G + hh) * D + lc * 4;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const floatx4 v = acc[mt][nt];
+            bf16x4 o = {(bf16_t)(v[0] * inv), (bf16_t)(v[1] * inv), (bf16_t)(v[2] * inv), (bf16_t)(v[3] * inv)};
+            *reinterpret_cast<bf16x4*>(dst + nt * 16) = o;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// fp32: grid (L_q, n_q, B), 256 threads; keys 256 at a time (thread t scores key t, thread c accumulates column c).
+// Row-major fp32 keys, blocked values.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256)
+void prefill_generic_kernel(const float* __restrict__ q, const float* __restrict__ kc, const float* __restrict__ vc,
+                            const int32_t* __restrict__ kv_len, const int32_t* __restrict__ n_new,
+                            const int32_t* __restrict__ n_bidir, float* __restrict__ out,
+                            int Lq, int n_q, int n_kv, int d, int l_max, float scale, int window) {
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int G = n_q / n_kv, g = h / G;
+    const size_t bg = (size_t)b * n_kv + g;
+    int L = kv_len[b]; L = L < 0 ? 0 : L;
+    int n = n_new[b]; n = n < 0 ? 0 : (n > Lq ? Lq : n);
+    if (L + n > l_max) n = l_max - L > 0 ? l_max - L : 0;
+    if (i >= n) return;                                    // uniform over the workgroup
+    const int hi = pf_hi(L + i, n_bidir ? n_bidir[b] : 0, L + n), lo = pf_lo(L + i, window);
+    __shared__ float qs[256];
+    __shared__ float w[256];
+    __shared__ float red[4];
+    const float* qr = q + (((size_t)b * Lq + i) * n_q + h) * d;
+    if (tid < d) qs[tid] = qr[tid];
+    __syncthreads();
+    float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+    for (int j0 = lo; j0 < hi; j0 += 256) {
+        const int j = j0 + tid;
+        float s = -INFINITY;
+        if (j < hi) {
+            const float* kr = kc + (bg * l_max + j) * d;
+            float dot = 0.f;
+            for (int c = 0; c < d; ++c) dot += qs[c] * kr[c];
+            s = dot * scale;
+        }
+        float mx = wave_max(s);
+        if ((tid & 63) == 0) red[tid >> 6] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        const float m_new = fmaxf(m_run, mx);              // finite: key j0 is visible
+        const float pe = (j < hi) ? expf(s - m_new) : 0.f;
+        w[tid] = pe;
+        float ps = wave_sum(pe);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = ps;
+        __syncthreads();
+        ps = red[0] + red[1] + red[2] + red[3];
+        const float alpha = expf(m_run - m_new);
+        l_run = l_run * alpha + ps;
+        acc *= alpha;
+        if (tid < d) {
+            const int cnt = (hi - j0) < 256 ? (hi - j0) : 256;
+            for (int t = 0; t < cnt; ++t) {
+                const int jj = j0 + t;
+                acc += w[t] * vc[((bg * (size_t)(l_max / kPfBlk) + (size_t)(jj / kPfBlk)) * d + tid) * kPfBlk + (jj % kPfBlk)];
+            }
+        }
+        m_run = m_new;
+        __syncthreads();
+    }
+    if (tid < d) out[(((size_t)b * Lq + i) * n_q + h) * d + tid] = acc / l_run;
+}
+
+template <int D, int MT>
+static int launch_prefill(const massv_attn_desc& a, PrefillParams p, hipStream_t st) {
+    const int rows_max = a.n_query * (a.n_q_heads / a.n_kv_heads);
+    const int per_wg = kPfWaves * MT * 16;
+    p.n_tiles = (rows_max + per_wg - 1) / per_wg;
+    if (p.n_tiles > 65535) return MASSV_EUNSUPPORTED;
+    launch_traced(MASSV_K_PREFILL_ATTENTION, prefill_attention_kernel<D, MT>, dim3(a.batch * a.n_kv_heads, p.n_tiles),
+                  dim3(kPfThreads), 0, st, p);
+    return launch_status();
+}
+
+}  // namespace massv
+
+using namespace massv;
+
+extern "C" int massv_prefill_attention(const massv_attn_desc* desc, const void* q, const void* k_cache,
+                                       const void* v_cache, const int32_t* kv_len, const int32_t* n_new,
+                                       const int32_t* n_bidir, void* out, void* stream) {
+    if (!desc) return MASSV_EINVAL;
+    // the descriptor rules of verify_attention, except that the row count per KV head is not limited
+    massv_attn_desc one = *desc;
+    one.n_query = 1;
+    const int rc = check_attn_desc(&one);
+    if (rc != MASSV_OK) return rc;
+    if (desc->n_query < 1 || desc->n_query > desc->l_max) return MASSV_EINVAL;
+    if (!q || !k_cache || !v_cache || !kv_len || !n_new || !out) return MASSV_EINVAL;
+    if ((int64_t)desc->batch * desc->n_kv_heads > 0x7fffffff) return MASSV_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const massv_attn_desc& a = *desc;
+    const float scale = a.scale > 0.f ? a.scale : 1.0f / sqrtf((float)a.head_dim);
+    if (a.dtype == MASSV_F32) {
+        if (a.n_query > 65535) return MASSV_EUNSUPPORTED;
+        hipLaunchKernelGGL(prefill_generic_kernel, dim3(a.n_query, a.n_q_heads, a.batch), dim3(256), 0, st,
+                           (const float*)q, (const float*)k_cache, (const float*)v_cache, kv_len, n_new, n_bidir,
+                           (float*)out, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, scale, a.window);
+        return launch_status();
+    }
+    PrefillParams p;
+    p.q = (const bf16_t*)q; p.kc = (const bf16_t*)k_cache; p.vc = (const bf16_t*)v_cache;
+    p.kv_len = kv_len; p.n_new = n_new; p.n_bidir = n_bidir;
+    p.out = (bf16_t*)out;
+    p.Lq = a.n_query; p.n_q = a.n_q_heads; p.n_kv = a.n_kv_heads; p.l_max = a.l_max; p.window = a.window;
+    p.n_tiles = 0;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    switch (a.head_dim) {
+        case 64: return launch_prefill<64, 4>(a, p, st);
+        case 128: return launch_prefill<128, 4>(a, p, st);
+        case 256: return launch_prefill<256, 2>(a, p, st);
+    }
+    return MASSV_EUNSUPPORTED;
+}
