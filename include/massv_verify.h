@@ -337,6 +337,27 @@ int massv_lm_head_greedy_accept(const void* x, const void* final_norm, const voi
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------- */
+/* lm_head_accept: massv_lm_head_logits followed by massv_spec_accept at any   */
+/* temperature, in one call (Section 2.1: the scores p_i and the accept rule). */
+/* T = 0 is massv_lm_head_greedy_accept (no logits are written; `logits` may   */
+/* be NULL).  T > 0: the logits ARE written to `logits` -- the rule reads      */
+/* p_i(x_i) from them and re-reads one row per sequence for the final draw --  */
+/* but the projection also leaves, per row and per piece of the vocabulary,    */
+/* the piece's largest logit, its column and its sum of exp((x - largest)/T),  */
+/* so the accept rule's first pass streams the draft rows only.  Results equal */
+/* those of the two separate calls wherever no decision lies within rounding   */
+/* (the row sums are formed from differently cut pieces: agreement to ~1e-7).  */
+/* Arguments as for the two calls; x [B][gamma+1][H] (dtype), logits           */
+/* [B*(gamma+1)][V] float32 out.  bf16 only.                                   */
+/* ------------------------------------------------------------------------- */
+size_t massv_lm_head_accept_workspace(int32_t B, int32_t gamma, int32_t H, int32_t V, int32_t dtype);
+int massv_lm_head_accept(const void* x, const void* final_norm, const void* w_lm,
+                         const float* draft_logits, const int32_t* draft_tokens, const float* uniforms,
+                         float temperature, int32_t B, int32_t gamma, int32_t H, int32_t V,
+                         float norm_eps, int32_t dtype, float* logits, int32_t* n_accepted, int32_t* out_tokens,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
 /* commit_tokens: bookkeeping after spec_accept, on the device so that the     */
 /* decoding loop of Section 2.1 needs no host round trip: sequence b keeps its */
 /* n_b accepted drafts and the final token, so                                 */

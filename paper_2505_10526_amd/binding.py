@@ -32,6 +32,7 @@ EXPORTS = [
     "massv_linear_workspace", "massv_linear",
     "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
     "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention",
+    "massv_lm_head_accept_workspace", "massv_lm_head_accept",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR, K_PREFILL_ATTENTION = range(11)
 LIN_NONE, LIN_SILU, LIN_GELU_TANH, LIN_GELU_ERF = range(4)
@@ -125,6 +126,10 @@ def load():
     lib.massv_lm_head_greedy_accept_workspace.argtypes = [i32, i32, i32, i32, i32]
     lib.massv_lm_head_greedy_accept.restype = C.c_int
     lib.massv_lm_head_greedy_accept.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.massv_lm_head_accept_workspace.restype = sz
+    lib.massv_lm_head_accept_workspace.argtypes = [i32, i32, i32, i32, i32]
+    lib.massv_lm_head_accept.restype = C.c_int
+    lib.massv_lm_head_accept.argtypes = [vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, f32, i32, vp, vp, vp, vp, sz, vp]
     lib.massv_commit_tokens.restype = C.c_int
     lib.massv_commit_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.massv_embed_tokens.restype = C.c_int
@@ -451,6 +456,32 @@ def lm_head_greedy_accept(x, final_norm, w_lm, draft_tokens, norm_eps=1e-6, n_ac
                                            float(norm_eps), dtype_code(x), _ptr(n_accepted), _ptr(out_tokens),
                                            _ptr(ws), ws.numel(), _stream()), "massv_lm_head_greedy_accept")
     return n_accepted, out_tokens
+
+
+def lm_head_accept(x, final_norm, w_lm, draft_logits, draft_tokens, uniforms, temperature, norm_eps=1e-6,
+                   logits=None, n_accepted=None, out_tokens=None, ws=None):
+    """x [B,Q,H]; w_lm [V,H] in streaming layout; draft_logits [B,Q-1,V] f32, draft_tokens [B,Q-1] i32 (None when
+    Q == 1), uniforms [B,Q] f32 (None at T = 0).  Vocabulary projection and accept rule in one call; at T > 0 the
+    logits are written to `logits` [B*Q, V].  Returns (n_accepted, out_tokens, logits or None)."""
+    lib = load()
+    _need(x, "x")
+    _need(w_lm, "w_lm", x.dtype)
+    B, Q, H = x.shape
+    V = w_lm.shape[0]
+    dev = x.device
+    if n_accepted is None:
+        n_accepted = torch.empty((B,), dtype=torch.int32, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, Q), dtype=torch.int32, device=dev)
+    if logits is None and temperature > 0:
+        logits = torch.empty((B * Q, V), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = workspace(lib.massv_lm_head_accept_workspace(B, Q - 1, H, V, dtype_code(x)), dev)
+    _check(lib.massv_lm_head_accept(_ptr(x), _ptr(final_norm), _ptr(w_lm), _ptr(draft_logits), _ptr(draft_tokens),
+                                    _ptr(uniforms), float(temperature), B, Q - 1, H, V, float(norm_eps), dtype_code(x),
+                                    _ptr(logits), _ptr(n_accepted), _ptr(out_tokens), _ptr(ws), ws.numel(), _stream()),
+           "massv_lm_head_accept")
+    return n_accepted, out_tokens, logits
 
 
 def spec_tvd(target_logits, draft_logits, temperature, tvd=None, ws=None):

@@ -33,7 +33,6 @@ constexpr int kMaxGamma = 15;
 struct SeqSel { int n; int bonus; int pad0; int pad1; double m_t, s_t, m_d, s_d; };
 struct ChunkMass { double r, p; };
 
-struct TempScale { float hi, lo; double inv; };   // log2(e)/T split in two floats: d*hi + d*lo is d*log2(e)/T to ~1 ulp; inv = 1/T
 
 // 2^x by the hardware instruction alone: x <= 0 here, results below the smallest normal number flush to
 // zero (a probability under 2^-126 of the row's largest), no range handling needed.
@@ -131,9 +130,9 @@ constexpr int kDecideThreads = 1024;                      // 16 waves: one row o
 __global__ __launch_bounds__(kDecideThreads)
 void accept_decide_kernel(const float* __restrict__ target, const float* __restrict__ draft,
                           const int* __restrict__ tokens, const float* __restrict__ uniforms,
-                          int B, int gamma, int V, int C, double inv_t, float scale2, int greedy,
-                          const RowPartial* __restrict__ part, SeqSel* __restrict__ sel,
-                          int* __restrict__ n_accepted, int* __restrict__ out_tokens) {
+                          int B, int gamma, int V, double inv_t, float scale2, int greedy,
+                          const RowPartial* __restrict__ part_t, int C_t, const RowPartial* __restrict__ part_d, int C_d,
+                          SeqSel* __restrict__ sel, int* __restrict__ n_accepted, int* __restrict__ out_tokens) {
     const int b = blockIdx.x, tid = threadIdx.x, Q = gamma + 1;
     const int wave = tid / kWave, lane = tid % kWave;
     __shared__ double row_m[2 * kMaxGamma + 1], row_s[2 * kMaxGamma + 1];
@@ -153,10 +152,11 @@ void accept_decide_kernel(const float* __restrict__ target, const float* __restr
             u_f = uniforms[b * Q + lane];
         }
     }
-    // one wave per row: lanes take the chunk partials, merged by a fixed shuffle tree
+    // one wave per row: lanes take the row's partials (part_t[B*Q][C_t] for target rows, part_d[B*gamma][C_d] for
+    // draft rows), merged by a fixed shuffle tree
     for (int t = wave; t < nrows; t += kDecideThreads / kWave) {
-        const int r = (t < Q) ? b * Q + t : B * Q + b * gamma + (t - Q);
-        const RowPartial* p = part + (size_t)r * C;
+        const int C = (t < Q) ? C_t : C_d;
+        const RowPartial* p = (t < Q) ? part_t + (size_t)(b * Q + t) * C_t : part_d + (size_t)(b * gamma + (t - Q)) * C_d;
         float m = -INFINITY; int am = INT_MAX;
         double s = 0.0;
         if (C <= 4 * kWave) {                       // the usual case: every partial is loaded once, all loads in flight
@@ -440,7 +440,7 @@ static TvdLayout tvd_layout(int rows, int V) {
     return l;
 }
 
-static TempScale temp_scale(float temperature) {
+TempScale temp_scale(float temperature) {
     TempScale ts;
     ts.inv = 1.0 / (double)temperature;
     const double k2 = ts.inv * 1.4426950408889634074;      // log2(e) / T
@@ -493,8 +493,9 @@ static int run_accept(const float* target_logits, const float* draft_logits, con
     launch_traced(MASSV_K_ACCEPT_STATS, accept_stats_kernel, dim3((C + kAccThreads / kWave - 1) / (kAccThreads / kWave), rows), dim3(kAccThreads), 0, st,
                   target_logits, draft_logits, B * Q, V, C, ts, greedy, vec, part);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
-                       target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, C, ts.inv,
-                       ts.hi, greedy, part, sel, n_accepted, out_tokens);
+                       target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, ts.inv,
+                       ts.hi, greedy, (const RowPartial*)part, C, (const RowPartial*)(part + (size_t)B * Q * C), C,
+                       sel, n_accepted, out_tokens);
     if (!greedy) {
         launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + kAccThreads / kWave - 1) / (kAccThreads / kWave), B), dim3(kAccThreads), 0, st,
                       target_logits, draft_logits, gamma, V, C, ts, vec, (const SeqSel*)sel, mass);
@@ -556,11 +557,50 @@ extern "C" int massv_spec_accept_static(const float* target_logits, const float*
 }
 
 namespace massv {
+// Target statistics come with the logits (one partial per row and workgroup of the vocabulary projection): pass 1
+// streams the draft rows only; the rest of the call is the same four-kernel chain.
+struct PrestatsLayout { size_t part_d, sel, mass, total; };
+static PrestatsLayout prestats_layout(int B, int gamma, int V) {
+    PrestatsLayout l;
+    const size_t C = n_chunks(V);
+    l.part_d = 0;
+    l.sel = align_up(l.part_d + (size_t)B * gamma * C * sizeof(RowPartial), 256);
+    l.mass = align_up(l.sel + (size_t)B * sizeof(SeqSel), 256);
+    l.total = align_up(l.mass + (size_t)B * C * sizeof(ChunkMass), 256);
+    return l;
+}
+size_t accept_prestats_bytes(int B, int gamma, int V) { return prestats_layout(B, gamma, V).total; }
+
+int launch_accept_prestats(const float* target_logits, const RowPartial* part_t, int C_t, const float* draft_logits,
+                           const int32_t* draft_tokens, const float* uniforms, float temperature, int B, int gamma, int V,
+                           int32_t* n_accepted, int32_t* out_tokens, void* workspace, hipStream_t st) {
+    const PrestatsLayout lay = prestats_layout(B, gamma, V);
+    char* ws = (char*)workspace;
+    RowPartial* part_d = (RowPartial*)(ws + lay.part_d);
+    SeqSel* sel = (SeqSel*)(ws + lay.sel);
+    ChunkMass* mass = (ChunkMass*)(ws + lay.mass);
+    const int C = n_chunks(V);
+    const TempScale ts = temp_scale(temperature);
+    const int vec = (V % 4 == 0) && ((uintptr_t)target_logits % 16 == 0) && (gamma == 0 || (uintptr_t)draft_logits % 16 == 0);
+    const int wpb = kAccThreads / kWave;
+    if (gamma > 0)
+        launch_traced(MASSV_K_ACCEPT_STATS, accept_stats_kernel, dim3((C + wpb - 1) / wpb, B * gamma), dim3(kAccThreads), 0, st,
+                      (const float*)nullptr, draft_logits, 0, V, C, ts, 0, vec, part_d);
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st,
+                       target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, ts.inv, ts.hi, 0,
+                       part_t, C_t, (const RowPartial*)part_d, C, sel, n_accepted, out_tokens);
+    launch_traced(MASSV_K_RESIDUAL_MASS, residual_mass_kernel, dim3((C + wpb - 1) / wpb, B), dim3(kAccThreads), 0, st,
+                  target_logits, draft_logits, gamma, V, C, ts, vec, (const SeqSel*)sel, mass);
+    hipLaunchKernelGGL(residual_pick_kernel, dim3(B), dim3(kWave), 0, st,
+                       target_logits, draft_logits, uniforms, gamma, V, C, ts, vec, sel, mass, out_tokens);
+    return launch_status();
+}
+
 int launch_accept_decide_greedy(const RowPartial* part, int C, const int32_t* draft_tokens, int B, int gamma, int V,
                                 int32_t* n_accepted, int32_t* out_tokens, hipStream_t st) {
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, st, (const float*)nullptr, (const float*)nullptr,
-                       draft_tokens, (const float*)nullptr, B, gamma, V, C, 1.0, 1.f, 1, part, (SeqSel*)nullptr, n_accepted,
-                       out_tokens);
+                       draft_tokens, (const float*)nullptr, B, gamma, V, 1.0, 1.f, 1, part, C, (const RowPartial*)nullptr, 0,
+                       (SeqSel*)nullptr, n_accepted, out_tokens);
     return launch_status();
 }
 

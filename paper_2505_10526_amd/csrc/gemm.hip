@@ -54,6 +54,8 @@ struct GemmDev {
     const bf16_t* w[3];
     int tiles[3];            // 16-feature tiles per matrix
     void* y;
+    void* stats;             // EPI_LOGITS_STATS: RowPartial[M][gridDim.x]
+    float ts_hi, ts_lo;      // EPI_LOGITS_STATS: log2(e)/T in two floats
     int M, K, ldy;           // ldy: elements per output row
     int act;
     int unit_base, unit_rem; // balanced split of the tile units over gridDim.x: the first unit_rem workgroups own unit_base+1
@@ -70,6 +72,12 @@ __device__ inline float gemm_act(float x, int act) {
     if (act == MASSV_ACT_SILU) return x * fast_sigmoid(x);
     const float c = 0.7978845608028654f;
     return x * fast_sigmoid(2.0f * c * (x + 0.044715f * x * x * x));
+}
+
+// 2^(d * log2(e)/T) for d <= 0 (a logit minus a running maximum; -inf and NaN from -inf - -inf give 0).
+__device__ inline float exp2_scaled(float d, float hi, float lo) {
+    d = fmaxf(d, -3.0e38f);
+    return __builtin_amdgcn_exp2f(fmaf(d, lo, d * hi));
 }
 
 __device__ inline bf16x8 ld8(const bf16_t* p, bool ok) {
@@ -195,11 +203,14 @@ void gemm_stream_kernel(GemmDev g) {
         }
     }
 
-    // EPI_ARGMAX: largest summed output (and its lowest column) seen by this lane for row 16 mt + lr
-    float best_v[MT];
+    // EPI_ARGMAX, EPI_LOGITS_STATS: largest summed output (and its lowest column) seen by this lane for row
+    // 16 mt + lr; EPI_LOGITS_STATS: also the sum of exp((x - largest)/T) over what the lane has seen (rescaled
+    // whenever the largest moves)
+    constexpr bool STATS = (EPI == EPI_LOGITS_STATS);
+    float best_v[MT], sum_e[MT];
     int best_i[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) { best_v[mt] = -INFINITY; best_i[mt] = INT_MAX; }
+    for (int mt = 0; mt < MT; ++mt) { best_v[mt] = -INFINITY; best_i[mt] = INT_MAX; sum_e[mt] = 0.f; }
 
     // ---- sum the waves through LDS in wave order, GRP tiles per round ----
     constexpr int GRP = ReduceGroup<MT, NT>::value;
@@ -235,10 +246,16 @@ void gemm_stream_kernel(GemmDev g) {
                         for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(gemm_act(s[i], g.act) * u[i]);
                         *reinterpret_cast<bf16x4*>((bf16_t*)g.y + packed_index(m, col, MT)) = o;
                     }
-                } else if (EPI == EPI_ARGMAX) {
+                } else if (EPI == EPI_ARGMAX || STATS) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)                   // ascending columns: a tie keeps the lower one
+                    for (int i = 0; i < 4; ++i) {                 // ascending columns: a tie keeps the lower one
+                        if constexpr (STATS) {
+                            if (s[i] > best_v[mt]) sum_e[mt] = sum_e[mt] * exp2_scaled(best_v[mt] - s[i], g.ts_hi, g.ts_lo) + 1.f;
+                            else sum_e[mt] += exp2_scaled(s[i] - best_v[mt], g.ts_hi, g.ts_lo);
+                        }
                         if (s[i] > best_v[mt] || (s[i] == best_v[mt] && col + i < best_i[mt])) { best_v[mt] = s[i]; best_i[mt] = col + i; }
+                    }
+                    if (STATS && m < g.M) *reinterpret_cast<floatx4*>((float*)g.y + (size_t)m * g.ldy + col) = s;
                 } else if (m < g.M) {
                     float* dst = (float*)g.y + (EPI == EPI_PARTIAL ? (size_t)by * g.slab_stride : 0) +
                                  (size_t)m * g.ldy + col;
@@ -247,21 +264,27 @@ void gemm_stream_kernel(GemmDev g) {
             }
         }
     }
-    if constexpr (EPI == EPI_ARGMAX) {
+    if constexpr (EPI == EPI_ARGMAX || STATS) {
         // lanes of the four column groups of a row, then the four waves, then one record per row and workgroup
         __syncthreads();                                         // the reduction buffer is free
         float* bv = reinterpret_cast<float*>(red);               // [WK][MT*16]
         int* bi = reinterpret_cast<int*>(bv + WK * MT * 16);
+        float* bs = reinterpret_cast<float*>(bi + WK * MT * 16);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            float v = best_v[mt]; int i = best_i[mt];
+            float v = best_v[mt], se = sum_e[mt]; int i = best_i[mt];
 #pragma unroll
             for (int o = 16; o <= 32; o <<= 1) {
                 const float ov = __shfl_xor(v, o, kWave);
                 const int oi = __shfl_xor(i, o, kWave);
+                if constexpr (STATS) {
+                    const float os = __shfl_xor(se, o, kWave);
+                    const float mn = fmaxf(v, ov);
+                    se = (mn == -INFINITY) ? 0.f : se * exp2_scaled(v - mn, g.ts_hi, g.ts_lo) + os * exp2_scaled(ov - mn, g.ts_hi, g.ts_lo);
+                }
                 if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
             }
-            if (lc == 0) { bv[wave * MT * 16 + mt * 16 + lr] = v; bi[wave * MT * 16 + mt * 16 + lr] = i; }
+            if (lc == 0) { bv[wave * MT * 16 + mt * 16 + lr] = v; bi[wave * MT * 16 + mt * 16 + lr] = i; bs[wave * MT * 16 + mt * 16 + lr] = se; }
         }
         __syncthreads();
         if (tid < MT * 16 && tid < g.M) {
@@ -271,7 +294,12 @@ void gemm_stream_kernel(GemmDev g) {
                 if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
             }
             RowPartial r; r.m = v; r.arg = i; r.s = 0.0;
-            reinterpret_cast<RowPartial*>(g.y)[(size_t)tid * gridDim.x + blockIdx.x] = r;
+            if constexpr (STATS) {                               // wave order, in double
+                for (int w = 0; w < WK; ++w)
+                    if (bv[w * MT * 16 + tid] > -INFINITY)
+                        r.s += (double)bs[w * MT * 16 + tid] * (double)exp2_scaled(bv[w * MT * 16 + tid] - v, g.ts_hi, g.ts_lo);
+            }
+            reinterpret_cast<RowPartial*>(STATS ? g.stats : g.y)[(size_t)tid * gridDim.x + blockIdx.x] = r;
         }
     }
 }
@@ -322,7 +350,9 @@ static int n_total(const GemmArgs& g) { return g.n[0] + g.n[1] + g.n[2]; }
 int gemm_supported(const GemmArgs& g) {
     if (g.M < 1 || g.K < 1 || g.n[0] < 1) return MASSV_EINVAL;
     if (g.epilogue == EPI_GATED && (g.n[1] != g.n[0] || g.n[2] != 0)) return MASSV_EINVAL;
-    if (g.dtype == MASSV_F32) return (g.epilogue == EPI_PARTIAL || g.epilogue == EPI_ARGMAX) ? MASSV_EINVAL : MASSV_OK;
+    if (g.dtype == MASSV_F32)
+        return (g.epilogue == EPI_PARTIAL || g.epilogue == EPI_ARGMAX || g.epilogue == EPI_LOGITS_STATS) ? MASSV_EINVAL : MASSV_OK;
+    if (g.epilogue == EPI_LOGITS_STATS && (!g.stats || !(g.temperature > 0.f))) return MASSV_EINVAL;
     if (g.epilogue == EPI_STORE || g.epilogue == EPI_RESIDUAL) return MASSV_EINVAL;   // bf16 goes through partial sums
     if (g.M > MASSV_MAX_ROWS) return MASSV_EUNSUPPORTED;
     if (g.K % 32) return MASSV_EUNSUPPORTED;
@@ -371,7 +401,7 @@ GemmPlan gemm_plan(const GemmArgs& g) {
     if (g.epilogue == EPI_PARTIAL && (T + 3) / 4 < kCUs) return plan_split(g, mt, T);
     // wide output (or a partial-sum output wide enough for 256 workgroups at full K): one slab
     static const int cand_partial[] = {8, 7, 4}, cand_gated[] = {10, 8, 4}, cand_logits[] = {10, 8, 4};
-    const int* cand = g.epilogue == EPI_GATED ? cand_gated : (g.epilogue == EPI_LOGITS || g.epilogue == EPI_ARGMAX) ? cand_logits : cand_partial;
+    const int* cand = g.epilogue == EPI_GATED ? cand_gated : (g.epilogue == EPI_LOGITS || g.epilogue == EPI_ARGMAX || g.epilogue == EPI_LOGITS_STATS) ? cand_logits : cand_partial;
     double best_score = -1.0;
     for (int i = 0; i < 3; ++i) {
         int nt = cand[i];
@@ -465,6 +495,9 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
     d.x = (const bf16_t*)g.x;
     for (int s = 0; s < 3; ++s) { d.w[s] = (const bf16_t*)g.w[s]; d.tiles[s] = g.n[s] / 16; }
     d.y = g.y;
+    d.stats = g.stats;
+    d.ts_hi = 1.f; d.ts_lo = 0.f;
+    if (g.epilogue == EPI_LOGITS_STATS) { const TempScale ts = temp_scale(g.temperature); d.ts_hi = ts.hi; d.ts_lo = ts.lo; }
     d.M = g.M; d.K = g.K;
     d.ldy = (g.epilogue == EPI_GATED) ? g.n[0] : N;
     d.act = g.act;
@@ -482,6 +515,7 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
         case EPI_GATED: rc2 = launch_stream_epi<EPI_GATED>(d, g.M, p, g.kid, st); break;
         case EPI_LOGITS: rc2 = launch_stream_epi<EPI_LOGITS>(d, g.M, p, g.kid, st); break;
         case EPI_ARGMAX: rc2 = launch_stream_epi<EPI_ARGMAX>(d, g.M, p, g.kid, st); break;
+        case EPI_LOGITS_STATS: rc2 = launch_stream_epi<EPI_LOGITS_STATS>(d, g.M, p, g.kid, st); break;
     }
     if (rc2 != MASSV_OK) return rc2;
     return launch_status();

@@ -62,8 +62,10 @@ enum Epilogue {
     EPI_LOGITS = 3,     // y = acc stored as float32 [M][N]
     EPI_PARTIAL = 4,    // bf16 only: fp32 partial sums y[slab][16*ceil(M/16)][N], one slab per K range;
                         // bias / residual are applied by the kernel that sums the slabs
-    EPI_ARGMAX = 5      // bf16 only: nothing is stored but, per row and workgroup, the largest output and its
+    EPI_ARGMAX = 5,     // bf16 only: nothing is stored but, per row and workgroup, the largest output and its
                         // (lowest) column: y is RowPartial[M][groups]
+    EPI_LOGITS_STATS = 6 // bf16 only: EPI_LOGITS, and stats[M][groups] receives per row and workgroup the largest
+                        // output, its lowest column and the sum of exp((x - largest) / T) over the workgroup's columns
 };
 // Maximum, first arg-max and sum of exponentials of one piece of a logit row (pieces are merged by accept_decide_kernel).
 struct RowPartial { float m; int arg; double s; };
@@ -71,6 +73,17 @@ struct GemmPlan { int nt, slabs, groups; };
 // Greedy accept chain from per-piece row partials: part[row][C] for the B*(gamma+1) target rows (accept.hip).
 int launch_accept_decide_greedy(const RowPartial* part, int C, const int32_t* draft_tokens, int B, int gamma, int V,
                                 int32_t* n_accepted, int32_t* out_tokens, hipStream_t st);
+// log2(e)/T split in two floats (d*hi + d*lo is d*log2(e)/T to about 1 ulp) and 1/T: how every kernel that forms
+// exp((x - max)/T) scales its exponent.
+struct TempScale { float hi, lo; double inv; };
+TempScale temp_scale(float temperature);
+// The accept rule at T > 0 with the target rows' statistics already formed by the vocabulary projection
+// (part_t[B*(gamma+1)][C_t], written by an EPI_LOGITS_STATS launch): pass 1 runs over the draft rows only.
+// ws: accept_prestats_bytes(B, gamma, V) bytes.
+size_t accept_prestats_bytes(int B, int gamma, int V);
+int launch_accept_prestats(const float* target_logits, const RowPartial* part_t, int C_t, const float* draft_logits,
+                           const int32_t* draft_tokens, const float* uniforms, float temperature, int B, int gamma, int V,
+                           int32_t* n_accepted, int32_t* out_tokens, void* ws, hipStream_t st);
 struct GemmArgs {
     const void* x;            // f32: [M][K] row-major; bf16: operand order (packed_index), packed_elems(M,K) elements
     const void* w[3];         // [n_i][K]
@@ -78,6 +91,8 @@ struct GemmArgs {
     int n[3];                 // rows of each matrix (0 = unused)
     const void* residual;     // EPI_RESIDUAL: [M][n0]
     void* y;
+    void* stats;              // EPI_LOGITS_STATS: RowPartial[M][groups]
+    float temperature;        // EPI_LOGITS_STATS: T > 0 of the exponentials
     void* scratch;            // f32 + EPI_GATED only: [M][2*n0] floats
     int M, K;
     int epilogue, act, dtype;

@@ -268,3 +268,53 @@ extern "C" int massv_lm_head_greedy_accept(const void* x, const void* final_norm
     if ((rc = launch_gemm(g, st)) != MASSV_OK) return rc;
     return launch_accept_decide_greedy(part, gemm_plan(g).groups, draft_tokens, B, gamma, V, n_accepted, out_tokens, st);
 }
+
+// lm_head and the accept rule in one call at any temperature.  T = 0: the greedy path above (no logits written).
+// T > 0: the projection writes the logits (the accept rule gathers p(x_i) from them and re-reads one row per sequence
+// for the final draw) and its epilogue leaves, per row and workgroup, the largest logit, its column and the sum of
+// exponentials -- the target half of the accept call's first pass, which then streams the draft rows only.
+static GemmArgs stats_gemm(int32_t M, int32_t H, int32_t V, float temperature) {
+    GemmArgs g = {};
+    g.n[0] = V; g.M = M; g.K = H; g.epilogue = EPI_LOGITS_STATS; g.dtype = MASSV_BF16; g.kid = MASSV_K_LMHEAD;
+    g.temperature = temperature;
+    return g;
+}
+
+extern "C" size_t massv_lm_head_accept_workspace(int32_t B, int32_t gamma, int32_t H, int32_t V, int32_t dtype) {
+    if (check_greedy(B, gamma, H, V, dtype) != MASSV_OK) return 0;
+    const int M = B * (gamma + 1);
+    const GemmPlan p = gemm_plan(stats_gemm(M, H, V, 1.f));
+    const size_t sampled = align_up(packed_elems(M, H) * 2, 256) + align_up((size_t)M * p.groups * sizeof(RowPartial), 256) +
+                           accept_prestats_bytes(B, gamma, V);
+    const size_t greedy = massv_lm_head_greedy_accept_workspace(B, gamma, H, V, dtype);
+    return sampled > greedy ? sampled : greedy;
+}
+
+extern "C" int massv_lm_head_accept(const void* x, const void* final_norm, const void* w_lm,
+                                    const float* draft_logits, const int32_t* draft_tokens, const float* uniforms,
+                                    float temperature, int32_t B, int32_t gamma, int32_t H, int32_t V,
+                                    float norm_eps, int32_t dtype, float* logits, int32_t* n_accepted, int32_t* out_tokens,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_greedy(B, gamma, H, V, dtype);
+    if (rc != MASSV_OK) return rc;
+    if (!(temperature >= 0.f) || isinf(temperature)) return MASSV_EINVAL;     // also catches NaN
+    if (!workspace || workspace_bytes < massv_lm_head_accept_workspace(B, gamma, H, V, dtype)) return MASSV_EWORKSPACE;
+    if (temperature == 0.f)
+        return massv_lm_head_greedy_accept(x, final_norm, w_lm, draft_tokens, B, gamma, H, V, norm_eps, dtype, n_accepted,
+                                           out_tokens, workspace, workspace_bytes, stream);
+    if (!x || !w_lm || !logits || !uniforms || !n_accepted || !out_tokens) return MASSV_EINVAL;
+    if (gamma > 0 && (!draft_tokens || !draft_logits)) return MASSV_EINVAL;
+    if (!(norm_eps >= 0.f)) return MASSV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int M = B * (gamma + 1);
+    if ((rc = launch_rmsnorm_packed(x, final_norm, workspace, M, H, norm_eps, st)) != MASSV_OK) return rc;
+    GemmArgs g = stats_gemm(M, H, V, temperature);
+    char* ws = (char*)workspace;
+    RowPartial* part = (RowPartial*)(ws + align_up(packed_elems(M, H) * 2, 256));
+    const int groups = gemm_plan(g).groups;
+    void* accept_ws = (char*)part + align_up((size_t)M * groups * sizeof(RowPartial), 256);
+    g.x = workspace; g.w[0] = w_lm; g.y = logits; g.stats = part;
+    if ((rc = launch_gemm(g, st)) != MASSV_OK) return rc;
+    return launch_accept_prestats(logits, part, groups, draft_logits, draft_tokens, uniforms, temperature, B, gamma, V,
+                                  n_accepted, out_tokens, accept_ws, st);
+}

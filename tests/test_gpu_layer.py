@@ -376,3 +376,39 @@ def test_lm_head_greedy_accept(s, B, gamma, dup):
         assert clear.all(axis=1).sum() >= 1                 # the comparison with the checker is not vacuous
     if gamma >= 5 and B >= 3:
         assert len(set(n_o.tolist())) > 1
+
+
+# ---------------------------------------------------------------------------
+# vocabulary projection + accept rule in one call at T > 0 (row statistics formed in the projection's epilogue)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("s,B,gamma,T,noise", [(synth.TINY_BF16, 3, 5, 1.0, 0.3), (synth.TINY_BF16, 1, 0, 0.7, 0.3),
+                                               (synth.TINY_BF16, 4, 15, 1.0, 0.1), (synth.QWEN7B, 8, 5, 1.0, 0.5),
+                                               (synth.QWEN7B, 8, 5, 0.7, 1.5), (synth.QWEN7B, 2, 3, 0.0, 1.0)],
+                         ids=["tiny", "tiny-gamma0", "tiny-gamma15", "qwen7b", "qwen7b-T0.7", "qwen7b-T0"])
+def test_lm_head_accept_one_call(s, B, gamma, T, noise):
+    Q, seed = gamma + 1, 70 + B + gamma
+    T = float(np.float32(T))
+    head = synth.lm_head_weights(s, seed, std=0.05)
+    xd = to_dev(synth.hidden_states(s, B, Q, seed), s.dtype)
+    norm, w = to_dev(head["final_norm"], s.dtype), binding.weight_pack(to_dev(head["w_lm"], s.dtype))
+    lg = binding.lm_head_logits(xd, norm, w, s.norm_eps)                   # the separate calls: logits first
+    tl = lg.cpu().numpy().reshape(B, Q, -1)
+    a = synth.accept_inputs(B, gamma, s.vocab, T, seed, noise_std=noise, target_logits=tl)   # drafts from the GPU's own logits
+    dl = torch.from_numpy(a.draft_logits).cuda() if gamma else None
+    dt = torch.from_numpy(a.draft_tokens).cuda() if gamma else None
+    u = torch.from_numpy(a.uniforms).cuda()
+    n_2, out_2 = binding.spec_accept(lg.view(B, Q, -1), dl if T > 0 else None, dt, u if T > 0 else None, T)
+    n_f, out_f, lg_f = binding.lm_head_accept(xd, norm, w, dl, dt, u if T > 0 else None, T, s.norm_eps)
+    torch.cuda.synchronize()
+    if T > 0:
+        assert torch.equal(lg_f, lg)                                        # the same projection arithmetic
+    # the checker on the same fp32 logits
+    n_o, out_o, margin = O.spec_accept(tl, a.draft_logits, a.draft_tokens, a.uniforms, T)
+    clear = np.all(margin > 1e-5, axis=1)
+    assert clear.sum() >= 0.5 * B, "pick another seed: too few decisions clear of rounding"
+    for b in range(B):
+        if clear[b]:
+            for n_g, out_g in ((n_2, out_2), (n_f, out_f)):
+                assert int(n_g[b]) == n_o[b] and np.array_equal(out_g[b].cpu().numpy(), out_o[b]), (b, out_g[b], out_o[b])
+    if gamma >= 5 and T > 0:
+        assert n_o.max() > 0                                                # drafts do get accepted in this case
