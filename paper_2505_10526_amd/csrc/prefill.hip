@@ -45,6 +45,14 @@ __host__ __device__ inline int pf_hi(int r, int m, int total) {
 }
 __host__ __device__ inline int pf_lo(int r, int W) { return (W > 0 && r + 1 > W) ? r + 1 - W : 0; }
 
+// max(a, b, c) in one instruction.  (fmaxf nests compile to a canonicalising self-maximum per operand plus the
+// maximum itself: 11 instructions for 8 scores instead of 4; operands here are never NaN -- masked scores are -inf.)
+__device__ inline float pf_max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ inline float pf_xor16_max(float v) {
     v = fmaxf(v, __shfl_xor(v, 16, kWave));
     return fmaxf(v, __shfl_xor(v, 32, kWave));
@@ -62,7 +70,10 @@ void prefill_attention_kernel(PrefillParams p) {
     constexpr int RW = MT * 16;         // stacked rows per wave
     const int pair = blockIdx.x, b = pair / p.n_kv, g = pair % p.n_kv;
     const int tile = p.n_tiles - 1 - (int)blockIdx.y;                 // the longest key ranges are started first
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    // the wave index as a scalar: everything derived from it (row range, key range, the loop, the mask decisions) then
+    // lives in scalar registers and branches, not in per-lane copies guarded by execution masks
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int lr = lane % 16, lc = lane / 16;
     const int G = p.n_q / p.n_kv;
     int L = p.kv_len[b]; L = L < 0 ? 0 : L;
@@ -126,34 +137,27 @@ void prefill_attention_kernel(PrefillParams p) {
     };
 
     constexpr float kLazy = 8.0f;       // a row's reference exponent is raised only when exceeded by 2^8
-    // d <= 128: the next block's keys are requested as soon as the scores are formed, its values after the second
-    // product (one register set, refilled in halves).  d = 256: loads at the top of the loop -- the longer live
-    // ranges of the refill scheme spill there.
-    constexpr bool REFILL = D <= 128;
-    bf16x8 k0[2][KS], v0[NT];
-    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
-        const bool more = REFILL && blk + 1 < blk_end;
-        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
-        // ---- S^T = K Q^T: lane holds keys 8 lc + (0..7) of the block for query row 16 mt + lr ----
-        floatx4 s0[MT], s1[MT];
+    // ---- S^T = K Q^T of one block: lane holds keys 8 lc + (0..7) of the block for query row 16 mt + lr ----
+    auto scores = [&](bf16x8 (&kr)[2][KS], floatx4 (&s0)[MT], floatx4 (&s1)[MT]) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) { s0[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; s1[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[0][ks], qreg[mt][ks], s0[mt], 0, 0, 0);
-                s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[1][ks], qreg[mt][ks], s1[mt], 0, 0, 0);
+                s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[0][ks], qreg[mt][ks], s0[mt], 0, 0, 0);
+                s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[1][ks], qreg[mt][ks], s1[mt], 0, 0, 0);
             }
-        if (more) load_k(blk + 1, k0);                     // the key registers are free: next block's keys
+    };
+    // ---- masks, streaming softmax and O^T += V^T P^T of one block, from its scores ----
+    auto finish = [&](int blk, floatx4 (&s0)[MT], floatx4 (&s1)[MT], bf16x8 (&vr)[NT]) {
         const int key0 = blk * kPfBlk + lc * 8;
         if ((blk + 1) * kPfBlk > total) {                  // rows past the valid length may hold anything
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    if (key0 + e >= total) v0[nt][e] = (bf16_t)0.f;
+                    if (key0 + e >= total) vr[nt][e] = (bf16_t)0.f;
         }
         const bool masked = (blk + 1) * kPfBlk > min_hi || blk * kPfBlk < max_lo;
         bf16x8 pv[MT];
@@ -165,7 +169,7 @@ void prefill_attention_kernel(PrefillParams p) {
                 for (int e = 0; e < 8; ++e)
                     if (key0 + e >= hi_row[mt] || key0 + e < lo_row[mt]) sv[e] = -INFINITY;
             }
-            float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            float mx = pf_max3(pf_max3(sv[0], sv[1], sv[2]), pf_max3(sv[3], sv[4], sv[5]), pf_max3(sv[6], sv[7], sv[7]));
             mx *= p.scale_log2;
             if (__any(mx > m_run[mt] + kLazy)) {
                 mx = pf_xor16_max(mx);
@@ -173,7 +177,14 @@ void prefill_attention_kernel(PrefillParams p) {
                     const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - mx);     // m_run = -inf gives 0
                     l_run[mt] *= alpha;
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= alpha;
+                    for (int nt = 0; nt < NT; ++nt) {
+                        // With 64 rows per wave the output accumulators live in the accumulation registers, which
+                        // vector arithmetic cannot read directly.  Left alone, the compiler copies all 128 of them
+                        // out ahead of this (rare) branch in every block, doubling the instruction count of the
+                        // loop; naming that register class here keeps the copies inside the branch.
+                        if constexpr (D * MT > 256) asm volatile("" : "+a"(acc[mt][nt]));
+                        acc[mt][nt] *= alpha;
+                    }
                     m_run[mt] = mx;
                 }
             }
@@ -187,12 +198,30 @@ void prefill_attention_kernel(PrefillParams p) {
             }
             l_run[mt] += ps;
         }
-        // ---- O^T += V^T P^T ----
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v0[nt], pv[mt], acc[mt][nt], 0, 0, 0);
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vr[nt], pv[mt], acc[mt][nt], 0, 0, 0);
+    };
+    // d <= 128: one register set refilled in halves -- the next block's keys are requested as soon as the scores
+    // are formed, its values after the second product.  d = 256: loads at the top of the loop (the longer live
+    // ranges of the refill scheme spill there).
+    // (Tried and dropped at 8 x 2048 positions, d = 128: two key / value register sets with Q re-read from LDS,
+    // 489 against 420 us; the score product of block j+1 issued ahead of the softmax of block j, 332 against 336 us
+    // -- one wave per SIMD issues a 16x16x32 matrix instruction only every ~31 cycles, and its vector arithmetic
+    // does not overlap them; 32 rows per wave with two waves per SIMD, 343-378 us: the vector cache cannot feed
+    // twice the operand traffic.)
+    constexpr bool REFILL = D <= 128;
+    bf16x8 k0[2][KS], v0[NT];
+    floatx4 s0[MT], s1[MT];
+    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const bool more = REFILL && blk + 1 < blk_end;
+        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
+        scores(k0, s0, s1);
+        if (more) load_k(blk + 1, k0);
+        finish(blk, s0, s1, v0);
         if (more) load_v(blk + 1, v0);
     }
 
