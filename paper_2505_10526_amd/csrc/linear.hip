@@ -2,21 +2,19 @@
 // counterpart of the verify projections: the multimodal projector that maps the vision encoder's features into
 // the language model's embedding space (paper Section 3.1) and the projections of an image-token prefill.
 //
-// One workgroup of four waves owns a 256-feature x 256-row tile of Y; each wave a 128 x 128 quarter held as 4 x 4
-// accumulators of v_mfma_f32_32x32x16_bf16 (all 256 accumulation registers).  A single wave per SIMD cannot issue
-// the 16x16x32 form back to back (measured 31 cycles per instruction against 16), the 32x32x16 form it can.
+// One workgroup of eight waves owns a 256-feature x 256-row tile of Y; each wave a 64 x 128 piece held as 2 x 4
+// accumulators of v_mfma_f32_32x32x16_bf16 (128 accumulation registers), two waves per SIMD so that one wave's
+// matrix instructions issue while the other waits for its fragments.  (A single wave per SIMD with a 128 x 128
+// piece reads less from LDS but gets a matrix instruction out only every 40 cycles instead of 32.)
 // Both operands arrive in operand order (W: the streaming layout of massv_weight_pack; X: re-laid out by
 // linear_pack_kernel), so every global load and every LDS access is a contiguous 1 KB per wave.
-// Pipeline per 64-wide k-step (four quarter-steps of 16 matrix instructions):
-//   * the tile of step ks+2 is requested from global memory into one of two register sets,
-//   * the tile of step ks+1 (requested a whole step earlier) moves to the other LDS buffer, one write per
-//     instruction slot, while quarters 1 and 2 are multiplied,
-//   * LDS reads of the next quarter's fragments are interleaved one per two matrix instructions (a burst of
-//     reads in front of the matrix instructions left the matrix pipe idle a third of the time),
-//   * the one barrier of the step sits in the middle of quarter 3 with matrix instructions queued on both sides.
+// Pipeline: a ring of four 32-wide k-stages in LDS (4 x 32 KB).  Stages travel from global memory straight into
+// LDS (global_load_lds, 16 bytes per lane, no staging registers and no LDS store instructions), three stages ahead
+// of the one being multiplied; one barrier per stage; the LDS reads of the next 16-wide quarter-step's fragments sit
+// one behind each of the current quarter-step's first matrix instructions.
 // The matrix instruction is issued through inline assembly with the accumulator tied as input and output: with
 // the builtin the register allocator separates the two whenever an accumulator is updated twice in one loop body
-// and then has to shuffle 256 accumulator registers every iteration.
+// and then has to shuffle the accumulator registers every iteration.
 #include "kernels.h"
 
 #include <atomic>
@@ -25,7 +23,8 @@ namespace massv {
 
 constexpr int kLinTile = 256;            // rows / features per workgroup
 constexpr int kLinGroupM = 8;            // row tiles per scheduling group
-constexpr size_t kLinLds = 2 * 2 * 2 * 16 * 64 * sizeof(bf16x8);      // [buf][k32 sub-step][W|X][tile16 * 64 + lane] = 128 KB
+constexpr size_t kLinLds = 4 * 2 * 16 * 64 * sizeof(bf16x8);          // [stage][W|X][tile16 * 64 + lane] = 128 KB
+constexpr int kLinWaves = 8;             // waves per workgroup (the kernel also builds with 4: 128 x 128 per wave)
 
 template <int ACT>
 __device__ inline float linear_act(float v) {
@@ -50,13 +49,20 @@ __global__ void linear_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __res
     *reinterpret_cast<bf16x8*>(dst + o * 8) = v;
 }
 
-template <int ACT>
-__global__ __launch_bounds__(256)
+// Tile kernel.  WAVES = 4: each wave a 128 x 128 quarter (4 x 4 accumulators, one wave per SIMD); WAVES = 8: each wave
+// 64 features x 128 rows (2 x 4 accumulators, two waves per SIMD).
+template <int ACT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64)
 void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict__ wpk, const bf16_t* __restrict__ bias,
                         bf16_t* __restrict__ y, int M, int N, int K, int tiles_m, int tiles_n) {
+    constexpr int FI = WAVES == 4 ? 4 : 2;        // 32-feature fragments per wave
+    constexpr int FJ = 4;                         // 32-row fragments per wave
+    constexpr int NMF = FI * FJ, NF = FI + FJ;    // matrix instructions and fragment loads per 16-wide quarter-step
+    constexpr int U = 32 / WAVES;                 // 1 KB pieces of a stage each wave brings in
     extern __shared__ bf16x8 lds_raw[];
-    bf16x8 (*lds)[2][2][16 * 64] = reinterpret_cast<bf16x8 (*)[2][2][16 * 64]>(lds_raw);
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    bf16x8 (*lds)[2][16 * 64] = reinterpret_cast<bf16x8 (*)[2][16 * 64]>(lds_raw);          // [stage][W|X][tile16 * 64 + lane]
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wy = wave / 2, wx = wave % 2;
     // Workgroup -> tile.  Consecutive workgroup ids go to different compute dies, each with its own L2: every die
     // gets a contiguous range of logical ids, and logical ids walk the tile grid in groups of kLinGroupM row tiles,
@@ -73,118 +79,122 @@ void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict
     const int tm = first_m + (pid % in_group) % gsz;
     const int tn = (pid % in_group) / gsz;
 
-    const int KS = K / 32, KS2 = K / 64, lastk = KS2 - 1;
+    const int KS = K / 32;
     const int n16 = N / 16, m16 = (M + 15) / 16;
-    // wave w stages feature tiles and row tiles 4w .. 4w+3; out-of-range tiles read a valid one instead (their
-    // results are never stored)
-    const bf16x8* wsrc[4];
-    const bf16x8* xsrc[4];
+    // Piece u of a stage (u < 16: feature tile u of W, else row tile u - 16 of X) is brought in by wave u / U, straight
+    // from global memory into LDS: lane l's 16 bytes land at the piece's base + 16 l, which is the layout the pieces
+    // have in memory.  Out-of-range tiles read a valid one instead (their results are never stored).
+    const bf16x8* src[U];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        int T = tn * 16 + 4 * wave + t; T = T < n16 ? T : n16 - 1;
-        wsrc[t] = reinterpret_cast<const bf16x8*>(wpk + ((size_t)T * KS) * 512) + lane;
-        int U = tm * 16 + 4 * wave + t; U = U < m16 ? U : m16 - 1;
-        xsrc[t] = reinterpret_cast<const bf16x8*>(xpk + ((size_t)U * KS) * 512) + lane;
+    for (int t = 0; t < U; ++t) {
+        const int u = wave * U + t;
+        if (u < 16) {
+            int T = tn * 16 + u; T = T < n16 ? T : n16 - 1;
+            src[t] = reinterpret_cast<const bf16x8*>(wpk + ((size_t)T * KS) * 512) + lane;
+        } else {
+            int R = tm * 16 + (u - 16); R = R < m16 ? R : m16 - 1;
+            src[t] = reinterpret_cast<const bf16x8*>(xpk + ((size_t)R * KS) * 512) + lane;
+        }
     }
-    bf16x8 gA[16], gB[16];
-    auto gload = [&](int ks, bf16x8 (&g)[16]) {
+    auto issue = [&](int ks, int slot) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                g[u * 8 + t] = wsrc[t][(size_t)(2 * ks + u) * 64];
-                g[u * 8 + 4 + t] = xsrc[t][(size_t)(2 * ks + u) * 64];
-            }
-    };
-    // n-th of the 16 staged 1 KB pieces of a k-step -> LDS
-    auto lstore1 = [&](int buf, const bf16x8 (&g)[16], int n) {
-        const int u = n / 8, r = n % 8, t = r % 4;
-        lds[buf][u][r < 4 ? 0 : 1][(4 * wave + t) * 64 + lane] = g[n];
+        for (int t = 0; t < U; ++t) {
+            const int u = wave * U + t;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[t] + (size_t)ks * 64),
+                                             (__attribute__((address_space(3))) void*)&lds[slot][u / 16][(u % 16) * 64], 16, 0, 0);
+        }
     };
 
-    floatx16 acc[4][4];
+    floatx16 acc[FI][FJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < FJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     // operand fragment (32 rows x 16 k) out of the 16-row x 32-k tiles in LDS: lane l takes row l % 32 and k chunk
     // l / 32 of half h, i.e. unit (tile16 = 2 i + (l % 32) / 16, lane' = l % 16 + 16 (2 h + l / 32))
     const int frag_off = ((lane % 32) / 16) * 64 + (lane % 16) + 16 * (lane / 32);
-    bf16x8 wf[2][4], xf[2][4];
-    // fragment f of quarter-step s (s = 2 u + h): f < 4 a feature fragment, else a row fragment
-    auto load_frag = [&](int buf, int s, int f, bf16x8 (&w)[4], bf16x8 (&x4)[4]) {
-        if (f < 4) w[f] = lds[buf][s / 2][0][(8 * wy + 2 * f) * 64 + frag_off + 32 * (s % 2)];
-        else x4[f - 4] = lds[buf][s / 2][1][(8 * wx + 2 * (f - 4)) * 64 + frag_off + 32 * (s % 2)];
+    bf16x8 wf[2][FI], xf[2][FJ];
+    // fragment f of half h of a stage: f < FI a feature fragment, else a row fragment
+    auto load_frag = [&](int slot, int h, int f, bf16x8 (&w)[FI], bf16x8 (&x4)[FJ]) {
+        if (f < FI) w[f] = lds[slot][0][(2 * FI * wy + 2 * f) * 64 + frag_off + 32 * h];
+        else x4[f - FI] = lds[slot][1][(8 * wx + 2 * (f - FI)) * 64 + frag_off + 32 * h];
     };
     auto mfma = [&](floatx16& c, bf16x8 a, bf16x8 b) {
         asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     };
+    // The compiler does not know that the loads above write LDS, so the waits are written here: the loads of a wave
+    // complete in order, and the counter operand is how many of the most recent ones may still be in flight.
+    auto wait_loads = [&](bool keep_one_stage) {
+        if (keep_one_stage) {
+            if constexpr (U == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
 
-    gload(0, gA);
-    gload(1 < KS2 ? 1 : lastk, gB);
-#pragma unroll
-    for (int n = 0; n < 16; ++n) lstore1(0, gA, n);
+    // Ring of four stages (32 k each).  Stage s + 3 is requested while stage s is multiplied; the barrier in the
+    // middle of stage s tells every wave that stage s + 1 has landed for all of them and that nobody reads stage
+    // s - 1 any more (its last fragments were fetched during the first half of stage s - 1), whose slot the new
+    // request overwrites.
+    issue(0, 0);
+    if (1 < KS) issue(1, 1);
+    if (2 < KS) issue(2, 2);
+    if (2 < KS) { if constexpr (U == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+    else wait_loads(1 < KS);
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < 8; ++f) load_frag(0, 0, f, wf[0], xf[0]);
+    for (int f = 0; f < NF; ++f) load_frag(0, 0, f, wf[0], xf[0]);
 
-    // step ks: g_free held tile ks (already in LDS) and receives tile ks+2; g_next holds tile ks+1.  Loads past the
-    // end re-read the last tile and what they bring is never multiplied.
-    auto step = [&](int ks, bf16x8 (&g_free)[16], const bf16x8 (&g_next)[16]) {
-        const int buf = ks & 1;
+    for (int s = 0; s < KS; ++s) {
+        const int slot = s & 3;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            if (s4 == 0) gload(ks + 2 < KS2 ? ks + 2 : lastk, g_free);
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int p = 0; p < 8; ++p) {
+            for (int idx = 0; idx < NMF; ++idx) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (s4 < 3) load_frag(buf, s4 + 1, p, wf[(s4 + 1) % 2], xf[(s4 + 1) % 2]);
-                if (s4 == 1 || s4 == 2) lstore1(buf ^ 1, g_next, (s4 - 1) * 8 + p);
-                if (s4 == 3 && p == 4) __syncthreads();
-                if (s4 == 3 && p >= 4) {                        // the next step's first fragments (set 0 is free)
-                    load_frag(buf ^ 1, 0, 2 * (p - 4), wf[0], xf[0]);
-                    load_frag(buf ^ 1, 0, 2 * (p - 4) + 1, wf[0], xf[0]);
+                const int j = idx / FI, i = idx % FI;
+                mfma(acc[i][j], wf[h][i], xf[h][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                // the next quarter-step's fragments, one behind each of this one's first matrix instructions (past the
+                // last stage they read a slot that holds nothing new; what they bring is never multiplied)
+                if (idx < NF) {
+                    if (h == 0) load_frag(slot, 1, idx, wf[1], xf[1]);
+                    else load_frag((s + 1) & 3, 0, idx, wf[0], xf[0]);
+                }
+                if (h == 0 && idx == 1) {
+                    wait_loads(s + 2 < KS);
+                    __syncthreads();
+                    if (s + 3 < KS) issue(s + 3, (s + 3) & 3);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int idx = 2 * p + t, j = idx / 4, i = idx % 4;
-                    mfma(acc[i][j], wf[s4 % 2][i], xf[s4 % 2][j]);
-                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-    };
-    int ks = 0;
-    for (; ks + 1 < KS2; ks += 2) {
-        step(ks, gA, gB);
-        step(ks + 1, gB, gA);
     }
-    if (ks < KS2) step(ks, gA, gB);
     // The matrix instructions above are assembly the compiler cannot see into: it does not know that their results
     // arrive up to 16 passes (64 cycles) after issue, so it inserts no wait before the epilogue reads the
-    // accumulators.  The wait is written here -- 4 x 16 idle cycles -- and tied to the data: the two statements take
+    // accumulators.  The wait is written here -- 4 x 16 idle cycles -- and tied to the data: the statements take
     // every accumulator as an in/out operand, so neither a matrix instruction nor an accumulator read can be
-    // scheduled across them (two statements because one takes at most 30 operands; volatile keeps their order).
+    // scheduled across them (several statements because one takes at most 30 operands; volatile keeps their order).
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
                  : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
                    "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]));
-    asm volatile("" : "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
-                      "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
+    if constexpr (FI == 4)
+        asm volatile("" : "+a"(acc[FI - 2][0]), "+a"(acc[FI - 2][1]), "+a"(acc[FI - 2][2]), "+a"(acc[FI - 2][3]),
+                          "+a"(acc[FI - 1][0]), "+a"(acc[FI - 1][1]), "+a"(acc[FI - 1][2]), "+a"(acc[FI - 1][3]));
 
     // epilogue: lane holds features 32 i + 8 g + 4 (lane / 32) + r (g, r = 0..3) of row 32 j + lane % 32
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < FJ; ++j) {
         const int m = tm * kLinTile + 128 * wx + 32 * j + lane % 32;
         if (m >= M) continue;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FI; ++i)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const int n = tn * kLinTile + 128 * wy + 32 * i + 8 * g4 + 4 * (lane / 32);
+                const int n = tn * kLinTile + 32 * FI * wy + 32 * i + 8 * g4 + 4 * (lane / 32);
                 if (n >= N) continue;
                 float v[4];
 #pragma unroll
@@ -232,8 +242,8 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MASSV_ELAUNCH;
     if (!lds_ready[dev].load(std::memory_order_acquire)) {
-        const void* kernels[4] = {(const void*)linear_tile_kernel<MASSV_LIN_NONE>, (const void*)linear_tile_kernel<MASSV_LIN_SILU>,
-                                  (const void*)linear_tile_kernel<MASSV_LIN_GELU_TANH>, (const void*)linear_tile_kernel<MASSV_LIN_GELU_ERF>};
+        const void* kernels[4] = {(const void*)linear_tile_kernel<MASSV_LIN_NONE, kLinWaves>, (const void*)linear_tile_kernel<MASSV_LIN_SILU, kLinWaves>,
+                                  (const void*)linear_tile_kernel<MASSV_LIN_GELU_TANH, kLinWaves>, (const void*)linear_tile_kernel<MASSV_LIN_GELU_ERF, kLinWaves>};
         for (const void* k : kernels)
             if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLds) != hipSuccess) return MASSV_ELAUNCH;
         lds_ready[dev].store(true, std::memory_order_release);
@@ -243,23 +253,23 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     hipLaunchKernelGGL(linear_pack_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const bf16_t*)x,
                        (bf16_t*)workspace, chunks, M, K);
     const int tiles_m = (M + kLinTile - 1) / kLinTile, tiles_n = (N + kLinTile - 1) / kLinTile;
-    const dim3 grid(tiles_m * tiles_n), block(256);
+    const dim3 grid(tiles_m * tiles_n), block(kLinWaves * kWave);
     const bf16_t* xp = (const bf16_t*)workspace;
     switch (act) {
         case MASSV_LIN_SILU:
-            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_SILU>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_SILU, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
                           (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         case MASSV_LIN_GELU_TANH:
-            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_TANH>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_TANH, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
                           (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         case MASSV_LIN_GELU_ERF:
-            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_ERF>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_ERF, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
                           (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         default:
-            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_NONE>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
+            launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_NONE, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
                           (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
     }
     return launch_status();
