@@ -244,6 +244,197 @@ void prefill_attention_kernel(PrefillParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// The same kernel on the 32x32x16 matrix instruction: a lone wave per SIMD gets one of those out every ~40 cycles
+// against ~31 for the 16x16x32 form that does half the work.  A wave owns RT tiles of 32 stacked rows.
+//   S^T tile (32 key slots x 32 rows): lane l holds row l % 32 and the slots 8 (v / 4) + 4 (l / 32) + v % 4, v = 0..15.
+//   Key slot rho of a block carries key 16 (g / 2) + 8 h + 4 (g % 2) + r (rho = 8 g + 4 h + r), so that the lane's
+//   values v = 8 t .. 8 t + 7 are the keys 16 t + 8 (l / 32) + (0..7): as they stand they are the B operand of step t
+//   of O^T += V^T P^T, whose A operand is then one 16-byte load of 8 consecutive keys of one dim.
+// ---------------------------------------------------------------------------
+__device__ inline float pf_xor32_max(float v) { return fmaxf(v, __shfl_xor(v, 32, kWave)); }
+
+template <int D, int RT>
+__global__ __launch_bounds__(kPfThreads)
+void prefill_attention_kernel32(PrefillParams p) {
+    constexpr int KS = D / 16;          // 16-wide k-steps of the score product
+    constexpr int NT = D / 32;          // 32-dim tiles of the output
+    constexpr int RW = RT * 32;         // stacked rows per wave
+    const int pair = blockIdx.x, b = pair / p.n_kv, g = pair % p.n_kv;
+    const int tile = p.n_tiles - 1 - (int)blockIdx.y;                 // the longest key ranges are started first
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lr = lane % 32, hh = lane / 32;
+    const int G = p.n_q / p.n_kv;
+    int L = p.kv_len[b]; L = L < 0 ? 0 : L;
+    int n = p.n_new[b]; n = n < 0 ? 0 : (n > p.Lq ? p.Lq : n);
+    if (L + n > p.l_max) n = p.l_max - L > 0 ? p.l_max - L : 0;
+    const int rows = n * G;
+    const int r0 = (tile * kPfWaves + wave) * RW;                     // first stacked row of this wave
+    if (r0 >= rows) return;                                            // (no barriers below: waves are independent)
+    const int total = L + n;
+    const int m_bidir = p.n_bidir ? p.n_bidir[b] : 0;
+    const int W = p.window;
+    const size_t bg = (size_t)b * p.n_kv + g;
+
+    // ---- rows of this wave: position, visible key range; Q operand in registers ----
+    bf16x8 qreg[RT][KS];
+    int hi_row[RT], lo_row[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        int r = r0 + rt * 32 + lr;
+        if (r >= rows) r = rows - 1;                                   // padding rows repeat the last one; never stored
+        const int i = r / G, qh = r % G;
+        hi_row[rt] = pf_hi(L + i, m_bidir, total);
+        lo_row[rt] = pf_lo(L + i, W);
+        const bf16_t* qr = p.q + (((size_t)b * p.Lq + i) * p.n_q + g * G + qh) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[rt][ks] = *reinterpret_cast<const bf16x8*>(qr + ks * 16 + hh * 8);
+    }
+    const int i_first = r0 / G;
+    const int r_last = (r0 + RW - 1 < rows - 1) ? r0 + RW - 1 : rows - 1;
+    const int i_last = r_last / G;
+    const int min_hi = pf_hi(L + i_first, m_bidir, total), max_hi = pf_hi(L + i_last, m_bidir, total);
+    const int min_lo = pf_lo(L + i_first, W), max_lo = pf_lo(L + i_last, W);
+    const int blk_begin = min_lo / kPfBlk, blk_end = (max_hi + kPfBlk - 1) / kPfBlk;
+
+    floatx16 acc[RT][NT];
+    float m_run[RT], l_run[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY; l_run[rt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][nt][e] = 0.f;
+    }
+
+    // key slot lr = 8 g + 4 h + r of a block -> key 16 (g / 2) + 8 h + 4 (g % 2) + r, which the blocked key cache
+    // keeps in its half g % 2 (bit 2 of the key) at place 4 (2 (g / 2) + h) + r; the lane's 8 dims are chunk
+    // 2 ks + hh of that half
+    const int sg = lr / 8, sh = (lr / 4) % 2, sr = lr % 4;
+    const bf16_t* kbase = p.kc + bg * (size_t)p.l_max * D + (size_t)(sg % 2) * (D * 16) + hh * 128 + ((2 * (sg / 2) + sh) * 4 + sr) * 8;
+    const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D + (size_t)lr * kPfBlk + hh * 8;
+    auto load_k = [&](int blk, bf16x8 (&kreg)[KS]) {
+        const bf16_t* kb = kbase + (size_t)blk * kPfBlk * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *reinterpret_cast<const bf16x8*>(kb + ks * 256);
+    };
+    // value operand (nt, t): dim 32 nt + lr, keys 16 t + 8 hh + (0..7) of the block
+    auto load_v = [&](int blk, bf16x8 (&vreg)[NT][2]) {
+        const bf16_t* vb = vbase + (size_t)blk * D * kPfBlk;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                vreg[nt][t] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 32) * kPfBlk + t * 16);
+    };
+
+    constexpr float kLazy = 8.0f;       // a row's reference exponent is raised only when exceeded by 2^8
+    auto scores = [&](bf16x8 (&kr)[KS], floatx16 (&sc)[RT]) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[rt][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                sc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qreg[rt][ks], sc[rt], 0, 0, 0);
+    };
+    auto finish = [&](int blk, floatx16 (&sc)[RT], bf16x8 (&vr)[NT][2]) {
+        const int key0 = blk * kPfBlk + hh * 8;            // value v of the lane is key key0 + 16 (v / 8) + v % 8
+        if ((blk + 1) * kPfBlk > total) {                  // rows past the valid length may hold anything
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (key0 + 16 * t + e >= total) vr[nt][t][e] = (bf16_t)0.f;
+        }
+        const bool masked = (blk + 1) * kPfBlk > min_hi || blk * kPfBlk < max_lo;
+        bf16x8 pv[RT][2];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float sv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sv[v] = sc[rt][v];
+            if (masked) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + 16 * (v / 8) + v % 8;
+                    if (key >= hi_row[rt] || key < lo_row[rt]) sv[v] = -INFINITY;
+                }
+            }
+            float mx = pf_max3(pf_max3(pf_max3(sv[0], sv[1], sv[2]), pf_max3(sv[3], sv[4], sv[5]), pf_max3(sv[6], sv[7], sv[8])),
+                               pf_max3(pf_max3(sv[9], sv[10], sv[11]), pf_max3(sv[12], sv[13], sv[14]), sv[15]), sv[15]);
+            mx *= p.scale_log2;
+            if (__any(mx > m_run[rt] + kLazy)) {
+                mx = pf_xor32_max(mx);
+                if (mx > m_run[rt] + kLazy) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - mx);     // m_run = -inf gives 0
+                    l_run[rt] *= alpha;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) {
+                        // keeps the copies out of the accumulation registers inside this rare branch
+                        asm volatile("" : "+a"(acc[rt][nt]));
+                        acc[rt][nt] *= alpha;
+                    }
+                    m_run[rt] = mx;
+                }
+            }
+            const float neg_m = (m_run[rt] == -INFINITY) ? 0.f : -m_run[rt];
+            float ps = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[v], p.scale_log2, neg_m));
+                ps += pe;
+                pv[rt][v / 8][v % 8] = (bf16_t)pe;
+            }
+            l_run[rt] += ps;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[nt][t], pv[rt][t], acc[rt][nt], 0, 0, 0);
+    };
+    constexpr bool REFILL = D <= 128;
+    bf16x8 k0[KS], v0[NT][2];
+    floatx16 sc[RT];
+    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const bool more = REFILL && blk + 1 < blk_end;
+        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
+        scores(k0, sc);
+        if (more) load_k(blk + 1, k0);
+        finish(blk, sc, v0);
+        if (more) load_v(blk + 1, v0);
+    }
+
+    // ---- write this wave's rows: lane holds dims 32 nt + 8 (v / 4) + 4 hh + v % 4 of row 32 rt + lr ----
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const float l = l_run[rt] + __shfl_xor(l_run[rt], 32, kWave);
+        const int r = r0 + rt * 32 + lr;
+        if (r >= rows) continue;
+        const float inv = 1.0f / l;                        // every row sees at least its own key
+        const int i = r / G, qh = r % G;
+        bf16_t* dst = p.out + (((size_t)b * p.Lq + i) * p.n_q + g * G + qh) * D + hh * 4;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const floatx16& v = acc[rt][nt];
+                bf16x4 o = {(bf16_t)(v[4 * q4] * inv), (bf16_t)(v[4 * q4 + 1] * inv), (bf16_t)(v[4 * q4 + 2] * inv), (bf16_t)(v[4 * q4 + 3] * inv)};
+                *reinterpret_cast<bf16x4*>(dst + nt * 32 + q4 * 8) = o;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // fp32: grid (L_q, n_q, B), 256 threads; keys 256 at a time (thread t scores key t, thread c accumulates column c).
 // Row-major fp32 keys, blocked values.
 // ---------------------------------------------------------------------------
@@ -304,13 +495,13 @@ void prefill_generic_kernel(const float* __restrict__ q, const float* __restrict
     if (tid < d) out[(((size_t)b * Lq + i) * n_q + h) * d + tid] = acc / l_run;
 }
 
-template <int D, int MT>
+template <int D, int RT>
 static int launch_prefill(const massv_attn_desc& a, PrefillParams p, hipStream_t st) {
     const int rows_max = a.n_query * (a.n_q_heads / a.n_kv_heads);
-    const int per_wg = kPfWaves * MT * 16;
+    const int per_wg = kPfWaves * RT * 32;
     p.n_tiles = (rows_max + per_wg - 1) / per_wg;
     if (p.n_tiles > 65535) return MASSV_EUNSUPPORTED;
-    launch_traced(MASSV_K_PREFILL_ATTENTION, prefill_attention_kernel<D, MT>, dim3(a.batch * a.n_kv_heads, p.n_tiles),
+    launch_traced(MASSV_K_PREFILL_ATTENTION, prefill_attention_kernel32<D, RT>, dim3(a.batch * a.n_kv_heads, p.n_tiles),
                   dim3(kPfThreads), 0, st, p);
     return launch_status();
 }
@@ -349,9 +540,9 @@ extern "C" int massv_prefill_attention(const massv_attn_desc* desc, const void* 
     p.n_tiles = 0;
     p.scale_log2 = scale * 1.4426950408889634f;
     switch (a.head_dim) {
-        case 64: return launch_prefill<64, 4>(a, p, st);
-        case 128: return launch_prefill<128, 4>(a, p, st);
-        case 256: return launch_prefill<256, 2>(a, p, st);
+        case 64: return launch_prefill<64, 2>(a, p, st);
+        case 128: return launch_prefill<128, 2>(a, p, st);
+        case 256: return launch_prefill<256, 1>(a, p, st);
     }
     return MASSV_EUNSUPPORTED;
 }
