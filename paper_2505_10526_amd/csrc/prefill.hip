@@ -23,6 +23,8 @@
 // fp32: the plain one-workgroup-per-(position, head) kernel below, for the small configuration.
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace massv {
 
 constexpr int kPfWaves = 4;
@@ -330,20 +332,26 @@ void prefill_attention_kernel32(PrefillParams p) {
     };
 
     constexpr float kLazy = 8.0f;       // a row's reference exponent is raised only when exceeded by 2^8
-    auto scores = [&](bf16x8 (&kr)[KS], floatx16 (&sc)[RT]) {
+    // ---- pieces of one block for one row tile ----
+    // S^T tile: KS matrix instructions
+    auto s_tile = [&](bf16x8 (&kr)[KS], int rt, floatx16& sc) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+        for (int e = 0; e < 16; ++e) sc[e] = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sc[rt][e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-                sc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qreg[rt][ks], sc[rt], 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qreg[rt][ks], sc, 0, 0, 0);
     };
-    auto finish = [&](int blk, floatx16 (&sc)[RT], bf16x8 (&vr)[NT][2]) {
-        const int key0 = blk * kPfBlk + hh * 8;            // value v of the lane is key key0 + 16 (v / 8) + v % 8
-        if ((blk + 1) * kPfBlk > total) {                  // rows past the valid length may hold anything
+    // O^T += V^T P^T: 2 NT matrix instructions
+    auto pv_tile = [&](int rt, bf16x8 (&vr)[NT][2], bf16x8 (&pv)[2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[rt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[nt][t], pv[t], acc[rt][nt], 0, 0, 0);
+    };
+    // values of rows past the valid length may hold anything: zero them (last block only)
+    auto v_clean = [&](int blk, bf16x8 (&vr)[NT][2]) {
+        const int key0 = blk * kPfBlk + hh * 8;
+        if ((blk + 1) * kPfBlk > total) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -352,66 +360,168 @@ void prefill_attention_kernel32(PrefillParams p) {
                     for (int e = 0; e < 8; ++e)
                         if (key0 + 16 * t + e >= total) vr[nt][t][e] = (bf16_t)0.f;
         }
+    };
+    // first half of the streaming softmax: masks, the lane's maximum, and (rarely) a raised reference with the
+    // accumulators rescaled.  Value v of the lane is key key0 + 16 (v / 8) + v % 8.
+    auto soft_max = [&](int rt, int blk, floatx16& sc) {
+        const int key0 = blk * kPfBlk + hh * 8;
         const bool masked = (blk + 1) * kPfBlk > min_hi || blk * kPfBlk < max_lo;
-        bf16x8 pv[RT][2];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            float sv[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sv[v] = sc[rt][v];
-            if (masked) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + 16 * (v / 8) + v % 8;
-                    if (key >= hi_row[rt] || key < lo_row[rt]) sv[v] = -INFINITY;
-                }
-            }
-            float mx = pf_max3(pf_max3(pf_max3(sv[0], sv[1], sv[2]), pf_max3(sv[3], sv[4], sv[5]), pf_max3(sv[6], sv[7], sv[8])),
-                               pf_max3(pf_max3(sv[9], sv[10], sv[11]), pf_max3(sv[12], sv[13], sv[14]), sv[15]), sv[15]);
-            mx *= p.scale_log2;
-            if (__any(mx > m_run[rt] + kLazy)) {
-                mx = pf_xor32_max(mx);
-                if (mx > m_run[rt] + kLazy) {
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - mx);     // m_run = -inf gives 0
-                    l_run[rt] *= alpha;
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        // keeps the copies out of the accumulation registers inside this rare branch
-                        asm volatile("" : "+a"(acc[rt][nt]));
-                        acc[rt][nt] *= alpha;
-                    }
-                    m_run[rt] = mx;
-                }
-            }
-            const float neg_m = (m_run[rt] == -INFINITY) ? 0.f : -m_run[rt];
-            float ps = 0.f;
+        if (masked) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[v], p.scale_log2, neg_m));
-                ps += pe;
-                pv[rt][v / 8][v % 8] = (bf16_t)pe;
+                const int key = key0 + 16 * (v / 8) + v % 8;
+                if (key >= hi_row[rt] || key < lo_row[rt]) sc[v] = -INFINITY;
             }
-            l_run[rt] += ps;
         }
+        float mx = pf_max3(pf_max3(pf_max3(sc[0], sc[1], sc[2]), pf_max3(sc[3], sc[4], sc[5]), pf_max3(sc[6], sc[7], sc[8])),
+                           pf_max3(pf_max3(sc[9], sc[10], sc[11]), pf_max3(sc[12], sc[13], sc[14]), sc[15]), sc[15]);
+        mx *= p.scale_log2;
+        if (__any(mx > m_run[rt] + kLazy)) {
+            mx = pf_xor32_max(mx);
+            if (mx > m_run[rt] + kLazy) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - mx);     // m_run = -inf gives 0
+                l_run[rt] *= alpha;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
-                    acc[rt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[nt][t], pv[rt][t], acc[rt][nt], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt) {
+                    // keeps the copies out of the accumulation registers inside this rare branch
+                    asm volatile("" : "+a"(acc[rt][nt]));
+                    acc[rt][nt] *= alpha;
+                }
+                m_run[rt] = mx;
+            }
+        }
     };
-    constexpr bool REFILL = D <= 128;
-    bf16x8 k0[KS], v0[NT][2];
-    floatx16 sc[RT];
-    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
-        const bool more = REFILL && blk + 1 < blk_end;
-        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
-        scores(k0, sc);
-        if (more) load_k(blk + 1, k0);
-        finish(blk, sc, v0);
-        if (more) load_v(blk + 1, v0);
+    // second half: probabilities relative to the reference, their sum, and the bf16 operand of the second product
+    auto soft_exp = [&](int rt, const floatx16& sc, bf16x8 (&pv)[2]) {
+        const float neg_m = (m_run[rt] == -INFINITY) ? 0.f : -m_run[rt];
+        float ps = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float pe = __builtin_amdgcn_exp2f(fmaf(sc[v], p.scale_log2, neg_m));
+            ps += pe;
+            pv[v / 8][v % 8] = (bf16_t)pe;
+        }
+        l_run[rt] += ps;
+    };
+
+    if constexpr (RT == 2) {
+        // Two row tiles A and B leapfrog, so that the vector arithmetic of one tile's softmax is issued between the
+        // matrix instructions of the other tile (one wave per SIMD: a matrix instruction holds the wave's issue for
+        // about 18 of the 40 cycles it needs, the rest is free for independent vector instructions -- but only if
+        // the instruction stream alternates, since a wave issues in order):
+        //   step 1 of block i:  exponentials of (B, i)      between   O_A += V_i P_A,i   and   S_A,i+1 = K_i+1 Q_A
+        //   step 2 of block i:  exponentials of (A, i + 1)  between   O_B += V_i P_B,i   and   S_B,i+1 = K_i+1 Q_B
+        // Keys are held two blocks ahead and values one block ahead, in two register sets each.
+        // A step is two halves of 8 score values each: the first next to the KS matrix instructions of the other
+        // tile's next scores, the second next to the 2 NT matrix instructions of the other tile's second product.
+        // One key set and one value set: the keys of block i + 2 are requested as soon as the scores of block i + 1
+        // are formed (middle of step 2), the values of block i + 1 at the end of step 2; each has the other half of
+        // the work before it is needed.
+        auto exps = [&](int rv, const floatx16& sv, bf16x8& po, int v0, float neg_m, float& ps) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[v0 + e], p.scale_log2, neg_m));
+                ps += pe;
+                po[e] = (bf16_t)pe;
+            }
+        };
+        auto order = [&](auto n_mfma) {            // the order asked of the scheduler for one half
+            constexpr int N = decltype(n_mfma)::value, VP = 8 / N;
+#pragma unroll
+            for (int m = 0; m < N; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2 * VP, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, VP, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2 * VP, 0);
+            }
+        };
+        // first half: tile rv's values 0..7, tile rm's scores of the block whose keys kq holds
+        auto half_s = [&](int rv, const floatx16& sv, bf16x8 (&pvo)[2], float neg_m, float& ps, int rm, bf16x8 (&kq)[KS], floatx16& sm) {
+            __builtin_amdgcn_sched_barrier(0);
+            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                sm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[ks], qreg[rm][ks], ks == 0 ? zero : sm, 0, 0, 0);
+            exps(rv, sv, pvo[0], 0, neg_m, ps);
+            order(std::integral_constant<int, KS>{});
+            // (the probabilities are first needed a step later; without a use here the compiler moves their
+            // arithmetic down to that step, away from the matrix instructions it is meant to sit between)
+            asm volatile("" : "+v"(pvo[0]), "+v"(ps));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // second half: tile rv's values 8..15, tile rm's second product with the values vq holds
+        auto half_pv = [&](int rv, const floatx16& sv, bf16x8 (&pvo)[2], float neg_m, float& ps, int rm, bf16x8 (&pm)[2], bf16x8 (&vq)[NT][2]) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[rm][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[nt][t], pm[t], acc[rm][nt], 0, 0, 0);
+            exps(rv, sv, pvo[1], 8, neg_m, ps);
+            order(std::integral_constant<int, 2 * NT>{});
+            asm volatile("" : "+v"(pvo[1]), "+v"(ps));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        const int nb = blk_end - blk_begin;
+        bf16x8 kq[KS], vq[NT][2];
+        floatx16 sA, sB;
+        bf16x8 pA[2], pB[2];
+        if (nb > 0) {
+            load_k(blk_begin, kq);
+            s_tile(kq, 0, sA);
+            s_tile(kq, 1, sB);
+            if (nb > 1) load_k(blk_begin + 1, kq);
+            load_v(blk_begin, vq);                     // keys before values, the order the loop requests them in
+            soft_max(0, blk_begin, sA);
+            soft_exp(0, sA, pA);
+        }
+        // entering block i: kq holds the keys of block i + 1, vq the values of block i, pA tile A's probabilities
+        // and sB tile B's scores of block i
+        for (int i = 0; i + 1 < nb; ++i) {
+            const int blk = blk_begin + i;
+            v_clean(blk, vq);
+            soft_max(1, blk, sB);
+            {
+                const float neg_m = (m_run[1] == -INFINITY) ? 0.f : -m_run[1];
+                float ps = 0.f;
+                half_s(1, sB, pB, neg_m, ps, 0, kq, sA);
+                half_pv(1, sB, pB, neg_m, ps, 0, pA, vq);
+                l_run[1] += ps;
+            }
+            soft_max(0, blk + 1, sA);
+            {
+                const float neg_m = (m_run[0] == -INFINITY) ? 0.f : -m_run[0];
+                float ps = 0.f;
+                half_s(0, sA, pA, neg_m, ps, 1, kq, sB);
+                if (i + 2 < nb) load_k(blk + 2, kq);
+                half_pv(0, sA, pA, neg_m, ps, 1, pB, vq);
+                load_v(blk + 1, vq);
+                l_run[0] += ps;
+            }
+        }
+        if (nb > 0) {                                  // the last block: nothing follows tile A's second product
+            const int blk = blk_end - 1;
+            v_clean(blk, vq);
+            soft_max(1, blk, sB);
+            const float neg_m = (m_run[1] == -INFINITY) ? 0.f : -m_run[1];
+            float ps = 0.f;
+            exps(1, sB, pB[0], 0, neg_m, ps);
+            half_pv(1, sB, pB, neg_m, ps, 0, pA, vq);
+            l_run[1] += ps;
+            pv_tile(1, vq, pB);
+        }
+    } else {
+        bf16x8 k0[KS], v0[NT][2];
+        floatx16 sc;
+        bf16x8 pv[2];
+        for (int blk = blk_begin; blk < blk_end; ++blk) {
+            load_k(blk, k0); load_v(blk, v0);
+            s_tile(k0, 0, sc);
+            v_clean(blk, v0);
+            soft_max(0, blk, sc);
+            soft_exp(0, sc, pv);
+            pv_tile(0, v0, pv);
+        }
     }
 
     // ---- write this wave's rows: lane holds dims 32 nt + 8 (v / 4) + 4 hh + v % 4 of row 32 rt + lr ----
