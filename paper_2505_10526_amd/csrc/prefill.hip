@@ -5,21 +5,26 @@
 // the roof, not HBM.
 //
 // bf16 kernel:
-//   * The caches are read in the library's blocked layouts, the same operand-order tiles verify_attention uses:
-//     a wave's key tile (16 keys x 32 dims) and value tile (16 dims x 32 keys) are each one 16-byte load per lane,
-//     no LDS staging and no transposes.
+//   * The caches are read in the library's blocked layouts; a wave's operands of both products are 16-byte loads per
+//     lane straight into registers, no LDS staging and no transposes.
 //   * The G query heads that share a KV head are stacked with the positions into rows (row = position * G + head),
 //     so every key / value tile fetched serves all G heads.
-//   * A wave owns 16*MT stacked rows (64 for d <= 128) for the whole key range: Q stays in registers as the B
-//     operand, scores are formed transposed (S^T = K Q^T) so that the probabilities already sit in the operand
-//     layout of O^T += V^T P^T, and the streaming softmax keeps (reference, sum, O) in registers.  Nothing is
-//     merged between waves; each writes its own rows.  64 rows per wave is what makes the operand traffic
-//     affordable: a key tile loaded once is multiplied against four row tiles.
+//   * A wave owns RT tiles of 32 stacked rows (64 rows for d <= 128) for the whole key range: Q stays in registers
+//     as the B operand of v_mfma_f32_32x32x16_bf16, scores are formed transposed (S^T = K Q^T) so that the
+//     probabilities already sit in the operand layout of O^T += V^T P^T, and the streaming softmax keeps
+//     (reference, sum, O) in registers.  Nothing is merged between waves; each writes its own rows.
 //   * The four waves of a workgroup take neighbouring row ranges, so they walk the same key blocks at nearly
 //     the same time and share them through the CU's vector cache; workgroups of one (sequence, KV head) pair
 //     have linear ids congruent modulo the pair count, which (8 dies, round-robin dispatch) puts them on one
 //     die whenever the pair count is a multiple of 8, so the pair's keys and values are fetched into one L2.
 //   * Only blocks that cross some row's first or last visible key pay for masks.
+// Measured and dropped at 8 x 2048 positions, d = 128 (the shipped kernel: 285-304 us):
+//   the 16x16x32 instruction with 4 tiles of 16 rows, 336-376 us (a lone wave issues one of those only every ~31
+//   cycles, and twice as many are needed); two key / value register sets with Q re-read from LDS, 489 us; 32 rows
+//   per wave with two waves per SIMD and operands loaded per wave, 343-378 us (the vector cache cannot feed twice
+//   the operand traffic); eight waves of 32 rows with the blocks staged once per workgroup in LDS by direct
+//   global->LDS loads (ring of 4 stages of 2 blocks, one barrier per stage), 283-313 us and no better on four
+//   other shapes: the barrier re-aligns the two waves of a SIMD, which then want the same unit at the same time.
 // fp32: the plain one-workgroup-per-(position, head) kernel below, for the small configuration.
 #include "kernels.h"
 
@@ -55,199 +60,9 @@ __device__ inline float pf_max3(float a, float b, float c) {
     return r;
 }
 
-__device__ inline float pf_xor16_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16, kWave));
-    return fmaxf(v, __shfl_xor(v, 32, kWave));
-}
-__device__ inline float pf_xor16_sum(float v) {
-    v += __shfl_xor(v, 16, kWave);
-    return v + __shfl_xor(v, 32, kWave);
-}
-
-template <int D, int MT>
-__global__ __launch_bounds__(kPfThreads)
-void prefill_attention_kernel(PrefillParams p) {
-    constexpr int KS = D / 32;          // k-steps of the score product
-    constexpr int NT = D / 16;          // 16-dim tiles of the output
-    constexpr int RW = MT * 16;         // stacked rows per wave
-    const int pair = blockIdx.x, b = pair / p.n_kv, g = pair % p.n_kv;
-    const int tile = p.n_tiles - 1 - (int)blockIdx.y;                 // the longest key ranges are started first
-    const int tid = threadIdx.x, lane = tid % kWave;
-    // the wave index as a scalar: everything derived from it (row range, key range, the loop, the mask decisions) then
-    // lives in scalar registers and branches, not in per-lane copies guarded by execution masks
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int lr = lane % 16, lc = lane / 16;
-    const int G = p.n_q / p.n_kv;
-    int L = p.kv_len[b]; L = L < 0 ? 0 : L;
-    int n = p.n_new[b]; n = n < 0 ? 0 : (n > p.Lq ? p.Lq : n);
-    if (L + n > p.l_max) n = p.l_max - L > 0 ? p.l_max - L : 0;
-    const int rows = n * G;
-    const int r0 = (tile * kPfWaves + wave) * RW;                     // first stacked row of this wave
-    if (r0 >= rows) return;                                            // (no barriers below: waves are independent)
-    const int total = L + n;
-    const int m_bidir = p.n_bidir ? p.n_bidir[b] : 0;
-    const int W = p.window;
-    const size_t bg = (size_t)b * p.n_kv + g;
-
-    // ---- rows of this wave: position, visible key range; Q operand in registers ----
-    bf16x8 qreg[MT][KS];
-    int hi_row[MT], lo_row[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        int r = r0 + mt * 16 + lr;
-        if (r >= rows) r = rows - 1;                                   // padding rows repeat the last one; never stored
-        const int i = r / G, hh = r % G;
-        hi_row[mt] = pf_hi(L + i, m_bidir, total);
-        lo_row[mt] = pf_lo(L + i, W);
-        const bf16_t* qr = p.q + (((size_t)b * p.Lq + i) * p.n_q + g * G + hh) * D;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qreg[mt][ks] = *reinterpret_cast<const bf16x8*>(qr + ks * 32 + lc * 8);
-    }
-    const int i_first = r0 / G;
-    const int r_last = (r0 + RW - 1 < rows - 1) ? r0 + RW - 1 : rows - 1;
-    const int i_last = r_last / G;
-    // both limits grow with the position: the wave's key range and the part of it that needs masks
-    const int min_hi = pf_hi(L + i_first, m_bidir, total), max_hi = pf_hi(L + i_last, m_bidir, total);
-    const int min_lo = pf_lo(L + i_first, W), max_lo = pf_lo(L + i_last, W);
-    const int blk_begin = min_lo / kPfBlk, blk_end = (max_hi + kPfBlk - 1) / kPfBlk;
-
-    floatx4 acc[MT][NT];
-    float m_run[MT], l_run[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        m_run[mt] = -INFINITY; l_run[mt] = 0.f;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const bf16_t* kbase = p.kc + bg * (size_t)p.l_max * D;
-    const bf16_t* vbase = p.vc + bg * (size_t)p.l_max * D;
-    // Loads stay cached: the other waves of the workgroup and the other row tiles of the pair read the same blocks.
-    auto load_k = [&](int blk, bf16x8 (&kreg)[2][KS]) {
-        const bf16_t* kb = kbase + (size_t)blk * kPfBlk * D + lane * 8;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kreg[t][ks] = *reinterpret_cast<const bf16x8*>(kb + (t * KS + ks) * 512);
-    };
-    auto load_v = [&](int blk, bf16x8 (&vreg)[NT]) {
-        const bf16_t* vb = vbase + (size_t)blk * D * kPfBlk + lc * 8;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            vreg[nt] = *reinterpret_cast<const bf16x8*>(vb + (size_t)(nt * 16 + lr) * kPfBlk);
-    };
-
-    constexpr float kLazy = 8.0f;       // a row's reference exponent is raised only when exceeded by 2^8
-    // ---- S^T = K Q^T of one block: lane holds keys 8 lc + (0..7) of the block for query row 16 mt + lr ----
-    auto scores = [&](bf16x8 (&kr)[2][KS], floatx4 (&s0)[MT], floatx4 (&s1)[MT]) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) { s0[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; s1[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                s0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[0][ks], qreg[mt][ks], s0[mt], 0, 0, 0);
-                s1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[1][ks], qreg[mt][ks], s1[mt], 0, 0, 0);
-            }
-    };
-    // ---- masks, streaming softmax and O^T += V^T P^T of one block, from its scores ----
-    auto finish = [&](int blk, floatx4 (&s0)[MT], floatx4 (&s1)[MT], bf16x8 (&vr)[NT]) {
-        const int key0 = blk * kPfBlk + lc * 8;
-        if ((blk + 1) * kPfBlk > total) {                  // rows past the valid length may hold anything
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (key0 + e >= total) vr[nt][e] = (bf16_t)0.f;
-        }
-        const bool masked = (blk + 1) * kPfBlk > min_hi || blk * kPfBlk < max_lo;
-        bf16x8 pv[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            float sv[8] = {s0[mt][0], s0[mt][1], s0[mt][2], s0[mt][3], s1[mt][0], s1[mt][1], s1[mt][2], s1[mt][3]};
-            if (masked) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (key0 + e >= hi_row[mt] || key0 + e < lo_row[mt]) sv[e] = -INFINITY;
-            }
-            float mx = pf_max3(pf_max3(sv[0], sv[1], sv[2]), pf_max3(sv[3], sv[4], sv[5]), pf_max3(sv[6], sv[7], sv[7]));
-            mx *= p.scale_log2;
-            if (__any(mx > m_run[mt] + kLazy)) {
-                mx = pf_xor16_max(mx);
-                if (mx > m_run[mt] + kLazy) {
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - mx);     // m_run = -inf gives 0
-                    l_run[mt] *= alpha;
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        // With 64 rows per wave the output accumulators live in the accumulation registers, which
-                        // vector arithmetic cannot read directly.  Left alone, the compiler copies all 128 of them
-                        // out ahead of this (rare) branch in every block, doubling the instruction count of the
-                        // loop; naming that register class here keeps the copies inside the branch.
-                        if constexpr (D * MT > 256) asm volatile("" : "+a"(acc[mt][nt]));
-                        acc[mt][nt] *= alpha;
-                    }
-                    m_run[mt] = mx;
-                }
-            }
-            const float neg_m = (m_run[mt] == -INFINITY) ? 0.f : -m_run[mt];
-            float ps = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], p.scale_log2, neg_m));
-                ps += pe;
-                pv[mt][e] = (bf16_t)pe;
-            }
-            l_run[mt] += ps;
-        }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vr[nt], pv[mt], acc[mt][nt], 0, 0, 0);
-    };
-    // d <= 128: one register set refilled in halves -- the next block's keys are requested as soon as the scores
-    // are formed, its values after the second product.  d = 256: loads at the top of the loop (the longer live
-    // ranges of the refill scheme spill there).
-    // (Tried and dropped at 8 x 2048 positions, d = 128: two key / value register sets with Q re-read from LDS,
-    // 489 against 420 us; the score product of block j+1 issued ahead of the softmax of block j, 332 against 336 us
-    // -- one wave per SIMD issues a 16x16x32 matrix instruction only every ~31 cycles, and its vector arithmetic
-    // does not overlap them; 32 rows per wave with two waves per SIMD, 343-378 us: the vector cache cannot feed
-    // twice the operand traffic.)
-    constexpr bool REFILL = D <= 128;
-    bf16x8 k0[2][KS], v0[NT];
-    floatx4 s0[MT], s1[MT];
-    if (REFILL && blk_begin < blk_end) { load_k(blk_begin, k0); load_v(blk_begin, v0); }
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
-        const bool more = REFILL && blk + 1 < blk_end;
-        if (!REFILL) { load_k(blk, k0); load_v(blk, v0); }
-        scores(k0, s0, s1);
-        if (more) load_k(blk + 1, k0);
-        finish(blk, s0, s1, v0);
-        if (more) load_v(blk + 1, v0);
-    }
-
-    // ---- write this wave's rows: lane (lr, lc) holds dims 16 nt + 4 lc + (0..3) of row 16 mt + lr ----
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const float l = pf_xor16_sum(l_run[mt]);
-        const int r = r0 + mt * 16 + lr;
-        if (r >= rows) continue;
-        const float inv = 1.0f / l;                        // every row sees at least its own key
-        const int i = r / G, hh = r % G;
-        bf16_t* dst = p.out + (((size_t)b * p.Lq + i) * p.n_q + g * G + hh) * D + lc * 4;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const floatx4 v = acc[mt][nt];
-            bf16x4 o = {(bf16_t)(v[0] * inv), (bf16_t)(v[1] * inv), (bf16_t)(v[2] * inv), (bf16_t)(v[3] * inv)};
-            *reinterpret_cast<bf16x4*>(dst + nt * 16) = o;
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
-// The same kernel on the 32x32x16 matrix instruction: a lone wave per SIMD gets one of those out every ~40 cycles
-// against ~31 for the 16x16x32 form that does half the work.  A wave owns RT tiles of 32 stacked rows.
+// A lone wave per SIMD gets a 32x32x16 matrix instruction out every ~40 cycles (against ~31 for the 16x16x32 form
+// that does half the work).  A wave owns RT tiles of 32 stacked rows.
 //   S^T tile (32 key slots x 32 rows): lane l holds row l % 32 and the slots 8 (v / 4) + 4 (l / 32) + v % 4, v = 0..15.
 //   Key slot rho of a block carries key 16 (g / 2) + 8 h + 4 (g % 2) + r (rho = 8 g + 4 h + r), so that the lane's
 //   values v = 8 t .. 8 t + 7 are the keys 16 t + 8 (l / 32) + (0..7): as they stand they are the B operand of step t
@@ -257,7 +72,7 @@ __device__ inline float pf_xor32_max(float v) { return fmaxf(v, __shfl_xor(v, 32
 
 template <int D, int RT>
 __global__ __launch_bounds__(kPfThreads)
-void prefill_attention_kernel32(PrefillParams p) {
+void prefill_attention_kernel(PrefillParams p) {
     constexpr int KS = D / 16;          // 16-wide k-steps of the score product
     constexpr int NT = D / 32;          // 32-dim tiles of the output
     constexpr int RW = RT * 32;         // stacked rows per wave
@@ -611,7 +426,7 @@ static int launch_prefill(const massv_attn_desc& a, PrefillParams p, hipStream_t
     const int per_wg = kPfWaves * RT * 32;
     p.n_tiles = (rows_max + per_wg - 1) / per_wg;
     if (p.n_tiles > 65535) return MASSV_EUNSUPPORTED;
-    launch_traced(MASSV_K_PREFILL_ATTENTION, prefill_attention_kernel32<D, RT>, dim3(a.batch * a.n_kv_heads, p.n_tiles),
+    launch_traced(MASSV_K_PREFILL_ATTENTION, prefill_attention_kernel<D, RT>, dim3(a.batch * a.n_kv_heads, p.n_tiles),
                   dim3(kPfThreads), 0, st, p);
     return launch_status();
 }
