@@ -206,6 +206,71 @@ def test_lm_head_greedy_accept_argument_checks(lib):
     assert f(*ok(wsb=ws - 1)) == binding.EWORKSPACE
 
 
+def test_lm_head_accept_argument_checks(lib):
+    f = lib.massv_lm_head_accept
+    ws = lib.massv_lm_head_accept_workspace(8, 5, 3584, 152064, binding.BF16)
+    assert ws >= lib.massv_lm_head_greedy_accept_workspace(8, 5, 3584, 152064, binding.BF16)
+    assert lib.massv_lm_head_accept_workspace(8, 5, 3584, 152064, binding.F32) == 0
+    ok = lambda **kw: [kw.get("x", FAKE), FAKE, kw.get("w", FAKE), kw.get("dl", FAKE), kw.get("d", FAKE), kw.get("u", FAKE),
+                       kw.get("T", 0.7), kw.get("B", 8), kw.get("g", 5), kw.get("H", 3584), kw.get("V", 152064), kw.get("eps", 1e-6),
+                       kw.get("dt", binding.BF16), kw.get("lg", FAKE), kw.get("n", FAKE), kw.get("o", FAKE), kw.get("ws", FAKE),
+                       kw.get("wsb", ws), None]
+    assert f(*ok(x=None)) == binding.EINVAL
+    assert f(*ok(w=None)) == binding.EINVAL
+    assert f(*ok(lg=None)) == binding.EINVAL               # T > 0: the residual draw reads the logits
+    assert f(*ok(u=None)) == binding.EINVAL
+    assert f(*ok(dl=None)) == binding.EINVAL
+    assert f(*ok(d=None)) == binding.EINVAL
+    assert f(*ok(n=None)) == binding.EINVAL
+    assert f(*ok(o=None)) == binding.EINVAL
+    assert f(*ok(T=-1.0)) == binding.EINVAL
+    assert f(*ok(T=float("nan"))) == binding.EINVAL
+    assert f(*ok(T=float("inf"))) == binding.EINVAL
+    assert f(*ok(eps=-1.0)) == binding.EINVAL
+    assert f(*ok(B=0)) == binding.EINVAL
+    assert f(*ok(T=0.0, x=None)) == binding.EINVAL         # T = 0 goes through the greedy call's checks
+    assert f(*ok(dt=binding.F32)) == binding.EUNSUPPORTED
+    assert f(*ok(B=11)) == binding.EUNSUPPORTED            # 66 rows
+    assert f(*ok(V=152065)) == binding.EUNSUPPORTED
+    assert f(*ok(wsb=ws - 1)) == binding.EWORKSPACE
+    assert f(*ok(ws=None)) == binding.EWORKSPACE
+
+
+def test_spec_accept_static_argument_checks(lib):
+    f = lib.massv_spec_accept_static
+    limit = lib.massv_spec_accept_static_limit()
+    assert limit == 4 << 20
+    ok = lambda **kw: [kw.get("t", FAKE), kw.get("d", FAKE), kw.get("x", FAKE), kw.get("u", FAKE), kw.get("T", 1.0),
+                       kw.get("B", 2), kw.get("g", 5), kw.get("V", 1000), kw.get("n", FAKE), kw.get("o", FAKE), None]
+    assert f(*ok(t=None)) == binding.EINVAL
+    assert f(*ok(d=None)) == binding.EINVAL
+    assert f(*ok(u=None)) == binding.EINVAL
+    assert f(*ok(n=None)) == binding.EINVAL
+    assert f(*ok(T=-0.5)) == binding.EINVAL
+    assert f(*ok(B=0)) == binding.EINVAL
+    assert f(*ok(g=99)) == binding.EUNSUPPORTED
+    # a call whose partial results do not fit the fixed array is refused before anything is looked up or launched
+    assert lib.massv_spec_accept_workspace(256, 7, 262144) > limit
+    assert f(*ok(B=256, g=7, V=262144)) == binding.EUNSUPPORTED
+
+
+def test_prefill_attention_argument_checks(lib):
+    f = lib.massv_prefill_attention
+    def desc(**kw):
+        return binding.AttnDesc(kw.get("B", 2), kw.get("Q", 64), kw.get("nq", 28), kw.get("nkv", 4), kw.get("d", 128),
+                                kw.get("lmax", 256), 0.0, kw.get("dt", binding.BF16), kw.get("window", 0))
+    args = lambda d, **kw: [C.byref(d) if d is not None else None, kw.get("q", FAKE), kw.get("k", FAKE), kw.get("v", FAKE),
+                            kw.get("kv", FAKE), kw.get("nn", FAKE), None, kw.get("o", FAKE), None]
+    assert f(*args(None)) == binding.EINVAL
+    for name in ("q", "k", "v", "kv", "nn", "o"):
+        assert f(*args(desc(), **{name: None})) == binding.EINVAL
+    assert f(*args(desc(Q=0))) == binding.EINVAL
+    assert f(*args(desc(Q=257))) == binding.EINVAL          # more new positions than the cache has rows
+    assert f(*args(desc(nq=28, nkv=3))) == binding.EINVAL   # query heads must divide over the KV heads
+    assert f(*args(desc(window=-1))) == binding.EINVAL
+    assert f(*args(desc(d=96))) in (binding.EINVAL, binding.EUNSUPPORTED)
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
