@@ -55,6 +55,16 @@ What it leaves open, and the reading taken here:
       position.  Optionally (off by default) the leading image block attends
       within itself in both directions, as the Gemma 3 family's public
       description has it; the paper does not say.
+  R15 Rotary position ids of the prompt pass.  Section 2.2 puts the m image
+      features ahead of the text as ordinary positions; Section 5 ("Models")
+      names the Qwen2.5-VL targets, whose public description numbers an image
+      position by three ids (temporal, height, width) and gives each rotary
+      pair j one of them: with sections (s_t, s_h, s_w), s_t + s_h + s_w = d/2,
+      pairs [0, s_t) turn by the temporal id, the next s_h by the height id, the
+      last s_w by the width id, each by id * theta^(-2j/d) with j the pair's own
+      index.  Text positions carry three equal ids, which is the one-id rotation
+      of R8.  The paper itself does not describe this; the position ids are an
+      input either way (R10).
 
 Pins (tests/test_oracle_*.py): brute-force attention loops, closed forms for
 constant keys / values, causality and grouped-head invariants, equivalence of
@@ -124,6 +134,60 @@ def rope(x, pos, theta):
     c, s = np.cos(ang), np.sin(ang)
     x1, x2 = x[..., :half], x[..., half:]
     return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def rope_multi(x, pos3, sections, theta):
+    """Rotary embedding with three position ids per row (R15).
+
+    x: [B, Q, heads, d]; pos3: [3, B, Q] (temporal, height, width ids); sections: three pair counts summing to
+    d/2.  Pair j = (j, j + d/2) turns by pos3[c(j)] * theta^(-2j/d), c(j) = the section j falls in."""
+    x = np.asarray(x, dtype=np.float64)
+    pos3 = np.asarray(pos3, dtype=np.float64)
+    d = x.shape[-1]
+    half = d // 2
+    st, sh, sw = (int(v) for v in sections)
+    if st + sh + sw != half or min(st, sh, sw) < 0:
+        raise ValueError("sections must be non-negative and sum to d/2")
+    comp = np.array([0] * st + [1] * sh + [2] * sw)                   # component of each pair
+    j = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * j / d)
+    ids = np.moveaxis(pos3, 0, -1)[..., comp]                          # [B, Q, half]: the id each pair turns by
+    ang = (ids * inv_freq)[:, :, None, :]                              # [B, Q, 1, half]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def rope_append(qkv, pos, kv_len, n_new, k_cache, v_cache, n_q, n_kv, d, theta, dtype, sections=None,
+                q_norm=None, k_norm=None, eps=1e-6):
+    """Prompt-pass step between the q/k/v projection and the attention (Section 2.2; R14, R15): split the projected
+    rows into heads, optionally normalise query and key heads (R13), rotate queries and keys by their position ids,
+    and write keys and values of the first n_new[b] rows of sequence b into the caches at rows kv_len[b] + i.
+
+    qkv: [B, L, (n_q + 2 n_kv) d] (query heads, key heads, value heads); pos: [B, L], or [3, B, L] with sections.
+    Returns (q [B, L, n_q, d] on the storage grid -- rows at and past n_new[b] are zero --, k_cache, v_cache)."""
+    qkv = np.asarray(qkv, dtype=np.float64)
+    B, L, _ = qkv.shape
+    k_cache = np.array(k_cache, dtype=np.float64)
+    v_cache = np.array(v_cache, dtype=np.float64)
+    q = qkv[..., :n_q * d].reshape(B, L, n_q, d)
+    k = qkv[..., n_q * d:(n_q + n_kv) * d].reshape(B, L, n_kv, d)
+    v = qkv[..., (n_q + n_kv) * d:].reshape(B, L, n_kv, d)
+    if q_norm is not None:
+        q = rmsnorm(q, q_norm, eps)
+    if k_norm is not None:
+        k = rmsnorm(k, k_norm, eps)
+    if sections is None:
+        q, k = rope(q, pos, theta), rope(k, pos, theta)
+    else:
+        q, k = rope_multi(q, pos, sections, theta), rope_multi(k, pos, sections, theta)
+    q_out = np.zeros((B, L, n_q, d))
+    for b in range(B):
+        L0, n = int(kv_len[b]), int(n_new[b])
+        q_out[b, :n] = _store(q[b, :n], dtype)
+        k_cache[b, :, L0:L0 + n] = _store(k[b, :n].transpose(1, 0, 2), dtype)
+        v_cache[b, :, L0:L0 + n] = _store(v[b, :n].transpose(1, 0, 2), dtype)
+    return q_out, k_cache, v_cache
 
 
 def silu(x):

@@ -171,6 +171,106 @@ def test_rope_explicit_pair_rotation():
     np.testing.assert_allclose(y, want, rtol=1e-13)
 
 
+def test_rope_multi_with_equal_ids_is_the_one_id_rotation():
+    """Text positions carry three equal ids: every section turns by the same position."""
+    rng = np.random.default_rng(40)
+    x = rng.standard_normal((2, 5, 3, 16))
+    pos = rng.integers(0, 5000, (2, 5))
+    for sections in ([8, 0, 0], [2, 3, 3], [0, 4, 4], [1, 1, 6]):
+        np.testing.assert_allclose(O.rope_multi(x, np.stack([pos, pos, pos]), sections, 1e6), O.rope(x, pos, 1e6), rtol=1e-13)
+
+
+def test_rope_multi_explicit_rotation_by_section():
+    """d = 8, theta = 10^4: pair frequencies 1, 0.1, 0.01, 0.001.  Sections (1, 2, 1): pair 0 turns by the temporal
+    id, pairs 1 and 2 by the height id, pair 3 by the width id -- each at its OWN frequency."""
+    x = np.arange(1.0, 9.0).reshape(1, 1, 1, 8)
+    t, h, w = 2, 3, 5
+    y = O.rope_multi(x, np.array([[[t]], [[h]], [[w]]]), [1, 2, 1], 1e4)[0, 0, 0]
+    ang = [t * 1.0, h * 0.1, h * 0.01, w * 0.001]
+    want = [x[0, 0, 0, j] * math.cos(ang[j]) - x[0, 0, 0, j + 4] * math.sin(ang[j]) for j in range(4)] + \
+           [x[0, 0, 0, j + 4] * math.cos(ang[j]) + x[0, 0, 0, j] * math.sin(ang[j]) for j in range(4)]
+    np.testing.assert_allclose(y, want, rtol=1e-12)
+
+
+def test_rope_multi_each_id_moves_only_its_own_section():
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((1, 1, 2, 32))
+    sections = [4, 6, 6]
+    base = np.array([[[7]], [[11]], [[13]]])
+    y0 = O.rope_multi(x, base, sections, 1e4)
+    bounds = [(0, 4), (4, 10), (10, 16)]
+    for c in range(3):
+        p = base.copy(); p[c] += 100
+        moved = np.abs(O.rope_multi(x, p, sections, 1e4) - y0).max(axis=(0, 1, 2))       # per feature
+        pairs = np.maximum(moved[:16], moved[16:])
+        lo, hi = bounds[c]
+        assert np.all(pairs[lo:hi] > 1e-6) and np.all(np.delete(pairs, np.arange(lo, hi)) == 0)
+    with pytest.raises(ValueError):
+        O.rope_multi(x, base, [4, 6, 5], 1e4)
+
+
+def test_rope_append_by_loops():
+    """The prompt-pass step between projection and attention, against per-element loops: head split, rotation of
+    queries and keys, rows [kv_len, kv_len + n_new) of the caches written, everything else untouched."""
+    rng = np.random.default_rng(42)
+    B, L, nq, nkv, d, lmax = 2, 5, 4, 2, 8, 16
+    qkv = rng.standard_normal((B, L, (nq + 2 * nkv) * d))
+    pos = rng.integers(0, 50, (B, L))
+    kv_len, n_new = [3, 0], [5, 2]
+    k0, v0 = rng.standard_normal((B, nkv, lmax, d)), rng.standard_normal((B, nkv, lmax, d))
+    q, k1, v1 = O.rope_append(qkv, pos, kv_len, n_new, k0, v0, nq, nkv, d, 1e4, "f32")
+    f32 = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)          # the fp32 storage grid
+    half = d // 2
+    def turn(vec, p):
+        out = np.empty(d)
+        for j in range(half):
+            a = p * 1e4 ** (-2.0 * j / d)
+            out[j] = vec[j] * math.cos(a) - vec[j + half] * math.sin(a)
+            out[j + half] = vec[j + half] * math.cos(a) + vec[j] * math.sin(a)
+        return out
+    kw, vw = k0.copy(), v0.copy()
+    for b in range(B):
+        for i in range(L):
+            row = qkv[b, i]
+            for h in range(nq):
+                want = turn(row[h * d:(h + 1) * d], pos[b, i]) if i < n_new[b] else np.zeros(d)
+                np.testing.assert_allclose(q[b, i, h], f32(want), rtol=1e-15, atol=0)
+            if i < n_new[b]:
+                for g in range(nkv):
+                    kw[b, g, kv_len[b] + i] = turn(row[(nq + g) * d:(nq + g + 1) * d], pos[b, i])
+                    vw[b, g, kv_len[b] + i] = row[(nq + nkv + g) * d:(nq + nkv + g + 1) * d]
+    written = np.zeros_like(k0, dtype=bool)
+    for b in range(B):
+        written[b, :, kv_len[b]:kv_len[b] + n_new[b]] = True
+    np.testing.assert_allclose(k1, np.where(written, f32(kw), kw), rtol=1e-15, atol=0)
+    np.testing.assert_allclose(v1, np.where(written, f32(vw), vw), rtol=0, atol=0)
+    # head norms come before the rotation, storage rounding after it
+    gq, gk = rng.standard_normal(d), rng.standard_normal(d)
+    q2, k2, _ = O.rope_append(qkv, pos, kv_len, n_new, k0, v0, nq, nkv, d, 1e4, "bf16", q_norm=gq, k_norm=gk, eps=1e-6)
+    hq = qkv[0, 1, d:2 * d]
+    want = O.round_bf16(turn(hq * gq / math.sqrt(np.mean(hq ** 2) + 1e-6), pos[0, 1]))
+    np.testing.assert_allclose(q2[0, 1, 1], want, rtol=0, atol=0)
+    hk = qkv[0, 1, (nq + 1) * d:(nq + 2) * d]
+    want = O.round_bf16(turn(hk * gk / math.sqrt(np.mean(hk ** 2) + 1e-6), pos[0, 1]))
+    np.testing.assert_allclose(k2[0, 1, kv_len[0] + 1], want, rtol=0, atol=0)
+
+
+def test_rope_append_feeds_prefill_attention_like_the_layer_does():
+    """Projection rows -> rope_append -> prefill_attention gives what verify_layer's own attention block gives on
+    the same rows (same cache, same positions): the two paths through the checker agree."""
+    rng = np.random.default_rng(43)
+    s = synth.TINY
+    B, Q = 2, 4
+    nq, nkv, d = s.n_q_heads, s.n_kv_heads, s.head_dim
+    kv = synth.kv_cache(s, B, Q, [9, 20], [4, 6], 43, junk_tail=False)
+    qkv = rng.standard_normal((B, Q, (nq + 2 * nkv) * d))
+    pos = synth.positions(kv.kv_len, kv.n_img, Q)
+    q, k1, v1 = O.rope_append(qkv, pos, kv.kv_len, [Q, Q], kv.k, kv.v, nq, nkv, d, s.rope_theta, "f32")
+    got = O.prefill_attention(q, k1, v1, kv.kv_len, [Q, Q])
+    qh = O.rope(qkv[..., :nq * d].reshape(B, Q, nq, d), pos, s.rope_theta)
+    np.testing.assert_allclose(got, O.attention(qh, k1, v1, kv.kv_len), rtol=1e-5, atol=1e-6)   # q goes through fp32 storage
+
+
 # ---------------------------------------------------------------------------
 # norm, activations, projections, storage rounding
 # ---------------------------------------------------------------------------
