@@ -153,6 +153,36 @@ int massv_prefill_attention(const massv_attn_desc* desc, const void* q,
                             const int32_t* kv_len, const int32_t* n_new, const int32_t* n_bidir,
                             void* out, void* stream);
 
+/* ------------------------------------------------------------------------- */
+/* rope_append: the step of the prompt pass between the q/k/v projection and   */
+/* prefill_attention (Section 2.2: image features, then text, enter the        */
+/* sequence as positions).  The projected rows are split into heads, query and */
+/* key heads optionally normalised (q_norm, k_norm [d], may be NULL; as in the */
+/* layer), queries and keys rotated by their position ids in the half-split    */
+/* pairing (j, j + d/2), and the keys and values of the first n_new[b] rows of */
+/* sequence b written into the caches at rows kv_len[b] + i.                   */
+/* Position ids: n_pos = 1, pos [B][L_q]: pair j turns by pos * theta^(-2j/d). */
+/* n_pos = 3, pos [3][B][L_q] (temporal, height, width ids, the numbering the  */
+/* Qwen2.5-VL targets of Section 5 give image positions; text positions carry  */
+/* three equal ids) and sections = three HOST int32 pair counts summing to     */
+/* d/2: pairs [0, s0) turn by the temporal id, the next s1 by the height id,   */
+/* the last s2 by the width id, each at its own frequency theta^(-2j/d).       */
+/*   desc: n_query = L_q rows per sequence in qkv, pos and q_out; heads,       */
+/*         head_dim, l_max, dtype as for verify_attention; no limit on L_q.    */
+/*   qkv   [B][L_q][(n_q + 2 n_kv) d] (dtype) in: query, key, value heads      */
+/*   q_out [B][L_q][n_q][d] (dtype) out; rows i >= n_new[b] are not written    */
+/*   k_cache, v_cache in/out, layouts above; rows outside                      */
+/*         [kv_len[b], kv_len[b] + n_new[b]) are not touched                   */
+/*   kv_len, n_new [B] int32 device; kv_len[b] + n_new[b] <= l_max is the      */
+/*         caller's duty (clamped).  No workspace.                             */
+/* MASSV_EINVAL: NULL pointers, n_pos not 1 or 3, sections missing, negative   */
+/* or not summing to d/2, theta <= 0.                                          */
+/* ------------------------------------------------------------------------- */
+int massv_rope_append(const massv_attn_desc* desc, const void* qkv, const int32_t* pos, int32_t n_pos,
+                      const int32_t* sections, float rope_theta, const void* q_norm, const void* k_norm,
+                      float norm_eps, const int32_t* kv_len, const int32_t* n_new, void* q_out,
+                      void* k_cache, void* v_cache, void* stream);
+
 /* Row-major [B][n_kv][L_max][d] values -> blocked value-cache layout. src and
  * dst must not overlap. */
 int massv_v_cache_pack(const void* src_row_major, void* dst_blocked,

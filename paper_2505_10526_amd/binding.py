@@ -31,7 +31,7 @@ EXPORTS = [
     "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
     "massv_linear_workspace", "massv_linear",
     "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
-    "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention",
+    "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention", "massv_rope_append",
     "massv_lm_head_accept_workspace", "massv_lm_head_accept",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR, K_PREFILL_ATTENTION = range(11)
@@ -85,6 +85,8 @@ def load():
     lib.massv_verify_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.massv_prefill_attention.restype = C.c_int
     lib.massv_prefill_attention.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.massv_rope_append.restype = C.c_int
+    lib.massv_rope_append.argtypes = [C.POINTER(AttnDesc), vp, vp, i32, C.POINTER(C.c_int32), f32, vp, vp, f32, vp, vp, vp, vp, vp, vp]
     lib.massv_v_cache_pack.restype = C.c_int
     lib.massv_v_cache_pack.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
     lib.massv_k_cache_pack.restype = C.c_int
@@ -250,6 +252,32 @@ def prefill_attention(q, k_cache, v_cache, kv_len, n_new, n_bidir=None, scale=0.
     _check(load().massv_prefill_attention(C.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
                                           _ptr(n_new), _ptr(n_bidir), _ptr(out), _stream()), "massv_prefill_attention")
     return out
+
+
+def rope_append(qkv, pos, kv_len, n_new, k_cache, v_cache, n_q, rope_theta, sections=None, q_norm=None, k_norm=None,
+                norm_eps=1e-6, q_out=None):
+    """qkv [B,L_q,(n_q+2n_kv)d]; pos int32 [B,L_q], or [3,B,L_q] with `sections` (three pair counts, host ints);
+    caches as for verify_attention (written in place at rows kv_len[b] .. kv_len[b]+n_new[b]-1).
+    Returns q_out [B,L_q,n_q,d]; rows i >= n_new[b] are left as they were (zeros for a fresh `q_out`)."""
+    for t, n in ((qkv, "qkv"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _need(t, n, qkv.dtype)
+    for t, n in ((pos, "pos"), (kv_len, "kv_len"), (n_new, "n_new")):
+        _need(t, n, torch.int32)
+    B, Lq, width = qkv.shape
+    n_kv, l_max, d = k_cache.shape[1], k_cache.shape[2], k_cache.shape[3]
+    if width != (n_q + 2 * n_kv) * d:
+        raise ValueError("qkv width does not match the head counts")
+    n_pos = 1 if sections is None else 3
+    if tuple(pos.shape) != ((B, Lq) if n_pos == 1 else (3, B, Lq)):
+        raise ValueError("pos has the wrong shape")
+    sec = None if sections is None else (C.c_int32 * 3)(*[int(v) for v in sections])
+    desc = attn_desc(B, Lq, n_q, n_kv, d, l_max, dtype_code(qkv), 0.0, 0)
+    if q_out is None:
+        q_out = torch.zeros((B, Lq, n_q, d), dtype=qkv.dtype, device=qkv.device)
+    _check(load().massv_rope_append(C.byref(desc), _ptr(qkv), _ptr(pos), n_pos, sec, float(rope_theta), _ptr(q_norm),
+                                    _ptr(k_norm), float(norm_eps), _ptr(kv_len), _ptr(n_new), _ptr(q_out), _ptr(k_cache),
+                                    _ptr(v_cache), _stream()), "massv_rope_append")
+    return q_out
 
 
 # ---------------------------------------------------------------------------

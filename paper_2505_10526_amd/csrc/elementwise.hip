@@ -154,6 +154,64 @@ int launch_rope_append(const void* qkv, const int32_t* pos, const int32_t* kv_le
     return launch_status();
 }
 
+// Prompt pass (paper Section 2.2): the same rotation and append for a block of L_q new positions per sequence, of
+// which the first n_new[b] exist.  One, or three rotary position ids per row: with three (temporal, height, width,
+// the numbering the Qwen2.5-VL family gives image positions) pair j turns by the id of the section it falls in --
+// pairs [0, s_t) temporal, [s_t, s_th) height, the rest width -- at its own frequency theta^(-2j/d).
+// grid = (B * L_q, n_q + 2 n_kv); thread j < d/2 owns the pair (j, j + d/2).  bf16 keys go to the blocked cache.
+template <typename T>
+__global__ void rope_rows_kernel(const T* __restrict__ qkv, const int32_t* __restrict__ pos, int n_pos, size_t pos_stride,
+                                 int s_t, int s_th, const int32_t* __restrict__ kv_len, const int32_t* __restrict__ n_new,
+                                 T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                 const T* __restrict__ q_norm, const T* __restrict__ k_norm, float eps,
+                                 int Lq, int n_q, int n_kv, int d, int l_max, double log2_theta) {
+    const int m = blockIdx.x, head = blockIdx.y, j = threadIdx.x;
+    const int half = d / 2;
+    const bool live = j < half;
+    const int b = m / Lq, i = m % Lq;
+    int L0 = kv_len[b]; L0 = L0 < 0 ? 0 : L0;
+    int n = n_new[b]; n = n < 0 ? 0 : (n > Lq ? Lq : n);
+    if (L0 + n > l_max) n = l_max - L0 > 0 ? l_max - L0 : 0;
+    if (i >= n) return;                                  // uniform over the workgroup
+    const int width = (n_q + 2 * n_kv) * d;
+    const T* src = qkv + (size_t)m * width + (size_t)head * d;
+    float x1 = live ? ldf(src + j) : 0.f, x2 = live ? ldf(src + j + half) : 0.f;
+    const T* hn = head < n_q ? q_norm : head < n_q + n_kv ? k_norm : nullptr;
+    if (hn) {                                            // uniform over the workgroup: RMSNorm of the head
+        __shared__ float red[4];
+        const float ss = block_sum_256(x1 * x1 + x2 * x2, red);
+        const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+        if (live) { x1 *= rstd * ldf(hn + j); x2 *= rstd * ldf(hn + j + half); }
+    }
+    if (!live) return;
+    const int row = L0 + i;
+    if (head < n_q + n_kv) {
+        const int comp = n_pos == 1 ? 0 : (j < s_t ? 0 : j < s_th ? 1 : 2);
+        const double ang = (double)pos[(size_t)comp * pos_stride + m] * exp2(-2.0 * (double)j / (double)d * log2_theta);
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        const float y1 = (float)((double)x1 * cs - (double)x2 * sn);
+        const float y2 = (float)((double)x2 * cs + (double)x1 * sn);
+        if (head < n_q) {
+            T* dst = q_out + ((size_t)m * n_q + head) * d;
+            stf(dst + j, y1); stf(dst + j + half, y2);
+        } else {
+            const size_t bg = (size_t)b * n_kv + (head - n_q);
+            if constexpr (sizeof(T) == 2) {
+                stf(k_cache + k_cache_index(bg, l_max, d, row, j), y1);
+                stf(k_cache + k_cache_index(bg, l_max, d, row, j + half), y2);
+            } else {
+                T* dst = k_cache + (bg * l_max + row) * d;
+                stf(dst + j, y1); stf(dst + j + half, y2);
+            }
+        }
+    } else {
+        const size_t bg = (size_t)b * n_kv + (head - n_q - n_kv);
+        stf(v_cache + v_cache_index(bg, l_max, d, row, j), x1);
+        stf(v_cache + v_cache_index(bg, l_max, d, row, j + half), x2);
+    }
+}
+
 // bf16 path: the q/k/v projection leaves fp32 partial sums per K slab; this kernel sums them, adds the
 // bias, optionally normalises the query / key head, applies the rotary embedding and scatters q / k / v.
 // Grid (heads, rows): consecutive workgroups read adjacent pieces of one row of partial sums (with rows as the
@@ -402,6 +460,45 @@ void embed_tokens_kernel(const uint32_t* __restrict__ table, const int* __restri
 }  // namespace massv
 
 using namespace massv;
+
+extern "C" int massv_rope_append(const massv_attn_desc* desc, const void* qkv, const int32_t* pos, int32_t n_pos,
+                                 const int32_t* sections, float rope_theta, const void* q_norm, const void* k_norm,
+                                 float norm_eps, const int32_t* kv_len, const int32_t* n_new, void* q_out,
+                                 void* k_cache, void* v_cache, void* stream) {
+    if (!desc) return MASSV_EINVAL;
+    // the descriptor rules of verify_attention, except that the row count per KV head is not limited
+    massv_attn_desc one = *desc;
+    one.n_query = 1;
+    const int rc = check_attn_desc(&one);
+    if (rc != MASSV_OK) return rc;
+    if (desc->n_query < 1 || desc->n_query > desc->l_max) return MASSV_EINVAL;
+    if (!qkv || !pos || !kv_len || !n_new || !q_out || !k_cache || !v_cache) return MASSV_EINVAL;
+    if (!(rope_theta > 0.f) || isinf(rope_theta) || !(norm_eps >= 0.f)) return MASSV_EINVAL;
+    if (n_pos != 1 && n_pos != 3) return MASSV_EINVAL;
+    int s_t = 0, s_th = 0;
+    if (n_pos == 3) {
+        if (!sections) return MASSV_EINVAL;
+        if (sections[0] < 0 || sections[1] < 0 || sections[2] < 0) return MASSV_EINVAL;
+        if ((int64_t)sections[0] + sections[1] + sections[2] != desc->head_dim / 2) return MASSV_EINVAL;
+        s_t = sections[0]; s_th = sections[0] + sections[1];
+    }
+    const massv_attn_desc& a = *desc;
+    if (a.head_dim > 512) return MASSV_EUNSUPPORTED;
+    const int64_t M = (int64_t)a.batch * a.n_query;
+    if (M > 0x7fffffff || a.n_q_heads + 2 * a.n_kv_heads > 65535) return MASSV_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)M, a.n_q_heads + 2 * a.n_kv_heads), block(a.head_dim / 2 < 64 ? 64 : a.head_dim / 2);
+    const double l2t = log2((double)rope_theta);
+    if (a.dtype == MASSV_F32)
+        hipLaunchKernelGGL(rope_rows_kernel<float>, grid, block, 0, st, (const float*)qkv, pos, n_pos, (size_t)M, s_t, s_th,
+                           kv_len, n_new, (float*)q_out, (float*)k_cache, (float*)v_cache, (const float*)q_norm,
+                           (const float*)k_norm, norm_eps, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+    else
+        hipLaunchKernelGGL(rope_rows_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)qkv, pos, n_pos, (size_t)M, s_t, s_th,
+                           kv_len, n_new, (bf16_t*)q_out, (bf16_t*)k_cache, (bf16_t*)v_cache, (const bf16_t*)q_norm,
+                           (const bf16_t*)k_norm, norm_eps, a.n_query, a.n_q_heads, a.n_kv_heads, a.head_dim, a.l_max, l2t);
+    return launch_status();
+}
 
 extern "C" int massv_embed_tokens(const void* table, const int32_t* tokens, void* x,
                                   int32_t M, int32_t H, int32_t V, int32_t dtype, void* stream) {

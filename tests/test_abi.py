@@ -271,6 +271,28 @@ def test_prefill_attention_argument_checks(lib):
     assert f(*args(desc(d=96))) in (binding.EINVAL, binding.EUNSUPPORTED)
 
 
+def test_rope_append_argument_checks(lib):
+    f = lib.massv_rope_append
+    def desc(**kw):
+        return binding.AttnDesc(kw.get("B", 2), kw.get("Q", 64), 28, 4, kw.get("d", 128), kw.get("lmax", 256), 0.0,
+                                kw.get("dt", binding.BF16), 0)
+    sec = lambda *v: (C.c_int32 * 3)(*v)
+    args = lambda d, **kw: [C.byref(d) if d is not None else None, kw.get("qkv", FAKE), kw.get("pos", FAKE), kw.get("n_pos", 1),
+                            kw.get("sec", None), kw.get("theta", 1e6), None, None, 1e-6, kw.get("kv", FAKE), kw.get("nn", FAKE),
+                            kw.get("q", FAKE), kw.get("k", FAKE), kw.get("v", FAKE), None]
+    assert f(*args(None)) == binding.EINVAL
+    for name in ("qkv", "pos", "kv", "nn", "q", "k", "v"):
+        assert f(*args(desc(), **{name: None})) == binding.EINVAL
+    assert f(*args(desc(Q=0))) == binding.EINVAL
+    assert f(*args(desc(Q=257))) == binding.EINVAL
+    assert f(*args(desc(), theta=0.0)) == binding.EINVAL
+    assert f(*args(desc(), n_pos=2)) == binding.EINVAL
+    assert f(*args(desc(), n_pos=3)) == binding.EINVAL                       # three ids need the sections
+    assert f(*args(desc(), n_pos=3, sec=sec(16, 24, 23))) == binding.EINVAL   # must sum to d/2
+    assert f(*args(desc(), n_pos=3, sec=sec(70, -6, 0))) == binding.EINVAL
+    assert f(*args(desc(d=96))) == binding.EUNSUPPORTED
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
