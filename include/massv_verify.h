@@ -446,6 +446,23 @@ size_t massv_linear_workspace(int32_t M, int32_t N, int32_t K, int32_t dtype);
 int massv_linear(const void* x, const void* w, const void* bias, void* y, int32_t M, int32_t N, int32_t K,
                  int32_t act, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same with two optional row-major [M][N] operands applied after the activation, in this order:
+ *   Y = act(X W^T + bias) * mul + add
+ * mul (or NULL): e.g. the up projection's rows, for the gated MLP act(gate(x)) * up(x); add (or NULL): e.g. the
+ * residual stream.  add may be y itself (each element is read before it is written); mul and x must not overlap y. */
+int massv_linear_ex(const void* x, const void* w, const void* bias, const void* mul, const void* add, void* y,
+                    int32_t M, int32_t N, int32_t K, int32_t act, int32_t dtype, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------- */
+/* rmsnorm: y[m, :] = x[m, :] * gain / sqrt(mean(x[m, :]^2) + eps) for any     */
+/* number of rows (the norm of a prompt pass; inside the verify step the norms */
+/* are fused into the neighbouring kernels).  x, y [M][H] row-major, gain [H], */
+/* all of `dtype`, device; y must not overlap x.  Sums in fp32.                */
+/* ------------------------------------------------------------------------- */
+int massv_rmsnorm(const void* x, const void* gain, void* y, int32_t M, int32_t H, float eps, int32_t dtype,
+                  void* stream);
+
 /* ------------------------------------------------------------------------- */
 /* Timing hook (diagnostic; for callers that want one kernel's duration        */
 /* without a profiler).  Arms a one-shot request on the CALLING THREAD: the    */

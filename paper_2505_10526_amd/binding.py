@@ -31,7 +31,7 @@ EXPORTS = [
     "massv_spec_tvd_workspace", "massv_spec_tvd", "massv_embed_tokens", "massv_commit_tokens",
     "massv_linear_workspace", "massv_linear",
     "massv_lm_head_greedy_accept_workspace", "massv_lm_head_greedy_accept",
-    "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention", "massv_rope_append",
+    "massv_spec_accept_static_limit", "massv_spec_accept_static", "massv_prefill_attention", "massv_rope_append", "massv_linear_ex", "massv_rmsnorm",
     "massv_lm_head_accept_workspace", "massv_lm_head_accept",
 ]
 K_QKV, K_ATTENTION, K_ATTN_COMBINE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_ACCEPT_STATS, K_RESIDUAL_MASS, K_LINEAR, K_PREFILL_ATTENTION = range(11)
@@ -124,6 +124,10 @@ def load():
     lib.massv_linear_workspace.argtypes = [i32, i32, i32, i32]
     lib.massv_linear.restype = C.c_int
     lib.massv_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.massv_linear_ex.restype = C.c_int
+    lib.massv_linear_ex.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.massv_rmsnorm.restype = C.c_int
+    lib.massv_rmsnorm.argtypes = [vp, vp, vp, i32, i32, f32, i32, vp]
     lib.massv_lm_head_greedy_accept_workspace.restype = sz
     lib.massv_lm_head_greedy_accept_workspace.argtypes = [i32, i32, i32, i32, i32]
     lib.massv_lm_head_greedy_accept.restype = C.c_int
@@ -532,23 +536,44 @@ def spec_tvd(target_logits, draft_logits, temperature, tvd=None, ws=None):
     return tvd
 
 
-def linear(x, w_packed, bias=None, act=LIN_NONE, out=None, ws=None):
-    """x [M,K] row-major; w_packed [N,K] in streaming layout (weight_pack); bias [N] or None -> y [M,N]."""
+def linear(x, w_packed, bias=None, act=LIN_NONE, out=None, ws=None, mul=None, add=None):
+    """x [M,K] row-major; w_packed [N,K] in streaming layout (weight_pack); bias [N] or None -> y [M,N]
+    = act(x w^T + bias) * mul + add, with mul / add [M,N] row-major or None (`add` may be `out`)."""
     lib = load()
     _need(x, "x")
     _need(w_packed, "w", x.dtype)
-    if bias is not None:
-        _need(bias, "bias", x.dtype)
     M, K = x.shape
     N = w_packed.shape[0]
+    for t, n in ((bias, "bias"), (mul, "mul"), (add, "add")):
+        if t is not None:
+            _need(t, n, x.dtype)
+            if n != "bias" and tuple(t.shape) != (M, N):
+                raise ValueError(f"{n} must be [M, N]")
     if out is None:
         out = torch.empty((M, N), dtype=x.dtype, device=x.device)
     else:
         _need(out, "out", x.dtype)
     if ws is None:
         ws = workspace(lib.massv_linear_workspace(M, N, K, dtype_code(x)), x.device)
-    _check(lib.massv_linear(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(out), M, N, K, int(act), dtype_code(x),
-                            _ptr(ws), ws.numel(), _stream()), "massv_linear")
+    if mul is None and add is None:
+        _check(lib.massv_linear(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(out), M, N, K, int(act), dtype_code(x),
+                                _ptr(ws), ws.numel(), _stream()), "massv_linear")
+    else:
+        _check(lib.massv_linear_ex(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(mul), _ptr(add), _ptr(out), M, N, K, int(act),
+                                   dtype_code(x), _ptr(ws), ws.numel(), _stream()), "massv_linear_ex")
+    return out
+
+
+def rmsnorm(x, gain, eps=1e-6, out=None):
+    """x [M,H] row-major, gain [H] -> y [M,H] = x * gain / sqrt(mean(x^2) + eps), any number of rows."""
+    _need(x, "x")
+    _need(gain, "gain", x.dtype)
+    M, H = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    else:
+        _need(out, "out", x.dtype)
+    _check(load().massv_rmsnorm(_ptr(x), _ptr(gain), _ptr(out), M, H, float(eps), dtype_code(x), _stream()), "massv_rmsnorm")
     return out
 
 

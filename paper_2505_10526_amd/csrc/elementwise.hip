@@ -500,6 +500,18 @@ extern "C" int massv_rope_append(const massv_attn_desc* desc, const void* qkv, c
     return launch_status();
 }
 
+extern "C" int massv_rmsnorm(const void* x, const void* gain, void* y, int32_t M, int32_t H, float eps, int32_t dtype,
+                             void* stream) {
+    if (!x || !gain || !y || M < 1 || H < 1 || !(eps >= 0.f)) return MASSV_EINVAL;
+    if (dtype != MASSV_F32 && dtype != MASSV_BF16) return MASSV_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == MASSV_F32)
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)x, (const float*)gain, (float*)y, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)gain, (bf16_t*)y, H, eps);
+    return launch_status();
+}
+
 extern "C" int massv_embed_tokens(const void* table, const int32_t* tokens, void* x,
                                   int32_t M, int32_t H, int32_t V, int32_t dtype, void* stream) {
     if (!table || !tokens || !x || M < 1 || H < 1 || V < 1) return MASSV_EINVAL;

@@ -54,7 +54,8 @@ __global__ void linear_pack_kernel(const bf16_t* __restrict__ src, bf16_t* __res
 template <int ACT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64)
 void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict__ wpk, const bf16_t* __restrict__ bias,
-                        bf16_t* __restrict__ y, int M, int N, int K, int tiles_m, int tiles_n) {
+                        const bf16_t* __restrict__ mul, const bf16_t* add, bf16_t* y,
+                        int M, int N, int K, int tiles_m, int tiles_n) {
     constexpr int FI = WAVES == 4 ? 4 : 2;        // 32-feature fragments per wave
     constexpr int FJ = 4;                         // 32-row fragments per wave
     constexpr int NMF = FI * FJ, NF = FI + FJ;    // matrix instructions and fragment loads per 16-wide quarter-step
@@ -204,9 +205,21 @@ void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict
 #pragma unroll
                     for (int r = 0; r < 4; ++r) v[r] += (float)bv[r];
                 }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = linear_act<ACT>(v[r]);
+                if (mul) {                               // e.g. the up projection's rows: act(gate) * up
+                    const bf16x4 mv = *reinterpret_cast<const bf16x4*>(mul + (size_t)m * N + n);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] *= (float)mv[r];
+                }
+                if (add) {                               // e.g. the residual stream (may be y itself: read before written)
+                    const bf16x4 av = *reinterpret_cast<const bf16x4*>(add + (size_t)m * N + n);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] += (float)av[r];
+                }
                 bf16x4 o;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (bf16_t)linear_act<ACT>(v[r]);
+                for (int r = 0; r < 4; ++r) o[r] = (bf16_t)v[r];
                 *reinterpret_cast<bf16x4*>(y + (size_t)m * N + n) = o;
             }
     }
@@ -231,8 +244,9 @@ extern "C" size_t massv_linear_workspace(int32_t M, int32_t N, int32_t K, int32_
     return align_up(packed_elems(M, K) * sizeof(bf16_t), 256);
 }
 
-extern "C" int massv_linear(const void* x, const void* w, const void* bias, void* y, int32_t M, int32_t N, int32_t K,
-                            int32_t act, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" int massv_linear_ex(const void* x, const void* w, const void* bias, const void* mul, const void* add, void* y,
+                               int32_t M, int32_t N, int32_t K, int32_t act, int32_t dtype, void* workspace,
+                               size_t workspace_bytes, void* stream) {
     const int rc = check_linear(M, N, K, act, dtype);
     if (rc != MASSV_OK) return rc;
     if (!x || !w || !y) return MASSV_EINVAL;
@@ -258,19 +272,24 @@ extern "C" int massv_linear(const void* x, const void* w, const void* bias, void
     switch (act) {
         case MASSV_LIN_SILU:
             launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_SILU, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
-                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+                          (const bf16_t*)bias, (const bf16_t*)mul, (const bf16_t*)add, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         case MASSV_LIN_GELU_TANH:
             launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_TANH, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
-                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+                          (const bf16_t*)bias, (const bf16_t*)mul, (const bf16_t*)add, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         case MASSV_LIN_GELU_ERF:
             launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_GELU_ERF, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
-                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+                          (const bf16_t*)bias, (const bf16_t*)mul, (const bf16_t*)add, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
             break;
         default:
             launch_traced(MASSV_K_LINEAR, linear_tile_kernel<MASSV_LIN_NONE, kLinWaves>, grid, block, kLinLds, st, xp, (const bf16_t*)w,
-                          (const bf16_t*)bias, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
+                          (const bf16_t*)bias, (const bf16_t*)mul, (const bf16_t*)add, (bf16_t*)y, M, N, K, tiles_m, tiles_n);
     }
     return launch_status();
+}
+
+extern "C" int massv_linear(const void* x, const void* w, const void* bias, void* y, int32_t M, int32_t N, int32_t K,
+                            int32_t act, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return massv_linear_ex(x, w, bias, nullptr, nullptr, y, M, N, K, act, dtype, workspace, workspace_bytes, stream);
 }

@@ -186,6 +186,28 @@ def test_linear_argument_checks(lib):
     assert f(*ok(ws=None)) == binding.EWORKSPACE
 
 
+def test_linear_ex_and_rmsnorm_argument_checks(lib):
+    f = lib.massv_linear_ex
+    ws = lib.massv_linear_workspace(300, 272, 128, binding.BF16)
+    ok = lambda **kw: [kw.get("x", FAKE), kw.get("w", FAKE), None, kw.get("mul", FAKE), kw.get("add", None), kw.get("y", FAKE),
+                       kw.get("M", 300), kw.get("N", 272), kw.get("K", 128), kw.get("act", 1), binding.BF16, kw.get("ws", FAKE),
+                       kw.get("wsb", ws), None]
+    assert f(*ok(x=None)) == binding.EINVAL
+    assert f(*ok(y=None)) == binding.EINVAL
+    assert f(*ok(act=-1)) == binding.EINVAL
+    assert f(*ok(K=96)) == binding.EUNSUPPORTED
+    assert f(*ok(wsb=ws - 1)) == binding.EWORKSPACE
+    g = lib.massv_rmsnorm
+    okn = lambda **kw: [kw.get("x", FAKE), kw.get("g", FAKE), kw.get("y", FAKE), kw.get("M", 4), kw.get("H", 256),
+                        kw.get("eps", 1e-6), kw.get("dt", binding.BF16), None]
+    for name in ("x", "g", "y"):
+        assert g(*okn(**{name: None})) == binding.EINVAL
+    assert g(*okn(M=0)) == binding.EINVAL
+    assert g(*okn(H=0)) == binding.EINVAL
+    assert g(*okn(eps=-1.0)) == binding.EINVAL
+    assert g(*okn(dt=7)) == binding.EINVAL
+
+
 def test_lm_head_greedy_accept_argument_checks(lib):
     f = lib.massv_lm_head_greedy_accept
     ws = lib.massv_lm_head_greedy_accept_workspace(8, 5, 3584, 152064, binding.BF16)

@@ -86,3 +86,41 @@ def test_smallest_and_tile_edge_shapes(M, N, K):
     """One row / one feature tile / one k-step; sizes one short of, equal to and one past a 256-wide tile."""
     x, w, b = inputs(M, N, K, seed=100 + M + N + K)
     assert_close(run_gpu(x, w, b, binding.LIN_GELU_TANH), O.gelu_tanh(O.linear(x, w, b)), TOL, f"{M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("use_mul,use_add,act", [(True, False, binding.LIN_SILU), (False, True, binding.LIN_NONE),
+                                                 (True, True, binding.LIN_GELU_TANH)])
+def test_multiplier_and_addend_after_the_activation(use_mul, use_add, act):
+    """Y = act(X W^T + b) * mul + add: the gated MLP's act(gate) * up, and a projection added to the residual stream."""
+    M, N, K = 333, 528, 192
+    x, w, b = inputs(M, N, K, seed=31)
+    mul = synth.normal((M, N), 1.0, 31, 63, dtype="bf16") if use_mul else None
+    add = synth.normal((M, N), 2.0, 31, 64, dtype="bf16") if use_add else None
+    y = binding.linear(to_dev(x, "bf16"), binding.weight_pack(to_dev(w, "bf16")), to_dev(b, "bf16"), act,
+                       mul=None if mul is None else to_dev(mul, "bf16"), add=None if add is None else to_dev(add, "bf16"))
+    torch.cuda.synchronize()
+    ref = ACTS[act](O.linear(x, w, b))
+    if use_mul:
+        ref = ref * mul
+    if use_add:
+        ref = ref + add
+    assert_close(y.float().cpu().numpy(), ref, TOL, "fused epilogue")
+
+
+def test_addend_may_be_the_output_itself():
+    M, N, K = 260, 272, 128
+    x, w, _ = inputs(M, N, K, seed=32, bias=False)
+    h = synth.normal((M, N), 1.0, 32, 65, dtype="bf16")
+    hd = to_dev(h, "bf16")
+    binding.linear(to_dev(x, "bf16"), binding.weight_pack(to_dev(w, "bf16")), None, binding.LIN_NONE, out=hd, add=hd)
+    torch.cuda.synchronize()
+    assert_close(hd.float().cpu().numpy(), O.linear(x, w) + h, TOL, "residual add in place")
+
+
+def test_rmsnorm_rows():
+    for dtype, tol in (("bf16", 8e-3), ("f32", 2e-6)):
+        x = synth.normal((300, 1536), 1.0, 33, 66, dtype=dtype)
+        g = synth.normal((1536,), 0.1, 33, 67, dtype=dtype, mean=1.0)
+        y = binding.rmsnorm(to_dev(x, dtype), to_dev(g, dtype), 1e-6)
+        torch.cuda.synchronize()
+        assert_close(y.float().cpu().numpy(), O.rmsnorm(x, g, 1e-6), tol, f"rmsnorm {dtype}")
