@@ -123,6 +123,11 @@ void linear_tile_kernel(const bf16_t* __restrict__ xpk, const bf16_t* __restrict
         if (f < FI) w[f] = lds[slot][0][(2 * FI * wy + 2 * f) * 64 + frag_off + 32 * h];
         else x4[f - FI] = lds[slot][1][(8 * wx + 2 * (f - FI)) * 64 + frag_off + 32 * h];
     };
+    // Issued as assembly (see the file header), so the compiler's hazard tracking does not know it is a matrix
+    // instruction.  What it still sees is the data flow: the operands come out of LDS reads it waits for, successive
+    // updates of one accumulator are ordered by the in/out operand (the hardware interlocks dependent matrix
+    // instructions), and the one place where something else reads the accumulators -- the epilogue -- is behind the
+    // wait written out after the loop.
     auto mfma = [&](floatx16& c, bf16x8 a, bf16x8 b) {
         asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     };
