@@ -63,6 +63,8 @@ def parse():
     ap.add_argument("--temperature", type=float, default=None, help="override the workload's sampling temperature")
     ap.add_argument("--no-extra", action="store_true", help="skip the attention/accept bandwidth section")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU checker timing")
+    ap.add_argument("--only", default=None, choices=["linear_prefill", "prefill_attention"],
+                    help="run just this compute-bound extra and print its record (for profiler runs of that kernel)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, for scaling profiler byte counters)")
@@ -104,6 +106,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.only:
+        g0 = torch.Generator(device=dev)
+        g0.manual_seed(args.seed + 1)
+        fn = linear_prefill if args.only == "linear_prefill" else prefill_attention_bench
+        print(json.dumps({args.only: fn(torch, binding, synth, dev, g0)}))
+        return
     if args.workload == "sd_iteration":
         print(json.dumps(iteration_bench(torch, binding, synth, dev, args)))
         return
