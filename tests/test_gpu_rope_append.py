@@ -122,3 +122,25 @@ def test_feeds_prefill_attention():
     og = out.float().cpu().numpy()
     for b in range(B):
         assert_close(og[b, :n_new[b]], o_ref[b, :n_new[b]], 2e-2, f"attention output of sequence {b}")
+
+
+def test_rows_that_would_pass_the_end_of_the_cache_are_dropped():
+    """kv_len + n_new <= l_max is the caller's duty; a violation is clamped, never written past the cache."""
+    s = synth.QWEN7B
+    rng = np.random.default_rng(7)
+    B, Lq, l_max = 2, 48, 64
+    nq, nkv, d = s.n_q_heads, s.n_kv_heads, s.head_dim
+    qkv = to_dev(synth.bf16_representable(rng.standard_normal((B, Lq, (nq + 2 * nkv) * d))), "bf16")
+    pos = i32(np.tile(np.arange(Lq, dtype=np.int32), (B, 1)))
+    guard = 4 * l_max * d                                   # elements behind each cache that must stay as they are
+    kbuf = torch.full((B * nkv * l_max * d + guard,), 7.0, dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.full((B * nkv * l_max * d + guard,), 7.0, dtype=torch.bfloat16, device="cuda")
+    kd = kbuf[:B * nkv * l_max * d].view(B, nkv, l_max, d)
+    vd = vbuf[:B * nkv * l_max * d].view(B, nkv, l_max, d)
+    q = binding.rope_append(qkv, pos, i32([40, 64]), i32([Lq, Lq]), kd, vd, nq, s.rope_theta)
+    torch.cuda.synchronize()
+    assert torch.all(kbuf[B * nkv * l_max * d:] == 7.0) and torch.all(vbuf[B * nkv * l_max * d:] == 7.0)
+    kr = k_cache_to_rows(kd).float().cpu().numpy()
+    assert np.all(kr[0, :, :40] == 7.0) and np.all(kr[0, :, 40:] != 7.0)       # 24 rows fit, the rest are dropped
+    assert np.all(kr[1] == 7.0)                                              # a full cache takes nothing
+    assert q[0, :24].abs().sum() > 0 and not q[0, 24:].any() and not q[1].any()
