@@ -201,8 +201,8 @@ int massv_weight_pack(const void* src_row_major, void* dst, int32_t N, int32_t K
 
 /* ------------------------------------------------------------------------- */
 /* verify_layer: one pre-norm decoder layer of the parallel forward over the  */
-/* M = B*Q new positions ("one forward call" of Section 2.1; the paper does    */
-/* not spell the layer out -- this is the usual gated-MLP transformer block):  */
+/* M = B*Q new positions (the single forward pass of Section 2.1; the paper    */
+/* does not spell the layer out -- this is the usual gated-MLP block):         */
 /*   xn = rmsnorm(x, ln1);  q,k,v = xn Wq^T+bq, xn Wk^T+bk, xn Wv^T+bv         */
 /*   q,k = rope(q,k; pos);  cache rows L_b+i <- k,v;  a = attention(q, cache)  */
 /*   h = x + a Wo^T;  hn = rmsnorm(h, ln2)                                     */

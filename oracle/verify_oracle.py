@@ -36,7 +36,7 @@ What it leaves open, and the reading taken here:
   R7  Inverse CDF: ascending token id, smallest k with cumsum_k > u * total.
       total == 0 (p == q everywhere): draw from p_i instead.  If rounding lets no
       k cross, the largest index with positive mass.
-  R8  Layer internals (the paper only says "one forward call"): pre-norm decoder
+  R8  Layer internals (the paper only speaks of a single forward pass of the target): pre-norm decoder
       layer, RMSNorm y = x*g/sqrt(mean(x^2)+eps), grouped-query attention with
       head h reading KV head h // (n_q/n_kv), rotary embedding in the
       half-split pairing (j, j + d/2) with angle pos * theta^(-2j/d), gated MLP

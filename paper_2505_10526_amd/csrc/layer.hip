@@ -1,5 +1,5 @@
 // verify_layer and lm_head_logits: the parallel forward of the verify step
-// (paper Section 2.1, "one forward call") as a fixed sequence of kernel
+// (paper Section 2.1: the target scores all drafted positions in a single forward pass) as a fixed sequence of kernel
 // launches on the caller's stream.
 #include "kernels.h"
 

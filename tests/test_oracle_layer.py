@@ -111,7 +111,7 @@ def test_attention_is_causal():
 def test_attention_parallel_equals_sequential_decode():
     """Scoring all new positions in one pass equals one-query-at-a-time decoding
     with a growing cache (Section 2.1: the gamma+1 conditionals are computed in
-    parallel with one forward call)."""
+    parallel in a single forward pass of the target)."""
     q, k, v, kv_len = small_case(7)
     par = O.attention(q, k, v, kv_len)
     B, Q = q.shape[:2]
