@@ -413,6 +413,7 @@ GemmPlan gemm_plan(const GemmArgs& g) {
             groups = units < kCUs ? units : kCUs;
         }
         const int rounds = (groups + kCUs - 1) / kCUs;
+        if (rounds > 1 && rounds * kCUs <= T / ut) groups = rounds * kCUs;     // full rounds: the units are dealt evenly over them
         const double eff = (double)T / ((double)nt * rounds * kCUs);
         const double score = eff + 0.004 * nt;                 // near ties go to the larger tile count (less X traffic)
         if (score > best_score) { best_score = score; best.nt = nt; best.slabs = 1; best.groups = groups; }
